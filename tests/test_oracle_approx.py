@@ -1,0 +1,139 @@
+"""Pins for the oracle's selection step and Max Gradient Approximation (CPU only).
+
+Algorithm 1 is an algorithm, not a closed form, so it is pinned by reducing it to
+the (separately pinned) exact gradient: keeping one element per map turns the
+convolution into a collection of patches (Section 2.4), i.e.
+approx(X, dY) == exact(X, sparsify(dY)).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from tests.test_oracle_exact import SHAPES, mk, rand_inputs
+
+
+def sparsify(dY, idx, S):
+    """Per map keep only position idx, carrying the map's signed sum (Section 2.3)."""
+    N, K, Ho, Wo = dY.shape
+    out = np.zeros((N, K, Ho * Wo))
+    nn, kk = np.meshgrid(np.arange(N), np.arange(K), indexing="ij")
+    out[nn, kk, idx] = S
+    return out.reshape(N, K, Ho, Wo)
+
+
+# ---- selection -------------------------------------------------------------
+
+def test_select_matches_brute_force():
+    g = oracle.shape(5, 3, 9, 7, 4, stride=1, pad=1)
+    _, dY = rand_inputs(g, 21, np.float32)
+    idx, S = oracle.select(g, dY)
+    flat = np.abs(dY.astype(np.float64)).reshape(g.N, g.K, -1)
+    assert np.array_equal(idx, flat.argmax(axis=2))       # numpy returns the first maximum
+    np.testing.assert_allclose(S, dY.astype(np.float64).reshape(g.N, g.K, -1).sum(axis=2), atol=1e-12)
+
+
+def test_select_tie_rules():
+    g = oracle.shape(1, 1, 4, 4, 6, stride=1, pad=1)
+    dY = np.zeros((1, 6, 4, 4), np.float32)
+    dY[0, 0].flat[[3, 9]] = [2.0, -2.0]          # +v before -v: equal magnitude, lowest index wins
+    dY[0, 1].flat[[5, 7, 12]] = [-1.5, 1.5, 1.5]  # duplicate maxima, the first is negative
+    # map 2 stays all zero -> index 0, sum 0
+    dY[0, 3].flat[15] = 1e-30                    # maximum in the last position
+    dY[0, 4].flat[[0, 1]] = [0.0, -0.0]          # signed zeros are equal
+    dY[0, 5].flat[[2, 6, 10]] = [1.0, -3.0, 2.5]  # plain case, negative wins by magnitude
+    idx, S = oracle.select(g, dY)
+    assert idx[0].tolist() == [3, 5, 0, 15, 0, 6]
+    np.testing.assert_allclose(S[0], [0.0, 1.5, 0.0, 1e-30, 0.0, 0.5], rtol=1e-6)
+
+
+def test_select_on_bf16_maps_with_many_ties():
+    from paper_1908_05460_amd import inputs
+    g = oracle.shape(8, 1, 16, 16, 8, stride=1, pad=1)
+    rng = np.random.default_rng(3)
+    dY = (rng.integers(-3, 4, size=(8, 8, 16, 16)) * 0.25).astype(np.float32)  # few distinct values
+    bits = inputs.float32_to_bf16_bits(dY)
+    idx, S = oracle.select(g, bits)
+    flat = np.abs(dY).reshape(8, 8, -1)
+    assert np.array_equal(idx, flat.argmax(axis=2))
+    assert (flat == flat.max(axis=2, keepdims=True)).sum(axis=2).min() > 1   # ties really occur
+    np.testing.assert_array_equal(S, dY.astype(np.float64).reshape(8, 8, -1).sum(axis=2))
+
+
+def test_argmax_invariant_under_nonzero_scaling_of_dY():
+    g = mk(SHAPES[0])
+    _, dY = rand_inputs(g, 22)
+    i1, S1 = oracle.select(g, dY)
+    i2, S2 = oracle.select(g, -4.0 * dY)
+    assert np.array_equal(i1, i2)
+    np.testing.assert_allclose(S2, -4.0 * S1, rtol=1e-12)
+
+
+# ---- approximation ---------------------------------------------------------
+
+@pytest.mark.parametrize("st", SHAPES)
+def test_approx_equals_exact_of_sparsified_dY(st):
+    g = mk(st)
+    X, dY = rand_inputs(g, 31)
+    dW, idx, S = oracle.wgrad_approx(g, X, dY)
+    i2, S2 = oracle.select(g, dY)
+    assert np.array_equal(idx, i2) and np.array_equal(S, S2)
+    sp = sparsify(dY, idx, S)
+    assert np.count_nonzero(sp) <= g.N * g.K               # sparsity >= 1 - 1/(Ho*Wo), Section 2.3
+    np.testing.assert_allclose(dW, oracle.wgrad_exact(g, X, sp), rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("st", SHAPES)
+def test_approx_equals_exact_when_each_map_has_one_nonzero(st):
+    g = mk(st)
+    X, dY = rand_inputs(g, 32)
+    Ho, Wo = oracle.out_hw(g)
+    rng = np.random.default_rng(33)
+    pos = rng.integers(0, Ho * Wo, size=(g.N, g.K))
+    val = rng.standard_normal((g.N, g.K))
+    one = sparsify(dY, pos, val)
+    dW, idx, S = oracle.wgrad_approx(g, X, one)
+    assert np.array_equal(idx, pos)
+    np.testing.assert_allclose(dW, oracle.wgrad_exact(g, X, one), rtol=1e-12, atol=1e-12)
+
+
+def test_constant_input_without_padding_closed_form():
+    """X == x0 everywhere and pad = 0: every patch is x0, so for approx and exact alike
+    dW[k,c,r,s] = x0 * sum_n S[n,k]."""
+    g = oracle.shape(3, 2, 7, 7, 4, stride=2, pad=0)
+    _, dY = rand_inputs(g, 34)
+    X = np.full((3, 2, 7, 7), 1.75)
+    dW, _, S = oracle.wgrad_approx(g, X, dY)
+    want = 1.75 * S.sum(axis=0)
+    np.testing.assert_allclose(dW, np.broadcast_to(want[:, None, None, None], dW.shape), rtol=1e-12)
+    np.testing.assert_allclose(oracle.wgrad_exact(g, X, dY), dW, rtol=1e-10, atol=1e-12)
+
+
+def test_padding_taps_contribute_zero():
+    """Selected position in a corner with pad 1: the taps that fall outside X give 0,
+    the others read the input element the exact convolution would read."""
+    g = oracle.shape(1, 1, 4, 4, 1, stride=1, pad=1)
+    X = np.arange(1.0, 17.0).reshape(1, 1, 4, 4)
+    dY = np.zeros((1, 1, 4, 4)); dY[0, 0, 0, 0] = 2.0; dY[0, 0, 3, 3] = -0.5   # argmax at (0,0), sum 1.5
+    dW, idx, S = oracle.wgrad_approx(g, X, dY)
+    assert idx[0, 0] == 0 and S[0, 0] == 1.5
+    want = 1.5 * np.array([[0, 0, 0], [0, 1, 2], [0, 5, 6]], float)
+    assert np.array_equal(dW[0, 0], want)
+
+
+def test_linear_in_X_homogeneous_in_dY_and_power_of_two_scale_is_bit_exact():
+    g = mk(SHAPES[2])
+    X1, dY = rand_inputs(g, 35)
+    X2, _ = rand_inputs(g, 36)
+    f = lambda X, d, **kw: oracle.wgrad_approx(g, X, d, **kw)[0]
+    np.testing.assert_allclose(f(X1 + 2 * X2, dY), f(X1, dY) + 2 * f(X2, dY), atol=1e-11)
+    np.testing.assert_allclose(f(X1, -3 * dY), -3 * f(X1, dY), atol=1e-11)
+    assert np.array_equal(f(X1, dY, scale=2.0 ** -7), 2.0 ** -7 * f(X1, dY))
+    assert np.all(f(X1, np.zeros_like(dY)) == 0.0)
+
+
+def test_stride_and_padding_reading_on_a_resnet_downsampling_shape():
+    g = oracle.shape(2, 4, 8, 8, 5, stride=2, pad=1)
+    X, dY = rand_inputs(g, 37, np.float32)
+    dW, idx, S = oracle.wgrad_approx(g, X, dY)
+    np.testing.assert_allclose(dW, oracle.wgrad_exact(g, X.astype(np.float64),
+                                                      sparsify(dY, idx, S)), rtol=1e-12, atol=1e-12)
