@@ -1,0 +1,122 @@
+/*
+ * wgrad.h - C ABI of libwgrad: the filter (weight) gradient of a convolution
+ * layer on AMD MI355X (gfx950), exact and in the approximated forms of
+ * "Accelerated CNN Training Through Gradient Approximation" (arXiv 1908.05460).
+ *
+ * Tensors (Section 2.4 states the layer in NCHW; the paper's I, dO, df, C_i, C_o
+ * and filter size K are X, dY, dW, C, K and R x S here):
+ *   X   [N,C,H,W]      input activations saved by the forward pass, contiguous
+ *   dY  [N,K,Ho,Wo]    gradient w.r.t. the layer output, contiguous
+ *   dW  [K,C,R,S]      gradient w.r.t. the filters, contiguous, always float32
+ *   Ho = floor((H + 2*pad_h - R)/stride_h) + 1,  Wo likewise.
+ *
+ * Conventions for every entry point
+ *   - All tensor and workspace pointers are DEVICE pointers owned by the caller
+ *     (256-byte aligned workspace; tensors aligned to their element size; 16-byte
+ *     alignment enables the vector paths).  Descriptors and per-layer pointer
+ *     tables are HOST memory and are read before the call returns.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls only enqueue work; they never allocate, free or synchronise.
+ *   - dW is OVERWRITTEN, never accumulated into (Algorithm 1 starts from df = 0).
+ *   - Return value: WGRAD_OK (0) or a negative wgrad_status.  All validation is
+ *     done on the host before anything is launched, so on error nothing was
+ *     enqueued by that call.
+ *   - Thread-safe for calls that use distinct workspaces; calls sharing a
+ *     workspace must be ordered on one stream.
+ */
+#ifndef WGRAD_H
+#define WGRAD_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct {
+    int32_t N, C, H, W;          /* X  : [N,C,H,W]                                   */
+    int32_t K, R, S;             /* dW : [K,C,R,S]                                   */
+    int32_t stride_h, stride_w;  /* >= 1                                             */
+    int32_t pad_h, pad_w;        /* >= 0, zero padding                               */
+    int32_t dtype;               /* element type of X and dY: WGRAD_F32 or WGRAD_BF16 */
+} wgrad_conv_desc;
+
+enum { WGRAD_F32 = 0, WGRAD_BF16 = 1 };
+
+typedef enum { WGRAD_EXACT = 0, WGRAD_APPROX = 1, WGRAD_ZERO = 2, WGRAD_RANDOM = 3 } wgrad_method;
+
+typedef enum {
+    WGRAD_OK = 0,
+    WGRAD_INVALID_ARG = -1,         /* null pointer, non-positive size, empty output, bad dtype/method */
+    WGRAD_UNSUPPORTED = -2,         /* valid convolution this build has no kernel for                 */
+    WGRAD_WORKSPACE_TOO_SMALL = -3, /* ws_bytes < conv_wgrad_workspace_bytes(), or ws misaligned      */
+    WGRAD_LAUNCH_FAILED = -4        /* the HIP runtime refused a launch                               */
+} wgrad_status;
+
+/* Exact filter gradient (Section 2: the third convolution of a layer's
+ * forward-backward pass; Section 2.4: "convolve I with dO"):
+ *   dW[k,c,r,s] = sum_{n,h,w} dY[n,k,h,w] * X[n,c,h*stride_h + r - pad_h, w*stride_w + s - pad_w]
+ * with X read as zero outside its bounds.  fp32 accumulation for both dtypes.
+ * ws: device scratch of at least conv_wgrad_workspace_bytes(desc, WGRAD_EXACT). */
+int conv_wgrad_exact(const wgrad_conv_desc *desc, const void *X, const void *dY, float *dW,
+                     void *ws, size_t ws_bytes, void *stream);
+
+/* Max Gradient Approximation (Section 2.3 and Algorithm 1).  For every map
+ * dY[n,k,:,:] keep only the position p* = argmax |dY| (lowest flat index
+ * h*Wo + w among equal magnitudes), let it carry the map's signed sum S, and
+ * accumulate the input patch that position sees:
+ *   dW[k,c,r,s] = scale * sum_n S[n,k] * X[n,c,h* * stride_h + r - pad_h, w* * stride_w + s - pad_w]
+ * scale = 1 is Algorithm 1 as printed; the paper's runs use 1/128 (Section 2.3).
+ * idx_out, sum_out: optional device arrays of N*K elements (index n*K + k) that
+ * receive p* and S; either may be NULL.
+ * ws: at least conv_wgrad_workspace_bytes(desc, WGRAD_APPROX). */
+int conv_wgrad_approx(const wgrad_conv_desc *desc, const void *X, const void *dY, float *dW,
+                      float scale, int32_t *idx_out, float *sum_out,
+                      void *ws, size_t ws_bytes, void *stream);
+
+/* The two selection quantities of Algorithm 1 alone (its argmax and sum lines):
+ * idx[n*K + k] and sum[n*K + k] for every map of dY.  X is not read; only the
+ * output geometry of desc matters.  Needs no workspace. */
+int conv_wgrad_select(const wgrad_conv_desc *desc, const void *dY, int32_t *idx, float *sum,
+                      void *stream);
+
+/* Zero gradient (Section 2.1): dW = 0. */
+int conv_wgrad_zero(const wgrad_conv_desc *desc, float *dW, void *stream);
+
+/* Random gradient (Section 2.2): independent N(0, sigma) values (paper: 1/128).
+ * dW[i] is a pure function of (seed, offset + i): Philox4x32-10 with counter
+ * (lo32, hi32, 0, 0) of offset + i and key (lo32, hi32) of seed, then Box-Muller
+ * on the first two output words, u = ((word >> 8) + 0.5) / 2^24.  The caller
+ * advances offset by K*C*R*S per layer and batch so that every batch draws new
+ * numbers, as the method requires. */
+int conv_wgrad_random(const wgrad_conv_desc *desc, float *dW, float sigma,
+                      uint64_t seed, uint64_t offset, void *stream);
+
+/* Bytes of device scratch the given method needs for this layer (0 for
+ * WGRAD_ZERO and WGRAD_RANDOM).  Returns 0 for an invalid descriptor too; use a
+ * compute call to learn why a descriptor is rejected. */
+size_t conv_wgrad_workspace_bytes(const wgrad_conv_desc *desc, wgrad_method method);
+
+/* One batch of an approximation schedule (Section 2.5): layer i uses
+ * method[i] (a wgrad_method).  layers, X, dY, dW and method are host arrays of
+ * nlayers entries; X[i], dY[i], dW[i] are device pointers.  All layers are
+ * enqueued back to back on `stream` and share `ws`, which must hold the largest
+ * per-layer requirement (conv_wgrad_schedule_workspace_bytes).  A random layer i
+ * uses offset + (sum of K*C*R*S of the layers before it).  Validation of every
+ * layer happens before the first launch. */
+int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void *const *X,
+                            const void *const *dY, float *const *dW, const uint8_t *method,
+                            int32_t nlayers, float scale, float sigma, uint64_t seed,
+                            uint64_t offset, void *ws, size_t ws_bytes, void *stream);
+
+size_t conv_wgrad_schedule_workspace_bytes(const wgrad_conv_desc *layers, const uint8_t *method,
+                                           int32_t nlayers);
+
+/* Static, NUL-terminated description of a status code. */
+const char *conv_wgrad_status_string(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* WGRAD_H */

@@ -1,0 +1,165 @@
+// C ABI of libwgrad (declared in include/wgrad.h): argument validation and dispatch.
+// Everything here runs on the host; validation precedes the first launch.
+#include "common.hpp"
+
+using namespace wgrad;
+
+static int make_geometry(const wgrad_conv_desc *d, Geometry &g)
+{
+    if (!d) return WGRAD_INVALID_ARG;
+    if (d->N <= 0 || d->C <= 0 || d->H <= 0 || d->W <= 0 || d->K <= 0 || d->R <= 0 || d->S <= 0)
+        return WGRAD_INVALID_ARG;
+    if (d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0) return WGRAD_INVALID_ARG;
+    if (d->dtype != WGRAD_F32 && d->dtype != WGRAD_BF16) return WGRAD_INVALID_ARG;
+    if (d->H + 2 * (long)d->pad_h < d->R || d->W + 2 * (long)d->pad_w < d->S) return WGRAD_INVALID_ARG;  // empty output
+    g.N = d->N; g.C = d->C; g.H = d->H; g.W = d->W; g.K = d->K; g.R = d->R; g.S = d->S;
+    g.sh = d->stride_h; g.sw = d->stride_w; g.ph = d->pad_h; g.pw = d->pad_w;
+    g.Ho = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
+    g.Wo = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
+    g.bf16 = d->dtype == WGRAD_BF16;
+    // index arithmetic inside the kernels is 32-bit per tensor dimension product below
+    const long lim = 1l << 31;
+    if ((long)g.N * g.K >= lim || (long)g.Ho * g.Wo >= lim || g.dw_elems() >= lim || (long)g.H * g.W >= lim)
+        return WGRAD_UNSUPPORTED;
+    return WGRAD_OK;
+}
+
+static bool ws_ok(const void *ws, size_t have, size_t need)
+{
+    if (need == 0) return true;
+    return ws != nullptr && have >= need && ((uintptr_t)ws % kAlign) == 0;
+}
+
+extern "C" {
+
+int conv_wgrad_exact(const wgrad_conv_desc *desc, const void *X, const void *dY, float *dW,
+                     void *ws, size_t ws_bytes, void *stream)
+{
+    Geometry g;
+    int rc = make_geometry(desc, g);
+    if (rc != WGRAD_OK) return rc;
+    if (!X || !dY || !dW) return WGRAD_INVALID_ARG;
+    const ExactPlan pl = plan_exact(g);
+    if (!pl.ok) return WGRAD_UNSUPPORTED;
+    if (!ws_ok(ws, ws_bytes, pl.ws_bytes)) return WGRAD_WORKSPACE_TOO_SMALL;
+    return launch_exact(g, pl, X, dY, dW, ws, (hipStream_t)stream);
+}
+
+int conv_wgrad_approx(const wgrad_conv_desc *desc, const void *X, const void *dY, float *dW,
+                      float scale, int32_t *idx_out, float *sum_out,
+                      void *ws, size_t ws_bytes, void *stream)
+{
+    Geometry g;
+    int rc = make_geometry(desc, g);
+    if (rc != WGRAD_OK) return rc;
+    if (!X || !dY || !dW) return WGRAD_INVALID_ARG;
+    const ApproxPlan pl = plan_approx(g);
+    if (!ws_ok(ws, ws_bytes, pl.ws_bytes)) return WGRAD_WORKSPACE_TOO_SMALL;
+    return launch_approx(g, pl, X, dY, dW, scale, idx_out, sum_out, ws, (hipStream_t)stream);
+}
+
+int conv_wgrad_select(const wgrad_conv_desc *desc, const void *dY, int32_t *idx, float *sum, void *stream)
+{
+    Geometry g;
+    int rc = make_geometry(desc, g);
+    if (rc != WGRAD_OK) return rc;
+    if (!dY || !idx || !sum) return WGRAD_INVALID_ARG;
+    return launch_select(g, dY, idx, sum, (hipStream_t)stream);
+}
+
+int conv_wgrad_zero(const wgrad_conv_desc *desc, float *dW, void *stream)
+{
+    Geometry g;
+    int rc = make_geometry(desc, g);
+    if (rc != WGRAD_OK) return rc;
+    if (!dW) return WGRAD_INVALID_ARG;
+    return launch_zero(dW, g.dw_elems(), (hipStream_t)stream);
+}
+
+int conv_wgrad_random(const wgrad_conv_desc *desc, float *dW, float sigma, uint64_t seed,
+                      uint64_t offset, void *stream)
+{
+    Geometry g;
+    int rc = make_geometry(desc, g);
+    if (rc != WGRAD_OK) return rc;
+    if (!dW || !(sigma >= 0.0f)) return WGRAD_INVALID_ARG;
+    return launch_random(dW, g.dw_elems(), sigma, seed, offset, (hipStream_t)stream);
+}
+
+size_t conv_wgrad_workspace_bytes(const wgrad_conv_desc *desc, wgrad_method method)
+{
+    Geometry g;
+    if (make_geometry(desc, g) != WGRAD_OK) return 0;
+    if (method == WGRAD_EXACT) { const ExactPlan pl = plan_exact(g); return pl.ok ? pl.ws_bytes : 0; }
+    if (method == WGRAD_APPROX) return plan_approx(g).ws_bytes;
+    return 0;
+}
+
+size_t conv_wgrad_schedule_workspace_bytes(const wgrad_conv_desc *layers, const uint8_t *method, int32_t nlayers)
+{
+    if (!layers || !method || nlayers <= 0) return 0;
+    size_t need = 0;
+    for (int i = 0; i < nlayers; ++i) {
+        const size_t b = conv_wgrad_workspace_bytes(&layers[i], (wgrad_method)method[i]);
+        if (b > need) need = b;
+    }
+    return need;
+}
+
+int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void *const *X, const void *const *dY,
+                            float *const *dW, const uint8_t *method, int32_t nlayers, float scale,
+                            float sigma, uint64_t seed, uint64_t offset, void *ws, size_t ws_bytes,
+                            void *stream)
+{
+    if (!layers || !X || !dY || !dW || !method || nlayers <= 0) return WGRAD_INVALID_ARG;
+    // pass 1: validate every layer before anything is enqueued
+    for (int i = 0; i < nlayers; ++i) {
+        Geometry g;
+        int rc = make_geometry(&layers[i], g);
+        if (rc != WGRAD_OK) return rc;
+        if (method[i] > WGRAD_RANDOM) return WGRAD_INVALID_ARG;
+        if (!dW[i]) return WGRAD_INVALID_ARG;
+        if (method[i] == WGRAD_EXACT || method[i] == WGRAD_APPROX) {
+            if (!X[i] || !dY[i]) return WGRAD_INVALID_ARG;
+            size_t need;
+            if (method[i] == WGRAD_EXACT) {
+                const ExactPlan pl = plan_exact(g);
+                if (!pl.ok) return WGRAD_UNSUPPORTED;
+                need = pl.ws_bytes;
+            } else {
+                need = plan_approx(g).ws_bytes;
+            }
+            if (!ws_ok(ws, ws_bytes, need)) return WGRAD_WORKSPACE_TOO_SMALL;
+        } else if (method[i] == WGRAD_RANDOM && !(sigma >= 0.0f)) {
+            return WGRAD_INVALID_ARG;
+        }
+    }
+    // pass 2: enqueue back to back on the caller's stream
+    uint64_t off = offset;
+    for (int i = 0; i < nlayers; ++i) {
+        int rc = WGRAD_OK;
+        switch (method[i]) {
+            case WGRAD_EXACT: rc = conv_wgrad_exact(&layers[i], X[i], dY[i], dW[i], ws, ws_bytes, stream); break;
+            case WGRAD_APPROX: rc = conv_wgrad_approx(&layers[i], X[i], dY[i], dW[i], scale, nullptr, nullptr, ws, ws_bytes, stream); break;
+            case WGRAD_ZERO: rc = conv_wgrad_zero(&layers[i], dW[i], stream); break;
+            default: rc = conv_wgrad_random(&layers[i], dW[i], sigma, seed, off, stream); break;
+        }
+        if (rc != WGRAD_OK) return rc;
+        off += (uint64_t)layers[i].K * layers[i].C * layers[i].R * layers[i].S;
+    }
+    return WGRAD_OK;
+}
+
+const char *conv_wgrad_status_string(int status)
+{
+    switch (status) {
+        case WGRAD_OK: return "ok";
+        case WGRAD_INVALID_ARG: return "invalid argument (null pointer, non-positive size, empty output, bad dtype or method)";
+        case WGRAD_UNSUPPORTED: return "unsupported convolution (no kernel configuration fits it)";
+        case WGRAD_WORKSPACE_TOO_SMALL: return "workspace too small or not 256-byte aligned";
+        case WGRAD_LAUNCH_FAILED: return "the HIP runtime refused a kernel launch";
+        default: return "unknown status";
+    }
+}
+
+}  // extern "C"

@@ -1,0 +1,81 @@
+// Shared host/device declarations of libwgrad (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "wgrad.h"
+
+namespace wgrad {
+
+constexpr int kBlock = 256;          // threads per workgroup: 4 wavefronts of 64
+constexpr int kWave = 64;
+constexpr int kNumXCD = 8;           // MI355X: 8 accelerator dies, each with its own L2
+constexpr int kNumCU = 256;
+constexpr size_t kAlign = 256;       // workspace carve-out alignment
+
+// Division of a small unsigned number by a run-time constant: q = umulhi(n, m)
+// with m = floor(2^32/d) + 1 is exact while n*d < 2^32 (the host checks that
+// bound for every divisor it builds).
+struct FastDiv {
+    uint32_t d, m;
+    __host__ __device__ FastDiv() : d(1), m(0) {}
+    __host__ explicit FastDiv(uint32_t div) : d(div), m(div > 1 ? (uint32_t)((1ull << 32) / div) + 1u : 0u) {}
+    __device__ __forceinline__ uint32_t div(uint32_t n) const { return d == 1 ? n : __umulhi(n, m); }
+    __device__ __forceinline__ void divmod(uint32_t n, uint32_t &q, uint32_t &r) const {
+        q = div(n);
+        r = n - q * d;
+    }
+};
+
+struct Geometry {                    // validated convolution geometry
+    int N, C, H, W, K, R, S, sh, sw, ph, pw, Ho, Wo;
+    int bf16;                        // element type of X and dY
+    __host__ __device__ long crs() const { return (long)C * R * S; }
+    __host__ __device__ long dw_elems() const { return (long)K * C * R * S; }
+};
+
+inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
+
+// Physical workgroup id -> logical id such that the workgroups resident on one
+// XCD (ids congruent modulo 8 are dispatched to the same die) own a contiguous
+// range of logical ids, so neighbours in the logical order share that die's L2.
+__device__ __forceinline__ int xcd_contiguous_id(int bid, int nblocks)
+{
+    const int q = nblocks / kNumXCD, rem = nblocks % kNumXCD;
+    const int xcd = bid % kNumXCD, local = bid / kNumXCD;
+    return xcd * q + (xcd < rem ? xcd : rem) + local;
+}
+
+__device__ __forceinline__ float bf16_bits_to_float(uint16_t b) { return __uint_as_float((uint32_t)b << 16); }
+
+// ---- internal launchers (host). Each validates nothing: the C ABI layer did. ----
+struct ExactPlan {
+    int nt, wk, tap_mode;            // MFMA column tiles per wave, waves along K, column mapping
+    int ktiles, ctiles, splits;
+    int nti, ht, q, qpad, qp;        // images / output rows / positions per staged tile, LDS pitch of dY rows
+    int iht, iwt, pp, ctch;          // staged input rows / cols, LDS pitch of an X channel, channels staged
+    int h_tiles, n_groups;
+    int vec;                         // elements per staging load of dY (1 or 4)
+    size_t lds_bytes, ws_bytes;
+    bool ok;
+};
+ExactPlan plan_exact(const Geometry &g);
+int launch_exact(const Geometry &g, const ExactPlan &pl, const void *X, const void *dY, float *dW,
+                 void *ws, hipStream_t st);
+
+struct ApproxPlan {
+    int chunks;                      // batch chunks whose partial sums are combined afterwards
+    size_t off_idx, off_sum, off_part, ws_bytes;
+};
+ApproxPlan plan_approx(const Geometry &g);
+int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, hipStream_t st);
+int launch_approx(const Geometry &g, const ApproxPlan &pl, const void *X, const void *dY, float *dW,
+                  float scale, int32_t *idx_out, float *sum_out, void *ws, hipStream_t st);
+
+int launch_combine(const float *partials, int nparts, long elems, float scale, float *dW, hipStream_t st);
+int launch_zero(float *dW, long elems, hipStream_t st);
+int launch_random(float *dW, long elems, float sigma, uint64_t seed, uint64_t offset, hipStream_t st);
+
+inline int launch_status() { return hipGetLastError() == hipSuccess ? WGRAD_OK : WGRAD_LAUNCH_FAILED; }
+
+}  // namespace wgrad

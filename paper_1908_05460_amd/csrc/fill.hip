@@ -1,0 +1,67 @@
+// The two trivial gradient methods of arXiv 1908.05460: zero gradient (Section 2.1)
+// and random gradient (Section 2.2).
+#include "common.hpp"
+
+namespace wgrad {
+
+__global__ __launch_bounds__(kBlock) void fill_zero(float *__restrict__ dW, long elems)
+{
+    const long i = ((long)blockIdx.x * kBlock + threadIdx.x) * 4;
+    if (i + 3 < elems && ((uintptr_t)dW % 16) == 0) {
+        *(float4 *)(dW + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    } else {
+        for (long j = i; j < elems && j < i + 4; ++j) dW[j] = 0.f;
+    }
+}
+
+int launch_zero(float *dW, long elems, hipStream_t st)
+{
+    const long threads = (elems + 3) / 4;
+    hipLaunchKernelGGL(fill_zero, dim3((unsigned)((threads + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, dW, elems);
+    return launch_status();
+}
+
+// Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64
+// multiplications with the key bumped by the Weyl constants after each round.
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t &o0, uint32_t &o1)
+{
+#pragma unroll
+    for (int round = 0; round < 10; ++round) {
+        const uint32_t hi0 = __umulhi(0xD2511F53u, c0), lo0 = 0xD2511F53u * c0;
+        const uint32_t hi1 = __umulhi(0xCD9E8D57u, c2), lo1 = 0xCD9E8D57u * c2;
+        c0 = hi1 ^ c1 ^ k0;
+        c1 = lo1;
+        c2 = hi0 ^ c3 ^ k1;
+        c3 = lo0;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    o0 = c0;
+    o1 = c1;
+}
+
+// dW[i] = sigma * sqrt(-2 ln u1) * cos(2 pi u2), with (u1, u2) from the first two
+// Philox words of counter (offset + i) under key seed; u = ((word >> 8) + 0.5) / 2^24
+// lies strictly inside (0,1) and is exact in fp32.
+__global__ __launch_bounds__(kBlock) void fill_normal(float *__restrict__ dW, long elems, float sigma,
+                                                      uint64_t seed, uint64_t offset)
+{
+    const long i = (long)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= elems) return;
+    const uint64_t gidx = offset + (uint64_t)i;
+    uint32_t w0, w1;
+    philox4x32_10((uint32_t)gidx, (uint32_t)(gidx >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), w0, w1);
+    const float u1 = ((float)(w0 >> 8) + 0.5f) * (1.0f / 16777216.0f);
+    const float u2 = ((float)(w1 >> 8) + 0.5f) * (1.0f / 16777216.0f);
+    dW[i] = sigma * sqrtf(-2.0f * logf(u1)) * cospif(2.0f * u2);
+}
+
+int launch_random(float *dW, long elems, float sigma, uint64_t seed, uint64_t offset, hipStream_t st)
+{
+    hipLaunchKernelGGL(fill_normal, dim3((unsigned)((elems + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
+                       dW, elems, sigma, seed, offset);
+    return launch_status();
+}
+
+}  // namespace wgrad

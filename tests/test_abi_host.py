@@ -1,0 +1,94 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports every
+symbol include/wgrad.h declares, and rejects bad arguments before launching anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_1908_05460_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+FAKE = ctypes.c_void_p(0x1000)      # non-null, 256-aligned, never dereferenced by validation
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        import __graft_entry__
+        __graft_entry__.build()
+    return B.load()
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "wgrad.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(conv_wgrad_\w+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported(lib):
+    names = declared_functions()
+    assert set(names) == set(B.EXPORTS) and len(names) == 9
+    for n in names:
+        assert getattr(lib, n) is not None
+
+
+def test_descriptor_struct_matches_header():
+    assert ctypes.sizeof(B.ConvDesc) == 12 * 4
+    d = B.desc(2, 3, 8, 6, 5, R=3, S=2, stride=2, pad=1, stride_w=1, pad_w=0)
+    assert (d.Ho, d.Wo) == (4, 5)
+
+
+def test_invalid_arguments_are_rejected_before_any_launch(lib):
+    good = B.desc(2, 3, 8, 8, 4)
+    f = lib.conv_wgrad_exact
+    assert f(None, FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.INVALID_ARG
+    assert f(ctypes.byref(good), None, FAKE, FAKE, FAKE, 1 << 30, None) == B.INVALID_ARG
+    assert f(ctypes.byref(good), FAKE, None, FAKE, FAKE, 1 << 30, None) == B.INVALID_ARG
+    assert f(ctypes.byref(good), FAKE, FAKE, None, FAKE, 1 << 30, None) == B.INVALID_ARG
+    for field, val in (("N", 0), ("C", -1), ("K", 0), ("R", 0), ("stride_h", 0), ("pad_w", -1), ("dtype", 7)):
+        bad = B.desc(2, 3, 8, 8, 4)
+        setattr(bad, field, val)
+        assert f(ctypes.byref(bad), FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.INVALID_ARG, field
+        assert lib.conv_wgrad_zero(ctypes.byref(bad), FAKE, None) == B.INVALID_ARG
+        assert B.workspace_bytes(bad, B.EXACT) == 0
+    empty = B.desc(1, 1, 2, 2, 1, R=5, S=5, pad=1)          # filter larger than the padded input
+    assert f(ctypes.byref(empty), FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.INVALID_ARG
+    assert lib.conv_wgrad_approx(ctypes.byref(good), FAKE, FAKE, None, 1.0, None, None, FAKE, 1 << 30, None) == B.INVALID_ARG
+    assert lib.conv_wgrad_select(ctypes.byref(good), FAKE, None, FAKE, None) == B.INVALID_ARG
+    assert lib.conv_wgrad_random(ctypes.byref(good), FAKE, -1.0, 0, 0, None) == B.INVALID_ARG
+    assert lib.conv_wgrad_random(ctypes.byref(good), None, 1.0, 0, 0, None) == B.INVALID_ARG
+
+
+def test_workspace_is_checked(lib):
+    d = B.desc(128, 16, 32, 32, 16)
+    for method, call in ((B.EXACT, lambda ws, n: lib.conv_wgrad_exact(ctypes.byref(d), FAKE, FAKE, FAKE, ws, n, None)),
+                         (B.APPROX, lambda ws, n: lib.conv_wgrad_approx(ctypes.byref(d), FAKE, FAKE, FAKE, 1.0, None, None, ws, n, None))):
+        need = B.workspace_bytes(d, method)
+        assert need > 0 and need % 256 == 0
+        assert call(FAKE, need - 1) == B.WORKSPACE_TOO_SMALL
+        assert call(None, need) == B.WORKSPACE_TOO_SMALL
+        assert call(ctypes.c_void_p(0x1010), need) == B.WORKSPACE_TOO_SMALL      # misaligned
+    assert B.workspace_bytes(d, B.ZERO) == 0 and B.workspace_bytes(d, B.RANDOM) == 0
+
+
+def test_schedule_validates_all_layers_first(lib):
+    n = 3
+    descs = (B.ConvDesc * n)(B.desc(4, 8, 8, 8, 8), B.desc(64, 8, 8, 8, 8), B.desc(4, 8, 8, 8, 0))
+    ptrs = (ctypes.c_void_p * n)(0x1000, 0x1000, 0x1000)
+    meth = (ctypes.c_uint8 * n)(B.ZERO, B.ZERO, B.ZERO)
+    run = lib.conv_wgrad_schedule_run
+    assert run(descs, ptrs, ptrs, ptrs, meth, n, 1.0, 1.0, 0, 0, FAKE, 1 << 30, None) == B.INVALID_ARG  # layer 3 bad
+    descs[2].K = 8
+    meth[1] = 9
+    assert run(descs, ptrs, ptrs, ptrs, meth, n, 1.0, 1.0, 0, 0, FAKE, 1 << 30, None) == B.INVALID_ARG  # bad method
+    meth[1] = B.EXACT
+    assert B.workspace_bytes(descs[1], B.EXACT) > 0
+    assert run(descs, ptrs, ptrs, ptrs, meth, n, 1.0, 1.0, 0, 0, FAKE, 0, None) == B.WORKSPACE_TOO_SMALL
+    assert run(descs, ptrs, ptrs, ptrs, meth, 0, 1.0, 1.0, 0, 0, FAKE, 0, None) == B.INVALID_ARG
+    assert lib.conv_wgrad_schedule_workspace_bytes(descs, meth, n) == B.workspace_bytes(descs[1], B.EXACT)
+
+
+def test_status_strings(lib):
+    seen = {B.status_string(s) for s in (0, -1, -2, -3, -4, -99)}
+    assert len(seen) == 6 and B.status_string(0) == "ok"

@@ -1,0 +1,181 @@
+"""GPU parity: every entry point of libwgrad, through the C ABI, element by element
+against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1908_05460_amd import binding as B, inputs
+from tests.gpu_util import (TOL, as_float32, check_select, normwise_err, oracle_shape, rand_inputs,
+                            to_gpu)
+
+pytestmark = pytest.mark.gpu
+
+# N, C, H, W, K, R, S, stride_h, stride_w, pad_h, pad_w  -- several tiles plus ragged tails
+SMALL = [
+    (16, 16, 32, 32, 16, 3, 3, 1, 1, 1, 1),     # the small configuration
+    (3, 3, 32, 32, 16, 3, 3, 1, 1, 1, 1),       # first layer: C = 3 (flat column mapping)
+    (5, 16, 32, 32, 32, 3, 3, 2, 2, 1, 1),      # stride 2
+    (9, 32, 16, 16, 32, 3, 3, 1, 1, 1, 1),
+    (7, 64, 8, 8, 64, 3, 3, 1, 1, 1, 1),
+    (20, 64, 4, 4, 128, 3, 3, 1, 1, 1, 1),      # small planes: several images per tile
+    (37, 48, 2, 2, 80, 3, 3, 1, 1, 1, 1),       # 2x2 planes, ragged K and image groups
+    (4, 5, 9, 7, 19, 3, 3, 1, 1, 1, 1),         # nothing divisible by anything
+    (3, 7, 11, 13, 21, 3, 2, 2, 1, 1, 0),       # non-square filter, mixed stride and padding
+    (2, 64, 6, 6, 24, 1, 1, 1, 1, 0, 0),        # 1x1: a plain GEMM
+    (2, 70, 6, 6, 24, 1, 1, 1, 1, 0, 0),
+    (2, 4, 12, 12, 8, 5, 5, 1, 1, 2, 2),        # 5x5
+    (1, 1, 1, 1, 1, 1, 1, 1, 1, 0, 0),          # degenerate: a single multiply
+    (2, 2, 3, 40, 3, 3, 3, 1, 1, 1, 1),         # wide and flat
+    (130, 16, 8, 8, 16, 3, 3, 1, 1, 1, 1),      # long batch, many reduction splits
+]
+
+
+def mk(t, dtype="fp32"):
+    N, C, H, W, K, R, S, sh, sw, ph, pw = t
+    return B.desc(N, C, H, W, K, R, S, stride=sh, pad=ph, stride_w=sw, pad_w=pw,
+                  dtype=B.BF16 if dtype == "bf16" else B.F32)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("t", SMALL)
+def test_exact_matches_oracle(t, dtype):
+    d = mk(t, dtype)
+    X, dY = rand_inputs(d, 1234, dtype)
+    got = B.conv_wgrad_exact(d, to_gpu(X), to_gpu(dY)).cpu().numpy()
+    want = oracle.wgrad_exact(oracle_shape(d), X, dY)
+    assert normwise_err(got, want) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("t", SMALL)
+def test_approx_matches_oracle(t, dtype):
+    import torch
+    d = mk(t, dtype)
+    X, dY = rand_inputs(d, 4321, dtype)
+    idx = torch.empty((d.N, d.K), dtype=torch.int32, device="cuda")
+    S = torch.empty((d.N, d.K), dtype=torch.float32, device="cuda")
+    got = B.conv_wgrad_approx(d, to_gpu(X), to_gpu(dY), idx_out=idx, sum_out=S).cpu().numpy()
+    want, _, _ = oracle.wgrad_approx(oracle_shape(d), X, dY)
+    check_select(d, dY, idx.cpu().numpy(), S.cpu().numpy())
+    assert normwise_err(got, want) <= TOL[dtype]
+
+
+def test_approx_scale_is_applied_once_and_power_of_two_is_bit_exact():
+    d = mk(SMALL[0])
+    X, dY = rand_inputs(d, 5)
+    Xg, dYg = to_gpu(X), to_gpu(dY)
+    one = B.conv_wgrad_approx(d, Xg, dYg, scale=1.0).cpu().numpy()
+    scaled = B.conv_wgrad_approx(d, Xg, dYg, scale=1 / 128).cpu().numpy()
+    assert np.array_equal(scaled, one * np.float32(1 / 128))
+    want, _, _ = oracle.wgrad_approx(oracle_shape(d), X, dY, scale=1 / 128)
+    assert normwise_err(scaled, want) <= TOL["fp32"]
+
+
+def test_outputs_are_overwritten_not_accumulated_and_runs_are_deterministic():
+    import torch
+    d = mk(SMALL[3])
+    X, dY = rand_inputs(d, 6)
+    Xg, dYg = to_gpu(X), to_gpu(dY)
+    dW = torch.full((d.K, d.C, d.R, d.S), 7.0, device="cuda")
+    a = B.conv_wgrad_exact(d, Xg, dYg, dW=dW).clone()
+    b = B.conv_wgrad_exact(d, Xg, dYg, dW=dW).clone()
+    assert torch.equal(a, b)
+    dW.fill_(float("nan"))
+    c = B.conv_wgrad_approx(d, Xg, dYg, dW=dW).clone()
+    e = B.conv_wgrad_approx(d, Xg, dYg, dW=dW).clone()
+    assert torch.equal(c, e) and torch.isfinite(c).all()
+
+
+def test_zero_dY_gives_exact_zero_and_one_hot_maps_make_approx_equal_exact():
+    import torch
+    d = mk(SMALL[2])
+    X, dY = rand_inputs(d, 7)
+    Xg = to_gpu(X)
+    z = torch.zeros((d.N, d.K, d.Ho, d.Wo), device="cuda")
+    assert not B.conv_wgrad_exact(d, Xg, z).any() and not B.conv_wgrad_approx(d, Xg, z).any()
+    rng = np.random.default_rng(8)
+    one = np.zeros((d.N, d.K, d.Ho * d.Wo), np.float32)
+    pos = rng.integers(0, d.Ho * d.Wo, size=(d.N, d.K))
+    np.put_along_axis(one, pos[..., None], rng.standard_normal((d.N, d.K, 1)).astype(np.float32), axis=2)
+    og = to_gpu(one.reshape(d.N, d.K, d.Ho, d.Wo))
+    ex = B.conv_wgrad_exact(d, Xg, og).cpu().numpy()
+    ap = B.conv_wgrad_approx(d, Xg, og).cpu().numpy()
+    assert normwise_err(ap, ex.astype(np.float64)) <= 1e-5
+
+
+# ---- selection: ties and degenerate maps, bit-exact -------------------------------------
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("hw", [(1, 1), (2, 2), (1, 3), (4, 4), (3, 5), (8, 8), (7, 9), (16, 16), (32, 32), (33, 31), (64, 48)])
+def test_select_with_heavy_ties(hw, dtype):
+    Ho, Wo = hw
+    d = B.desc(6, 1, Ho, Wo, 11, R=1, S=1, pad=0, dtype=B.BF16 if dtype == "bf16" else B.F32)
+    rng = np.random.default_rng(Ho * 100 + Wo)
+    dY = (rng.integers(-3, 4, size=(d.N, d.K, Ho, Wo)) * 0.25).astype(np.float32)   # few distinct magnitudes
+    dY[0, 0] = 0.0                                   # all-zero map -> position 0
+    dY[0, 1] = 0.0; dY[0, 1].flat[-1] = -1e-20       # single tiny value in the last position
+    dY[0, 2] = -0.0
+    if dtype == "bf16":
+        dY = inputs.float32_to_bf16_bits(dY)
+    idx, S = B.conv_wgrad_select(d, to_gpu(dY))
+    check_select(d, dY, idx.cpu().numpy(), S.cpu().numpy())
+
+
+def test_select_on_workload_gradients_fp32_and_bf16():
+    for dtype in ("fp32", "bf16"):
+        d = B.desc(32, 1, 32, 32, 64, R=1, S=1, pad=0, dtype=B.BF16 if dtype == "bf16" else B.F32)
+        _, dY = rand_inputs(d, 99, dtype)
+        idx, S = B.conv_wgrad_select(d, to_gpu(dY))
+        check_select(d, dY, idx.cpu().numpy(), S.cpu().numpy())
+
+
+# ---- trivial methods -------------------------------------------------------------------
+
+def test_zero_gradient():
+    import torch
+    d = mk(SMALL[7])
+    dW = torch.full((d.K, d.C, d.R, d.S), 3.0, device="cuda")
+    B.conv_wgrad_zero(d, dW)
+    assert not dW.any()
+
+
+def test_random_gradient_matches_oracle_stream_value_by_value():
+    import torch
+    d = B.desc(1, 64, 8, 8, 129)                      # 74304 values
+    n = d.K * d.C * 9
+    sigma, seed = 1 / 128, 190805460
+    for offset in (0, 12345, (1 << 32) - 1000):
+        dW = torch.empty((d.K, d.C, 3, 3), device="cuda")
+        B.conv_wgrad_random(d, dW, sigma, seed, offset)
+        want = oracle.random_normal(seed, offset, n, sigma)
+        got = dW.cpu().numpy().ravel().astype(np.float64)
+        assert np.abs(got - want).max() <= 2e-5 * sigma          # fp32 log/sqrt/cos vs fp64
+    a = torch.empty((d.K, d.C, 3, 3), device="cuda"); b = torch.empty_like(a)
+    B.conv_wgrad_random(d, a, sigma, seed, 0); B.conv_wgrad_random(d, b, sigma, seed, n)
+    assert not torch.equal(a, b)                      # a new batch (advanced offset) draws new numbers
+    z = a.cpu().numpy().ravel() / sigma
+    assert abs(z.mean()) < 4 / np.sqrt(n) and abs(z.std() - 1) < 0.02
+
+
+def test_schedule_run_equals_the_individual_calls():
+    import torch
+    from paper_1908_05460_amd import schedule as sch
+    stack, N = inputs.resnet20_stack(), 4
+    descs = [B.desc_for(l, N) for l in stack]
+    data = [inputs.make_layer_inputs(l, N, config=2, layer_index=i) for i, l in enumerate(stack)]
+    Xs = [to_gpu(x) for x, _ in data]; dYs = [to_gpu(y) for _, y in data]
+    dWs = [torch.empty((l.K, l.C, 3, 3), device="cuda") for l in stack]
+    s = B.Schedule(descs, Xs, dYs, dWs)
+    methods = sch.every_other_layer(len(stack), 0)
+    methods[4] = sch.ZERO; methods[6] = sch.RANDOM
+    ws = B.alloc_workspace(s.workspace_bytes(methods))
+    s.run(methods, ws, scale=0.5, sigma=1 / 128, seed=3, offset=1000)
+    off = 1000
+    for i, l in enumerate(stack):
+        ref = torch.empty_like(dWs[i])
+        if methods[i] == sch.EXACT: B.conv_wgrad_exact(descs[i], Xs[i], dYs[i], dW=ref)
+        elif methods[i] == sch.APPROX: B.conv_wgrad_approx(descs[i], Xs[i], dYs[i], scale=0.5, dW=ref)
+        elif methods[i] == sch.ZERO: B.conv_wgrad_zero(descs[i], ref)
+        else: B.conv_wgrad_random(descs[i], ref, 1 / 128, 3, off)
+        assert torch.equal(ref, dWs[i]), l.name
+        off += ref.numel()
