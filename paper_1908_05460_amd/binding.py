@@ -43,6 +43,21 @@ class WgradError(RuntimeError):
 _lib = None
 
 
+def _bind_hip_runtime():
+    """libwgrad.so carries no dependency on a HIP runtime of its own: it must use the one
+    PyTorch allocates memory and creates streams with.  Make that runtime's symbols visible
+    (PyTorch wheels bundle libamdhip64.so under torch/lib; otherwise the system one)."""
+    import torch
+    bundled = os.path.join(os.path.dirname(torch.__file__), "lib", "libamdhip64.so")
+    for cand in (bundled, "libamdhip64.so", "/opt/rocm/lib/libamdhip64.so"):
+        try:
+            ctypes.CDLL(cand, mode=ctypes.RTLD_GLOBAL)
+            return
+        except OSError:
+            continue
+    raise RuntimeError("no HIP runtime (libamdhip64.so) found for libwgrad.so to bind to")
+
+
 def load():
     """Load libwgrad.so; raises if it has not been built (there is no fallback path)."""
     global _lib
@@ -51,6 +66,7 @@ def load():
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with __graft_entry__.build() "
                            "(python -m paper_1908_05460_amd.build)")
+    _bind_hip_runtime()
     L = ctypes.CDLL(LIB_PATH)
     P, vp, i32p, fp = ctypes.POINTER, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
     L.conv_wgrad_exact.argtypes = [P(ConvDesc), vp, vp, fp, vp, ctypes.c_size_t, vp]

@@ -41,7 +41,10 @@ def build(extra_flags=(), out=LIB, objdir=None, verbose=False):
 
     with ThreadPoolExecutor(max_workers=4) as ex:
         objs = list(ex.map(compile_one, SOURCES))
-    subprocess.run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-o", out, *objs], check=True)
+    # -no-hip-rt: the library does not name a HIP runtime of its own; it binds to the one the
+    # host process has already loaded (a process must never run two HIP runtimes side by side,
+    # and PyTorch wheels bundle theirs).  A plain C program links -lamdhip64 itself.
+    subprocess.run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-no-hip-rt", "-o", out, *objs], check=True)
     return out
 
 

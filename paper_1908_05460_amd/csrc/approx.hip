@@ -100,11 +100,11 @@ int launch_select2(const Geometry &g, const void *dY, int32_t *idx_a, float *sum
     const long waves = (maps + 64 / G - 1) / (64 / G);
     const int grid = (int)((waves + kBlock / 64 - 1) / (kBlock / 64));
     if (g.bf16) {
-        if (vec == 8) hipLaunchKernelGGL((approx_select<true, 8>), dim3(grid), dim3(kBlock), 0, st, dY, maps, len, G, idx_a, sum_a, idx_b, sum_b);
-        else          hipLaunchKernelGGL((approx_select<true, 1>), dim3(grid), dim3(kBlock), 0, st, dY, maps, len, G, idx_a, sum_a, idx_b, sum_b);
+        if (vec == 8) WGRAD_LAUNCH((approx_select<true, 8>), dim3(grid), dim3(kBlock), 0, st, dY, maps, len, G, idx_a, sum_a, idx_b, sum_b);
+        else          WGRAD_LAUNCH((approx_select<true, 1>), dim3(grid), dim3(kBlock), 0, st, dY, maps, len, G, idx_a, sum_a, idx_b, sum_b);
     } else {
-        if (vec == 4) hipLaunchKernelGGL((approx_select<false, 4>), dim3(grid), dim3(kBlock), 0, st, dY, maps, len, G, idx_a, sum_a, idx_b, sum_b);
-        else          hipLaunchKernelGGL((approx_select<false, 1>), dim3(grid), dim3(kBlock), 0, st, dY, maps, len, G, idx_a, sum_a, idx_b, sum_b);
+        if (vec == 4) WGRAD_LAUNCH((approx_select<false, 4>), dim3(grid), dim3(kBlock), 0, st, dY, maps, len, G, idx_a, sum_a, idx_b, sum_b);
+        else          WGRAD_LAUNCH((approx_select<false, 1>), dim3(grid), dim3(kBlock), 0, st, dY, maps, len, G, idx_a, sum_a, idx_b, sum_b);
     }
     return launch_status();
 }
@@ -183,8 +183,8 @@ int launch_approx(const Geometry &g, const ApproxPlan &pl, const void *X, const 
     const dim3 grid((unsigned)((outs + kBlock - 1) / kBlock), (unsigned)pl.chunks);
     float *out = pl.chunks > 1 ? part : dW;
     const float kscale = pl.chunks > 1 ? 1.0f : scale;
-    if (g.bf16) hipLaunchKernelGGL((approx_gather_direct<true>), grid, dim3(kBlock), 0, st, X, idx, sum, out, g, chunk_n, kscale);
-    else        hipLaunchKernelGGL((approx_gather_direct<false>), grid, dim3(kBlock), 0, st, X, idx, sum, out, g, chunk_n, kscale);
+    if (g.bf16) WGRAD_LAUNCH((approx_gather_direct<true>), grid, dim3(kBlock), 0, st, X, idx, sum, out, g, chunk_n, kscale);
+    else        WGRAD_LAUNCH((approx_gather_direct<false>), grid, dim3(kBlock), 0, st, X, idx, sum, out, g, chunk_n, kscale);
     rc = launch_status();
     if (rc != WGRAD_OK) return rc;
     if (pl.chunks > 1) return launch_combine(part, pl.chunks, outs, scale, dW, st);
@@ -208,7 +208,7 @@ __global__ __launch_bounds__(kBlock) void combine_partials(const float *__restri
 int launch_combine(const float *partials, int nparts, long elems, float scale, float *dW, hipStream_t st)
 {
     const int grid = (int)((elems + kBlock - 1) / kBlock);
-    hipLaunchKernelGGL(combine_partials, dim3(grid), dim3(kBlock), 0, st, partials, nparts, elems, scale, dW);
+    WGRAD_LAUNCH(combine_partials, dim3(grid), dim3(kBlock), 0, st, partials, nparts, elems, scale, dW);
     return launch_status();
 }
 

@@ -76,6 +76,14 @@ int launch_combine(const float *partials, int nparts, long elems, float scale, f
 int launch_zero(float *dW, long elems, hipStream_t st);
 int launch_random(float *dW, long elems, float sigma, uint64_t seed, uint64_t offset, hipStream_t st);
 
+// hipGetLastError() reports the last error of ANY earlier runtime call on this thread, so it
+// is cleared before a launch and read right after it.
+inline void clear_launch_error() { (void)hipGetLastError(); }
 inline int launch_status() { return hipGetLastError() == hipSuccess ? WGRAD_OK : WGRAD_LAUNCH_FAILED; }
+#define WGRAD_LAUNCH(kernel, grid, block, lds, stream, ...)                               \
+    do {                                                                                    \
+        ::wgrad::clear_launch_error();                                                      \
+        hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                  \
+    } while (0)
 
 }  // namespace wgrad

@@ -305,7 +305,7 @@ ExactPlan plan_exact(const Geometry &g)
 template <int NT, int WK, bool BF16, int VEC>
 static void launch_inst(const ExactParams &p, int grid, size_t lds, hipStream_t st)
 {
-    hipLaunchKernelGGL((wgrad_exact_mfma<NT, WK, BF16, VEC>), dim3(grid), dim3(kBlock), lds, st, p);
+    WGRAD_LAUNCH((wgrad_exact_mfma<NT, WK, BF16, VEC>), dim3(grid), dim3(kBlock), lds, st, p);
 }
 
 template <int NT, int WK>

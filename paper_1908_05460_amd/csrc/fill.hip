@@ -17,7 +17,7 @@ __global__ __launch_bounds__(kBlock) void fill_zero(float *__restrict__ dW, long
 int launch_zero(float *dW, long elems, hipStream_t st)
 {
     const long threads = (elems + 3) / 4;
-    hipLaunchKernelGGL(fill_zero, dim3((unsigned)((threads + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, dW, elems);
+    WGRAD_LAUNCH(fill_zero, dim3((unsigned)((threads + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, dW, elems);
     return launch_status();
 }
 
@@ -59,7 +59,7 @@ __global__ __launch_bounds__(kBlock) void fill_normal(float *__restrict__ dW, lo
 
 int launch_random(float *dW, long elems, float sigma, uint64_t seed, uint64_t offset, hipStream_t st)
 {
-    hipLaunchKernelGGL(fill_normal, dim3((unsigned)((elems + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
+    WGRAD_LAUNCH(fill_normal, dim3((unsigned)((elems + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
                        dW, elems, sigma, seed, offset);
     return launch_status();
 }
