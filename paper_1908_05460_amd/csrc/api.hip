@@ -21,6 +21,7 @@ static int make_geometry(const wgrad_conv_desc *d, Geometry &g)
     const long lim = 1l << 31;
     if ((long)g.N * g.K >= lim || (long)g.Ho * g.Wo >= lim || g.dw_elems() >= lim || (long)g.H * g.W >= lim)
         return WGRAD_UNSUPPORTED;
+    if (g.Ho >= 32768 || g.Wo >= 32768) return WGRAD_UNSUPPORTED;   // (row, col) of a map is packed in 32 bits
     return WGRAD_OK;
 }
 

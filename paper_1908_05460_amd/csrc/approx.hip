@@ -5,6 +5,8 @@
 //   gather :  dW[k,c,r,s] = scale * sum_n S[n,k] * X[n,c,h* sh + r - ph, w* sw + s - pw]
 //             (zero outside X)                                    -- reads the patches
 //   combine:  sums the batch-chunk partials of the gather (shared with the exact path).
+#include <algorithm>
+
 #include "common.hpp"
 
 namespace wgrad {
@@ -30,10 +32,9 @@ __device__ __forceinline__ uint32_t mag_key(uint32_t bits)   // bits of the valu
 
 template <bool BF16, int VEC>
 __global__ __launch_bounds__(kBlock) void approx_select(const void *__restrict__ dY, long maps, int len,
-                                                        int G, int32_t *__restrict__ idx_a,
-                                                        float *__restrict__ sum_a,
-                                                        int32_t *__restrict__ idx_b,
-                                                        float *__restrict__ sum_b)
+                                                        int Wo, int G, int32_t *__restrict__ flat_out,
+                                                        int32_t *__restrict__ hw_out,
+                                                        float *__restrict__ sum_a, float *__restrict__ sum_b)
 {
     const int lane = threadIdx.x & 63;
     const int maps_per_wave = 64 / G;
@@ -79,15 +80,15 @@ __global__ __launch_bounds__(kBlock) void approx_select(const void *__restrict__
     }
     if (map < maps && gl == 0) {
         const int32_t pos = (int32_t)~(uint32_t)packed;
-        idx_a[map] = pos;
-        sum_a[map] = sum;
-        if (idx_b) idx_b[map] = pos;
+        if (flat_out) flat_out[map] = pos;
+        if (hw_out) hw_out[map] = ((pos / Wo) << 16) | (pos % Wo);   // (row, col), for the gather
+        if (sum_a) sum_a[map] = sum;
         if (sum_b) sum_b[map] = sum;
     }
 }
 
-int launch_select2(const Geometry &g, const void *dY, int32_t *idx_a, float *sum_a, int32_t *idx_b,
-                   float *sum_b, hipStream_t st)
+static int launch_select_impl(const Geometry &g, const void *dY, int32_t *flat_out, int32_t *hw_out,
+                              float *sum_a, float *sum_b, hipStream_t st)
 {
     const int len = g.Ho * g.Wo;
     const long maps = (long)g.N * g.K;
@@ -99,29 +100,32 @@ int launch_select2(const Geometry &g, const void *dY, int32_t *idx_a, float *sum
     while (G < 64 && G * vec * 4 < len) G <<= 1;
     const long waves = (maps + 64 / G - 1) / (64 / G);
     const int grid = (int)((waves + kBlock / 64 - 1) / (kBlock / 64));
+#define SEL_ARGS dim3(grid), dim3(kBlock), 0, st, dY, maps, len, g.Wo, G, flat_out, hw_out, sum_a, sum_b
     if (g.bf16) {
-        if (vec == 8) WGRAD_LAUNCH((approx_select<true, 8>), dim3(grid), dim3(kBlock), 0, st, dY, maps, len, G, idx_a, sum_a, idx_b, sum_b);
-        else          WGRAD_LAUNCH((approx_select<true, 1>), dim3(grid), dim3(kBlock), 0, st, dY, maps, len, G, idx_a, sum_a, idx_b, sum_b);
+        if (vec == 8) WGRAD_LAUNCH((approx_select<true, 8>), SEL_ARGS);
+        else          WGRAD_LAUNCH((approx_select<true, 1>), SEL_ARGS);
     } else {
-        if (vec == 4) WGRAD_LAUNCH((approx_select<false, 4>), dim3(grid), dim3(kBlock), 0, st, dY, maps, len, G, idx_a, sum_a, idx_b, sum_b);
-        else          WGRAD_LAUNCH((approx_select<false, 1>), dim3(grid), dim3(kBlock), 0, st, dY, maps, len, G, idx_a, sum_a, idx_b, sum_b);
+        if (vec == 4) WGRAD_LAUNCH((approx_select<false, 4>), SEL_ARGS);
+        else          WGRAD_LAUNCH((approx_select<false, 1>), SEL_ARGS);
     }
+#undef SEL_ARGS
     return launch_status();
 }
 
 int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, hipStream_t st)
 {
-    return launch_select2(g, dY, idx, sum, nullptr, nullptr, st);
+    return launch_select_impl(g, dY, idx, nullptr, sum, nullptr, st);
 }
 
 // ------------------------------------------------------------------------------------
 // gather, direct form: one thread per filter-gradient entry (k, c, r, s) and batch
-// chunk; it walks the chunk's images, reads the map's (idx, S) and the one input
-// element its tap sees.  Used when the patches touch only part of each input plane.
+// chunk; it walks the chunk's images, reads the map's (row, col, S) and the one input
+// element its tap sees.  Used when the patches touch only part of each input plane
+// (few output channels, large planes) and for filters other than 3x3.
 // ------------------------------------------------------------------------------------
 template <bool BF16>
 __global__ __launch_bounds__(kBlock) void approx_gather_direct(const void *__restrict__ X,
-                                                               const int32_t *__restrict__ idx,
+                                                               const int32_t *__restrict__ hw,
                                                                const float *__restrict__ sum,
                                                                float *__restrict__ out, Geometry g,
                                                                int chunk_n, float scale)
@@ -136,9 +140,9 @@ __global__ __launch_bounds__(kBlock) void approx_gather_direct(const void *__res
     float acc = 0.f;
 #pragma unroll 4
     for (int n = n_begin; n < n_end; ++n) {
-        const int pos = idx[(long)n * g.K + k];
+        const int p = hw[(long)n * g.K + k];
         const float sv = sum[(long)n * g.K + k];
-        const int ih = (pos / g.Wo) * g.sh + r - g.ph, iw = (pos % g.Wo) * g.sw + s - g.pw;
+        const int ih = (p >> 16) * g.sh + r - g.ph, iw = (p & 0xffff) * g.sw + s - g.pw;
         if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) {
             const long xi = (((long)n * g.C + c) * g.H + ih) * g.W + iw;
             const float xv = BF16 ? bf16_bits_to_float(((const uint16_t *)X)[xi]) : ((const float *)X)[xi];
@@ -148,43 +152,266 @@ __global__ __launch_bounds__(kBlock) void approx_gather_direct(const void *__res
     out[(long)blockIdx.y * g.K * CRS + o] = acc * scale;
 }
 
-#ifndef WGRAD_APPROX_THREADS   // threads to aim for when chunking the batch
+// ------------------------------------------------------------------------------------
+// gather, LDS form (3x3 filters): used when the K patches of an image cover its input
+// planes many times over (small planes, many output channels).  A workgroup owns
+// 4*M output channels x 64 input channels and walks a chunk of the batch in groups of
+// `nb` images; every wavefront handles M output channels with one input channel per
+// lane and keeps its 9*M sums in registers.
+//
+// Per group the 64 input planes of the nb images are staged in LDS with a zero halo
+// (the padding the taps can reach), so a patch is nine unconditional reads at
+// window origin + r*WP + s; the halo is zeroed once, staging only writes the interior.
+// The plane pitch is odd: 32 consecutive channels hit 32 banks.  Everything is
+// software-pipelined one group ahead: the global loads of group g+1 (input planes, and
+// the (row, col, S) of the group's nb*M maps, one per lane) are issued before group g
+// is computed, and LDS is double-buffered so one barrier per group suffices.  The
+// selected position and sum of a map are moved to scalar registers with v_readlane, so
+// the window origin is scalar arithmetic and S is a scalar multiplier.
+// ------------------------------------------------------------------------------------
+constexpr int kGatherCT = 64;
+constexpr int kGatherSlots = 8;      // 16-byte loads per thread and group
+constexpr size_t kGatherLds = 64 * 1024;
+
+template <bool BF16> struct Raw4 { typedef float4 type; };
+template <> struct Raw4<true> { typedef uint2 type; };   // 4 bf16
+
+struct GatherParams {
+    int ctiles, nb, chunk_n;
+    int wp, pitch;                   // haloed row pitch, LDS pitch of a haloed plane (odd)
+    FastDiv d_hw4, d_w;
+    float scale;
+};
+
+template <bool BF16, int M>
+__global__ __launch_bounds__(kBlock) void approx_gather_lds3x3(const void *__restrict__ X,
+                                                               const int32_t *__restrict__ hw,
+                                                               const float *__restrict__ sum,
+                                                               float *__restrict__ out, Geometry g,
+                                                               GatherParams gp)
+{
+    typedef typename Raw4<BF16>::type raw4;
+    extern __shared__ float xs[];                         // [2][nb][64][pitch]
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ctile = blockIdx.x % gp.ctiles, ktile = blockIdx.x / gp.ctiles;
+    const int c0 = ctile * kGatherCT;
+    const int k_base = ktile * (4 * M) + wave * M;
+    const int HW = g.H * g.W, hw4 = HW >> 2;
+    const int nb = gp.nb, pitch = gp.pitch, WP = gp.wp;
+    const int n_begin = blockIdx.y * gp.chunk_n;
+    const int n_end = n_begin + gp.chunk_n < g.N ? n_begin + gp.chunk_n : g.N;
+    const int cvalid = g.C - c0 < kGatherCT ? g.C - c0 : kGatherCT;   // channels of this tile inside X
+    const int run4 = cvalid * hw4;                        // 16-byte pieces per image
+    const int buf_floats = nb * kGatherCT * pitch;
+    FastDiv d_run4;                                       // run4 differs for the last channel tile
+    d_run4.d = run4;
+    d_run4.m = run4 > 1 ? (uint32_t)((1ull << 32) / (uint32_t)run4) + 1u : 0u;
+
+    for (int e = tid; e < 2 * buf_floats; e += kBlock) xs[e] = 0.f;   // halo (and everything else) = 0
+
+    float acc[M][9];
+#pragma unroll
+    for (int j = 0; j < M; ++j)
+#pragma unroll
+        for (int t = 0; t < 9; ++t) acc[j][t] = 0.f;
+
+    raw4 xr[kGatherSlots];
+    int hw_next = 0;
+    float sv_next = 0.f;
+
+    // issue the loads of the group starting at image n0 (registers only)
+    auto prefetch = [&](int n0) {
+        // lane l of every wavefront: map (image n0 + l / M, channel k_base + l % M).  Issued before
+        // the plane loads: memory returns in order, so once the planes have arrived these have too.
+        const int n = n0 + lane / M, k = k_base + lane % M;
+        const bool ok = lane < nb * M && n < n_end && k < g.K;
+        hw_next = ok ? hw[(long)n * g.K + k] : 0;
+        sv_next = ok ? sum[(long)n * g.K + k] : 0.f;
+        const int nb_cur = n_end - n0 < nb ? n_end - n0 : nb;
+        const int total = nb_cur * run4;
+#pragma unroll
+        for (int u = 0; u < kGatherSlots; ++u) {
+            const int e = tid + u * kBlock;
+            if (e < total) {
+                uint32_t n_l, rem;
+                d_run4.divmod(e, n_l, rem);
+                const long src = ((long)(n0 + n_l) * g.C + c0) * HW + (long)rem * 4;
+                xr[u] = BF16 ? *(const raw4 *)((const uint16_t *)X + src) : *(const raw4 *)((const float *)X + src);
+            }
+        }
+    };
+
+    prefetch(n_begin);
+    int parity = 0;
+    for (int n0 = n_begin; n0 < n_end; n0 += nb, parity ^= 1) {
+        const int nb_cur = n_end - n0 < nb ? n_end - n0 : nb;
+        float *buf = xs + parity * buf_floats;
+        if (n0 == n_begin) __syncthreads();               // the zero fill is complete
+        {   // registers -> LDS (interior of the haloed planes)
+            const int total = nb_cur * run4;
+#pragma unroll
+            for (int u = 0; u < kGatherSlots; ++u) {
+                const int e = tid + u * kBlock;
+                if (e < total) {
+                    uint32_t n_l, rem, c_l, q4;
+                    d_run4.divmod(e, n_l, rem);
+                    gp.d_hw4.divmod(rem, c_l, q4);
+                    float v[4];
+                    if (BF16) {
+                        const uint2 r = *(const uint2 *)&xr[u];
+                        v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
+                        v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
+                    } else {
+                        const float4 r = *(const float4 *)&xr[u];
+                        v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+                    }
+                    float *dst = buf + (n_l * kGatherCT + c_l) * pitch + g.ph * WP + g.pw;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        uint32_t ih, iw;
+                        gp.d_w.divmod(q4 * 4 + i, ih, iw);
+                        dst[ih * WP + iw] = v[i];
+                    }
+                }
+            }
+        }
+        // Copy through an opaque move: it makes the wait for these two loads happen here, where
+        // they have long arrived, instead of at their first use below, after the next group's
+        // loads have been issued (the memory counter is in-order: waiting there would drain those).
+        int hw_cur;
+        float sv_cur;
+        asm volatile("v_mov_b32 %0, %1" : "=v"(hw_cur) : "v"(hw_next));
+        asm volatile("v_mov_b32 %0, %1" : "=v"(sv_cur) : "v"(sv_next));
+        __syncthreads();
+        if (n0 + nb < n_end) prefetch(n0 + nb);
+
+        if (lane < cvalid) {
+            const float *plane = buf + lane * pitch;
+            for (int n_l = 0; n_l < nb_cur; ++n_l, plane += kGatherCT * pitch) {
+#pragma unroll
+                for (int j = 0; j < M; ++j) {
+                    const int p = __builtin_amdgcn_readlane(hw_cur, n_l * M + j);
+                    const float sv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sv_cur), n_l * M + j));
+                    const float *win = plane + (p >> 16) * g.sh * WP + (p & 0xffff) * g.sw;   // window origin
+#pragma unroll
+                    for (int r = 0; r < 3; ++r) {
+                        const float *row = win + r * WP;
+#pragma unroll
+                        for (int s = 0; s < 3; ++s) acc[j][r * 3 + s] = fmaf(sv, row[s], acc[j][r * 3 + s]);
+                    }
+                }
+            }
+        }
+    }
+    if (lane < cvalid) {
+        float *o = out + (long)blockIdx.y * g.K * g.C * 9;
+#pragma unroll
+        for (int j = 0; j < M; ++j) {
+            const int k = k_base + j;
+            if (k >= g.K) continue;
+#pragma unroll
+            for (int t = 0; t < 9; ++t) o[((long)k * g.C + c0 + lane) * 9 + t] = acc[j][t] * gp.scale;
+        }
+    }
+}
+
+#ifndef WGRAD_APPROX_THREADS   // threads to aim for when chunking the batch (direct form)
 #define WGRAD_APPROX_THREADS (256 * 1024)
 #endif
+#ifndef WGRAD_GATHER_BLOCKS    // workgroups to aim for (LDS form)
+#define WGRAD_GATHER_BLOCKS 256
+#endif
 
-ApproxPlan plan_approx(const Geometry &g)
+ApproxPlan plan_approx(const Geometry &g, bool allow_lds)
 {
     ApproxPlan pl{};
     const long outs = g.dw_elems();
-    long chunks = (WGRAD_APPROX_THREADS + outs - 1) / outs;
-    if (chunks > g.N) chunks = g.N;
+    const int HW = g.H * g.W;
+    // LDS form when every input element is used several times over by the K patches of its image
+    // haloed plane: rows/cols -pad .. max(last tap the positions can reach, last row/col of X)
+    const int hp = std::max((g.Ho - 1) * g.sh + 3, g.H + g.ph), wp = std::max((g.Wo - 1) * g.sw + 3, g.W + g.pw);
+    const int pitch = (hp * wp) | 1;
+    pl.use_lds = allow_lds && g.R == 3 && g.S == 3 && g.C >= 16 && (long)g.K * 9 >= 2l * HW && HW % 4 == 0
+                 && kGatherCT * HW <= kGatherSlots * kBlock * 4
+                 && (size_t)2 * kGatherCT * pitch * 4 <= kGatherLds;
+    long chunks;
+    if (pl.use_lds) {
+        pl.m = g.K >= 256 ? 4 : (g.K >= 32 ? 2 : 1);
+        pl.pitch = pitch;
+        pl.wp = wp;
+        // images per group: at most 8 16-byte loads per thread, one lane per (image, channel) pair
+        pl.nb = kGatherSlots * kBlock * 4 / (kGatherCT * HW);
+        if (pl.nb > 64 / pl.m) pl.nb = 64 / pl.m;
+        const int lds_cap = (int)(kGatherLds / ((size_t)2 * kGatherCT * pl.pitch * 4));   // double buffered
+        if (pl.nb > lds_cap) pl.nb = lds_cap;
+        if (pl.nb > g.N) pl.nb = g.N;
+        pl.ctiles = (g.C + kGatherCT - 1) / kGatherCT;
+        pl.ktiles = (g.K + 4 * pl.m - 1) / (4 * pl.m);
+        const long tiles = (long)pl.ctiles * pl.ktiles;
+        chunks = tiles >= WGRAD_GATHER_BLOCKS ? 1 : (WGRAD_GATHER_BLOCKS + tiles - 1) / tiles;
+        const long max_chunks = (g.N + pl.nb - 1) / pl.nb;
+        if (chunks > max_chunks) chunks = max_chunks;
+    } else {
+        chunks = (WGRAD_APPROX_THREADS + outs - 1) / outs;
+        if (chunks > g.N) chunks = g.N;
+    }
     if (chunks < 1) chunks = 1;
-    const int chunk_n = (int)((g.N + chunks - 1) / chunks);
-    pl.chunks = (g.N + chunk_n - 1) / chunk_n;
+    pl.chunk_n = (int)((g.N + chunks - 1) / chunks);
+    pl.chunks = (g.N + pl.chunk_n - 1) / pl.chunk_n;
     size_t off = 0;
     pl.off_idx = off; off += align_up((size_t)g.N * g.K * 4);
     pl.off_sum = off; off += align_up((size_t)g.N * g.K * 4);
     pl.off_part = off; off += pl.chunks > 1 ? align_up((size_t)pl.chunks * outs * 4) : 0;
     pl.ws_bytes = off;
+    // a caller whose X is not 16-byte aligned gets the direct form: size the workspace for both
+    if (pl.use_lds) {
+        const size_t alt = plan_approx(g, false).ws_bytes;
+        if (alt > pl.ws_bytes) pl.ws_bytes = alt;
+    }
     return pl;
 }
 
-int launch_approx(const Geometry &g, const ApproxPlan &pl, const void *X, const void *dY, float *dW,
+template <bool BF16>
+static void launch_gather_lds(const ApproxPlan &pl, dim3 grid, size_t lds, hipStream_t st, const void *X,
+                              const int32_t *hw, const float *sum, float *out, const Geometry &g, float scale)
+{
+    GatherParams gp;
+    gp.ctiles = pl.ctiles; gp.nb = pl.nb; gp.chunk_n = pl.chunk_n; gp.wp = pl.wp; gp.pitch = pl.pitch;
+    gp.d_hw4 = FastDiv(g.H * g.W / 4);        // dividends stay below 64 * H*W, far under the 2^32 bound
+    gp.d_w = FastDiv(g.W);
+    gp.scale = scale;
+#define GL_ARGS grid, dim3(kBlock), lds, st, X, hw, sum, out, g, gp
+    if (pl.m == 4) WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 4>), GL_ARGS);
+    else if (pl.m == 2) WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 2>), GL_ARGS);
+    else WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 1>), GL_ARGS);
+#undef GL_ARGS
+}
+
+int launch_approx(const Geometry &g, const ApproxPlan &plan, const void *X, const void *dY, float *dW,
                   float scale, int32_t *idx_out, float *sum_out, void *ws, hipStream_t st)
 {
-    int32_t *idx = (int32_t *)((char *)ws + pl.off_idx);
+    const bool aligned = ((uintptr_t)X % (g.bf16 ? 8 : 16)) == 0;
+    const ApproxPlan pl = (plan.use_lds && !aligned) ? plan_approx(g, false) : plan;
+    int32_t *hw = (int32_t *)((char *)ws + pl.off_idx);
     float *sum = (float *)((char *)ws + pl.off_sum);
     float *part = (float *)((char *)ws + pl.off_part);
-    int rc = launch_select2(g, dY, idx, sum, idx_out, sum_out, st);
+    int rc = launch_select_impl(g, dY, idx_out, hw, sum, sum_out, st);
     if (rc != WGRAD_OK) return rc;
 
     const long outs = g.dw_elems();
-    const int chunk_n = (g.N + pl.chunks - 1) / pl.chunks;
-    const dim3 grid((unsigned)((outs + kBlock - 1) / kBlock), (unsigned)pl.chunks);
     float *out = pl.chunks > 1 ? part : dW;
     const float kscale = pl.chunks > 1 ? 1.0f : scale;
-    if (g.bf16) WGRAD_LAUNCH((approx_gather_direct<true>), grid, dim3(kBlock), 0, st, X, idx, sum, out, g, chunk_n, kscale);
-    else        WGRAD_LAUNCH((approx_gather_direct<false>), grid, dim3(kBlock), 0, st, X, idx, sum, out, g, chunk_n, kscale);
+    if (pl.use_lds) {
+        const dim3 grid((unsigned)(pl.ctiles * pl.ktiles), (unsigned)pl.chunks);
+        const size_t lds = (size_t)2 * pl.nb * kGatherCT * pl.pitch * 4;
+        if (g.bf16) launch_gather_lds<true>(pl, grid, lds, st, X, hw, sum, out, g, kscale);
+        else        launch_gather_lds<false>(pl, grid, lds, st, X, hw, sum, out, g, kscale);
+    } else {
+        const dim3 grid((unsigned)((outs + kBlock - 1) / kBlock), (unsigned)pl.chunks);
+        if (g.bf16) WGRAD_LAUNCH((approx_gather_direct<true>), grid, dim3(kBlock), 0, st, X, hw, sum, out, g, pl.chunk_n, kscale);
+        else        WGRAD_LAUNCH((approx_gather_direct<false>), grid, dim3(kBlock), 0, st, X, hw, sum, out, g, pl.chunk_n, kscale);
+    }
     rc = launch_status();
     if (rc != WGRAD_OK) return rc;
     if (pl.chunks > 1) return launch_combine(part, pl.chunks, outs, scale, dW, st);
@@ -192,23 +419,53 @@ int launch_approx(const Geometry &g, const ApproxPlan &pl, const void *X, const 
 }
 
 // ------------------------------------------------------------------------------------
-// combine: dW[o] = scale * sum_i partial[i][o], summed in ascending i (deterministic).
+// combine: dW[o] = scale * sum_i partial[i][o].  PL lanes share one output: lane pl adds
+// partials pl, pl+PL, ... in ascending order, then the PL sub-sums are added in
+// ascending pl through LDS -- a fixed order, so the result is deterministic.
 // ------------------------------------------------------------------------------------
+template <int PL>
 __global__ __launch_bounds__(kBlock) void combine_partials(const float *__restrict__ part, int nparts,
                                                            long elems, float scale, float *__restrict__ dW)
 {
-    const long o = (long)blockIdx.x * kBlock + threadIdx.x;
-    if (o >= elems) return;
+    constexpr int OB = kBlock / PL;                       // outputs per workgroup
+    __shared__ float red[PL][OB];
+    const int ol = threadIdx.x % OB, pl = threadIdx.x / OB;
+    const long o = (long)blockIdx.x * OB + ol;
     float acc = 0.f;
-#pragma unroll 8
-    for (int i = 0; i < nparts; ++i) acc += part[(long)i * elems + o];
-    dW[o] = acc * scale;
+    if (o < elems) {
+        int i = pl;
+        for (; i + 7 * PL < nparts; i += 8 * PL) {
+            float v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) v[u] = part[(long)(i + u * PL) * elems + o];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) acc += v[u];
+        }
+        for (; i < nparts; i += PL) acc += part[(long)i * elems + o];
+    }
+    if (PL == 1) {
+        if (o < elems) dW[o] = acc * scale;
+        return;
+    }
+    red[pl][ol] = acc;
+    __syncthreads();
+    if (pl == 0 && o < elems) {
+        float t = 0.f;
+#pragma unroll
+        for (int q = 0; q < PL; ++q) t += red[q][ol];
+        dW[o] = t * scale;
+    }
 }
 
 int launch_combine(const float *partials, int nparts, long elems, float scale, float *dW, hipStream_t st)
 {
-    const int grid = (int)((elems + kBlock - 1) / kBlock);
-    WGRAD_LAUNCH(combine_partials, dim3(grid), dim3(kBlock), 0, st, partials, nparts, elems, scale, dW);
+    // spread the partial index over lanes when there are few outputs and many partials
+    const int pl = (elems <= 16 * 1024 && nparts >= 64) ? 16 : ((elems <= 256 * 1024 && nparts >= 16) ? 4 : 1);
+    const int ob = kBlock / pl;
+    const int grid = (int)((elems + ob - 1) / ob);
+    if (pl == 16) WGRAD_LAUNCH(combine_partials<16>, dim3(grid), dim3(kBlock), 0, st, partials, nparts, elems, scale, dW);
+    else if (pl == 4) WGRAD_LAUNCH(combine_partials<4>, dim3(grid), dim3(kBlock), 0, st, partials, nparts, elems, scale, dW);
+    else WGRAD_LAUNCH(combine_partials<1>, dim3(grid), dim3(kBlock), 0, st, partials, nparts, elems, scale, dW);
     return launch_status();
 }
 

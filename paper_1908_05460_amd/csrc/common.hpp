@@ -55,7 +55,7 @@ struct ExactPlan {
     int nti, ht, q, qpad, qp;        // images / output rows / positions per staged tile, LDS pitch of dY rows
     int iht, iwt, pp, ctch;          // staged input rows / cols, LDS pitch of an X channel, channels staged
     int h_tiles, n_groups;
-    int vec;                         // elements per staging load of dY (1 or 4)
+    int xv;                          // elements per staging access (4, 2; 0 = element-wise staging)
     size_t lds_bytes, ws_bytes;
     bool ok;
 };
@@ -64,10 +64,11 @@ int launch_exact(const Geometry &g, const ExactPlan &pl, const void *X, const vo
                  void *ws, hipStream_t st);
 
 struct ApproxPlan {
-    int chunks;                      // batch chunks whose partial sums are combined afterwards
+    int chunks, chunk_n;             // batch chunks whose partial sums are combined afterwards
+    int use_lds, m, nb, pitch, wp, ctiles, ktiles;   // LDS form of the gather: tile shape
     size_t off_idx, off_sum, off_part, ws_bytes;
 };
-ApproxPlan plan_approx(const Geometry &g);
+ApproxPlan plan_approx(const Geometry &g, bool allow_lds = true);
 int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, hipStream_t st);
 int launch_approx(const Geometry &g, const ApproxPlan &pl, const void *X, const void *dY, float *dW,
                   float scale, int32_t *idx_out, float *sum_out, void *ws, hipStream_t st);
@@ -80,10 +81,10 @@ int launch_random(float *dW, long elems, float sigma, uint64_t seed, uint64_t of
 // is cleared before a launch and read right after it.
 inline void clear_launch_error() { (void)hipGetLastError(); }
 inline int launch_status() { return hipGetLastError() == hipSuccess ? WGRAD_OK : WGRAD_LAUNCH_FAILED; }
-#define WGRAD_LAUNCH(kernel, grid, block, lds, stream, ...)                               \
+#define WGRAD_LAUNCH(...)                                                                   \
     do {                                                                                    \
         ::wgrad::clear_launch_error();                                                      \
-        hipLaunchKernelGGL(kernel, grid, block, lds, stream, __VA_ARGS__);                  \
+        hipLaunchKernelGGL(__VA_ARGS__);                                                    \
     } while (0)
 
 }  // namespace wgrad

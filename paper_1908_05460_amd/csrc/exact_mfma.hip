@@ -13,6 +13,14 @@
 // reduction is long, so the reduction is split over workgroups; each keeps its
 // accumulators in registers across all of its tiles and writes one partial result.
 //
+// Pipeline (vector staging modes): while the wavefronts contract tile t out of LDS,
+// the 16-byte global loads of tile t+1 are already in flight into registers; they are
+// written to LDS after the barrier that ends tile t.  Which element of a tile a thread
+// stages is the same for every tile, so each thread decodes its staging slots once
+// (LDS destination, offset from the tile origin) and keeps them in registers.  The
+// contraction loop itself is unrolled by two with the LDS operand reads of step i+1
+// issued before the MFMAs of step i.
+//
 // MFMA: v_mfma_f32_16x16x4_f32.  Lane l supplies A[i = l%16][kk = l/16] and
 // B[kk = l/16][j = l%16]; the 4 reduction slots kk are 4 consecutive staged
 // positions.  The accumulator registers v = 0..3 of lane l hold D[4*(l/16) + v][l%16].
@@ -21,6 +29,9 @@
 namespace wgrad {
 
 typedef float float4_t __attribute__((ext_vector_type(4)));
+
+constexpr int kSlotsDY = 8;     // 16-byte global loads of dY per thread and tile
+constexpr int kSlotsX = 4;      // 16- or 8-byte global loads of X per thread and tile
 
 struct ExactParams {
     const void *X, *dY;
@@ -31,7 +42,8 @@ struct ExactParams {
     int seg;                    // ht * Wo : contiguous dY elements per (image, channel) in a tile
     int plane;                  // nti * iht * iwt : staged input elements per channel
     FastDiv d_segv, d_nsegv;    // dY staging: vectors per segment, per channel row
-    FastDiv d_plane, d_img, d_iwt;  // X staging
+    FastDiv d_plane, d_img, d_iwt;   // X staging, element-wise mode
+    FastDiv d_wv, d_rows, d_iht;     // X staging, vector modes: vectors per row, rows per channel, rows per image
 };
 
 template <bool BF16>
@@ -41,29 +53,74 @@ __device__ __forceinline__ float load_elem(const void *p, long i)
     return ((const float *)p)[i];
 }
 
-template <bool BF16>
-__device__ __forceinline__ float4_t load_vec4(const void *p, long i)   // i is a multiple of 4
-{
-    float4_t v;
-    if (BF16) {
-        const uint2 raw = *(const uint2 *)((const uint16_t *)p + i);
-        v.x = __uint_as_float(raw.x << 16);
-        v.y = __uint_as_float(raw.x & 0xffff0000u);
-        v.z = __uint_as_float(raw.y << 16);
-        v.w = __uint_as_float(raw.y & 0xffff0000u);
-    } else {
-        v = *(const float4_t *)((const float *)p + i);
+// V consecutive elements starting at element i (aligned to V elements), widened to fp32.
+template <bool BF16, int V> struct Vec;
+template <> struct Vec<false, 4> {
+    float4_t r;
+    __device__ __forceinline__ void load(const void *p, long i) { r = *(const float4_t *)((const float *)p + i); }
+    __device__ __forceinline__ void zero() { r = float4_t{0.f, 0.f, 0.f, 0.f}; }
+    __device__ __forceinline__ float get(int u) const { return r[u]; }
+};
+template <> struct Vec<false, 2> {
+    float2 r;
+    __device__ __forceinline__ void load(const void *p, long i) { r = *(const float2 *)((const float *)p + i); }
+    __device__ __forceinline__ void zero() { r = make_float2(0.f, 0.f); }
+    __device__ __forceinline__ float get(int u) const { return u == 0 ? r.x : r.y; }
+};
+template <> struct Vec<true, 4> {
+    uint2 r;
+    __device__ __forceinline__ void load(const void *p, long i) { r = *(const uint2 *)((const uint16_t *)p + i); }
+    __device__ __forceinline__ void zero() { r = make_uint2(0u, 0u); }
+    __device__ __forceinline__ float get(int u) const {
+        const uint32_t w = u < 2 ? r.x : r.y;
+        return __uint_as_float((u & 1) ? (w & 0xffff0000u) : (w << 16));
     }
-    return v;
+};
+template <> struct Vec<true, 2> {
+    uint32_t r;
+    __device__ __forceinline__ void load(const void *p, long i) { r = *(const uint32_t *)((const uint16_t *)p + i); }
+    __device__ __forceinline__ void zero() { r = 0u; }
+    __device__ __forceinline__ float get(int u) const { return __uint_as_float(u ? (r & 0xffff0000u) : (r << 16)); }
+};
+
+// Column mapping of MFMA column tile t for lane column i16.  tap_mode: the tile covers 16
+// consecutive channels at one filter tap (bank-conflict-free operand reads); otherwise 16
+// consecutive flat columns c*R*S + r*S + s (any C, R, S).  Returns the LDS offset of the
+// column inside the staged window (0 for a padding column) and its flat output column
+// (-1 for a padding column).
+template <int NT>
+__device__ __forceinline__ void column_of(const ExactParams &p, int coltile, int t, int i16, int c_first,
+                                          int &lds_off, int &out_col)
+{
+    const Geometry &g = p.g;
+    const int RS = g.R * g.S;
+    int c, tap;
+    bool ok;
+    if (p.tap_mode) {
+        c = c_first + (t / RS) * 16 + i16;
+        tap = t % RS;
+        ok = c < g.C;
+    } else {
+        const int col = coltile * NT * 16 + t * 16 + i16;
+        ok = col < g.C * RS;
+        c = col / RS;
+        tap = col % RS;
+    }
+    lds_off = ok ? (c - c_first) * p.pp + (tap / g.S) * p.iwt + tap % g.S : 0;
+    out_col = ok ? c * RS + tap : -1;
 }
 
-// NT: 16-column MFMA tiles per wavefront; WK: wavefronts along K (tile of 16*WK
-// output channels), the other 4/WK wavefronts split the staged positions; VEC:
-// elements per dY staging access.
-template <int NT, int WK, bool BF16, int VEC>
+// NT: 16-column MFMA tiles per wavefront; WK: wavefronts along K (tile of 16*WK output
+// channels), the other 4/WK wavefronts split the staged positions.  XV: elements per
+// global access when staging (4 or 2: rows of X and segments of dY are read in 16- or
+// 8-byte pieces, pipelined through registers; 0: element-wise staging for shapes and
+// alignments that allow nothing wider).
+template <int NT, int WK, bool BF16, int XV>
 __global__ __launch_bounds__(kBlock) void wgrad_exact_mfma(const ExactParams p)
 {
     constexpr int KT = 16 * WK, WQ = 4 / WK;
+    constexpr bool FAST = XV != 0;
+    constexpr int XVn = FAST ? XV : 2;                  // placeholder width for the unused registers
     extern __shared__ float smem[];
     float *dYs = smem;                              // [KT][qp]
     float *Xs = dYs + KT * p.qp;                    // [ctch][pp]
@@ -80,36 +137,18 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_mfma(const ExactParams p)
     const int ktile = (logical / p.ctiles) % p.ktiles;
     const int split = logical / (p.ctiles * p.ktiles);
     const int k0 = ktile * KT;
+    const int c_first = p.tap_mode ? coltile * 16 * (NT / RS) : (coltile * NT * 16) / RS;
 
-    // Column mapping. tap_mode: tile t covers 16 consecutive channels at one filter
-    // tap (bank-conflict-free operand reads); otherwise 16 consecutive flat columns
-    // c*R*S + r*S + s (any C, R, S).
-    int coloff[NT], outcol[NT];
-    int c_first;
-    if (p.tap_mode) {
-        c_first = coltile * 16 * (NT / RS);
+    int coloff[NT];
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const int c_l = (t / RS) * 16 + i16, tap = t % RS;
-            const bool ok = c_first + c_l < g.C;
-            coloff[t] = ok ? c_l * p.pp + (tap / g.S) * p.iwt + tap % g.S : 0;
-            outcol[t] = ok ? (c_first + c_l) * RS + tap : -1;
-        }
-    } else {
-        const int col0 = coltile * NT * 16;
-        c_first = col0 / RS;
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const int col = col0 + t * 16 + i16;
-            const bool ok = col < CRS;
-            const int c = col / RS, tap = col % RS;
-            coloff[t] = ok ? (c - c_first) * p.pp + (tap / g.S) * p.iwt + tap % g.S : 0;
-            outcol[t] = ok ? col : -1;
-        }
+    for (int t = 0; t < NT; ++t) {
+        int oc;
+        column_of<NT>(p, coltile, t, i16, c_first, coloff[t], oc);
     }
 
-    // Offset of staged position q inside a staged input channel (constant for the kernel).
-    for (int q = tid; q < p.qpad; q += kBlock) {
+    // Offset of staged position q inside a staged input channel (constant for the kernel);
+    // 8 spare entries let the contraction loop read two steps ahead.
+    for (int q = tid; q < p.qpad + 8; q += kBlock) {
         int off = 0;
         if (q < p.q) {
             const int n_l = q / p.seg, rem = q % p.seg;
@@ -121,6 +160,12 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_mfma(const ExactParams p)
     if (p.qpad > p.q)
         for (int e = tid; e < KT * (p.qpad - p.q); e += kBlock)
             dYs[(e / (p.qpad - p.q)) * p.qp + p.q + e % (p.qpad - p.q)] = 0.f;
+    // vector staging writes only cells that can hold data: padding columns of the window,
+    // channels beyond C and rows of dY beyond K are zeroed once here
+    if (FAST) {
+        for (int e = tid; e < p.ctch * p.pp; e += kBlock) Xs[e] = 0.f;
+        for (int e = tid; e < KT * p.qp; e += kBlock) dYs[e] = 0.f;
+    }
 
     float4_t acc[NT];
 #pragma unroll
@@ -130,65 +175,185 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_mfma(const ExactParams p)
     const int wt_begin = (int)((long)split * tiles_total / p.splits);
     const int wt_end = (int)((long)(split + 1) * tiles_total / p.splits);
 
-    const int a_row = (wk * 16 + i16) * p.qp;
-    const int steps = p.qpad >> 2;
-
-    for (int wt = wt_begin; wt < wt_end; ++wt) {
-        const int n0 = (wt / p.h_tiles) * p.nti, h0 = (wt % p.h_tiles) * p.ht;
-        __syncthreads();   // everyone is done reading the previous tile (and xoff is written)
-
-        // ---- stage dY[k0..k0+KT, n0..n0+nti, h0..h0+ht, :] ----
-        {
-            const int segv = p.seg / VEC;
-            const int valid = (g.Ho - h0 < p.ht ? g.Ho - h0 : p.ht) * g.Wo;   // elements of the segment inside the map
-            const int total = KT * p.nti * segv;
-            for (int e = tid; e < total; e += kBlock) {
+    // ---- vector modes: this thread's staging slots, decoded once.  No tile is ragged in
+    //      these modes (ht divides Ho, nti divides N), so a slot is either always inside
+    //      the tensors or never; only the input row can fall on padding, tile by tile. ----
+    Vec<BF16, 4> dyr[FAST ? kSlotsDY : 1];
+    Vec<BF16, XVn> xr[FAST ? kSlotsX : 1];
+    int dy_dst[FAST ? kSlotsDY : 1];       // LDS float index, -1 = slot unused
+    uint32_t dy_src[FAST ? kSlotsDY : 1];  // element offset from the tile's first dY element
+    int x_pack[FAST ? kSlotsX : 1];        // LDS float index | ih_l << 20 | valid elements << 28, -1 = unused
+    uint32_t x_src[FAST ? kSlotsX : 1];    // element offset from the tile's first (possibly virtual) X row
+    if (FAST) {
+        const int L = g.Ho * g.Wo;
+        const int dy_total = KT * p.nti * (p.seg >> 2);
+#pragma unroll
+        for (int u = 0; u < kSlotsDY; ++u) {
+            const int e = tid + u * kBlock;
+            dy_dst[u] = -1; dy_src[u] = 0;
+            if (e < dy_total) {
                 uint32_t k_l, rem, n_l, ev;
                 p.d_nsegv.divmod(e, k_l, rem);
                 p.d_segv.divmod(rem, n_l, ev);
-                const int k = k0 + k_l, n = n0 + n_l, el = ev * VEC;
-                float *dst = dYs + k_l * p.qp + n_l * p.seg + el;
-                const bool ok = k < g.K && n < g.N && el < valid;
-                const long src = (((long)n * g.K + k) * g.Ho + h0) * g.Wo + el;
-                if (VEC == 4) {
-                    float4_t v = float4_t{0.f, 0.f, 0.f, 0.f};
-                    if (ok) v = load_vec4<BF16>(p.dY, src);
-                    *(float4_t *)dst = v;
-                } else {
-                    *dst = ok ? load_elem<BF16>(p.dY, src) : 0.f;
+                if (k0 + (int)k_l < g.K) {
+                    dy_dst[u] = k_l * p.qp + n_l * p.seg + ev * 4;
+                    dy_src[u] = (n_l * g.K + k_l) * L + ev * 4;
                 }
             }
         }
-        // ---- stage the input window, zero outside X (padding, ragged edges) ----
-        {
-            const int total = p.ctch * p.plane;
-            const int ih0 = h0 * g.sh - g.ph;
-            for (int e = tid; e < total; e += kBlock) {
-                uint32_t c_l, rem, n_l, rem2, ih_l, iw_l;
-                p.d_plane.divmod(e, c_l, rem);
-                p.d_img.divmod(rem, n_l, rem2);
-                p.d_iwt.divmod(rem2, ih_l, iw_l);
-                const int c = c_first + c_l, n = n0 + n_l, ih = ih0 + (int)ih_l, iw = (int)iw_l - g.pw;
-                float v = 0.f;
-                if (c < g.C && n < g.N && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
-                    v = load_elem<BF16>(p.X, (((long)n * g.C + c) * g.H + ih) * g.W + iw);
-                Xs[c_l * p.pp + rem] = v;
+        const int x_total = p.ctch * p.nti * p.iht * (int)p.d_wv.d;
+#pragma unroll
+        for (int u = 0; u < kSlotsX; ++u) {
+            const int e = tid + u * kBlock;
+            x_pack[u] = -1; x_src[u] = 0;
+            if (e < x_total) {
+                uint32_t row, jv, c_l, rem, n_l, ih_l;
+                p.d_wv.divmod(e, row, jv);
+                p.d_rows.divmod(row, c_l, rem);
+                p.d_iht.divmod(rem, n_l, ih_l);
+                const int col0 = g.pw + jv * XVn;            // window column of the first element
+                int nv = p.iwt - col0;                       // columns right of the window are not staged
+                nv = nv > XVn ? XVn : nv;
+                if (c_first + (int)c_l < g.C && nv > 0) {
+                    x_pack[u] = (int)(c_l * p.pp + rem * p.iwt + col0) | (int)(ih_l << 20) | (nv << 28);
+                    x_src[u] = ((n_l * g.C + c_l) * g.H + ih_l) * g.W + jv * XVn;
+                }
+            }
+        }
+    }
+
+    // issue the global loads of one tile into registers
+    auto prefetch = [&](int wt) {
+        const int n0 = (wt / p.h_tiles) * p.nti, h0 = (wt % p.h_tiles) * p.ht;
+        const long dy_base = (((long)n0 * g.K + k0) * g.Ho + h0) * g.Wo;
+#pragma unroll
+        for (int u = 0; u < kSlotsDY; ++u)
+            if (dy_dst[u] >= 0) dyr[u].load(p.dY, dy_base + dy_src[u]);
+        const int ih0 = h0 * g.sh - g.ph;
+        const long x_base = (((long)n0 * g.C + c_first) * g.H + ih0) * g.W;   // may lie before X: only rows inside X are read
+#pragma unroll
+        for (int u = 0; u < kSlotsX; ++u) {
+            xr[u].zero();
+            const int ih = ih0 + ((x_pack[u] >> 20) & 0xff);
+            if (x_pack[u] >= 0 && ih >= 0 && ih < g.H) xr[u].load(p.X, x_base + x_src[u]);
+        }
+    };
+    // registers -> LDS
+    auto commit = [&]() {
+#pragma unroll
+        for (int u = 0; u < kSlotsDY; ++u)
+            if (dy_dst[u] >= 0) {
+                float4_t v;
+#pragma unroll
+                for (int i = 0; i < 4; ++i) v[i] = dyr[u].get(i);
+                *(float4_t *)(dYs + dy_dst[u]) = v;
+            }
+#pragma unroll
+        for (int u = 0; u < kSlotsX; ++u)
+            if (x_pack[u] >= 0) {
+                float *dst = Xs + (x_pack[u] & 0xfffff);
+                const int nv = x_pack[u] >> 28;
+#pragma unroll
+                for (int i = 0; i < XVn; ++i)
+                    if (i < nv) dst[i] = xr[u].get(i);
+            }
+    };
+
+    // contraction geometry: every wavefront owns spw consecutive steps of 4 positions
+    const int spw = (p.qpad >> 2) / WQ;                // even (qpad is a multiple of 8 * WQ)
+    const float *a_ptr = dYs + (wk * 16 + i16) * p.qp + 4 * wq * spw + kk;
+    const int *xo_ptr = xoff + 4 * wq * spw + kk;
+
+    if (FAST && wt_begin < wt_end) prefetch(wt_begin);
+
+    for (int wt = wt_begin; wt < wt_end; ++wt) {
+        const int n0 = (wt / p.h_tiles) * p.nti, h0 = (wt % p.h_tiles) * p.ht;
+        __syncthreads();   // everyone is done reading the previous tile (and the tables are written)
+
+        if (FAST) {
+            commit();
+        } else {
+            // ---- element-wise staging of dY[k0..k0+KT, n0..n0+nti, h0..h0+ht, :] ----
+            {
+                const int valid = (g.Ho - h0 < p.ht ? g.Ho - h0 : p.ht) * g.Wo;
+                const int total = KT * p.nti * p.seg;
+                for (int e0 = tid; e0 < total; e0 += 4 * kBlock) {
+                    float v[4];
+                    int dst[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int e = e0 + u * kBlock;
+                        v[u] = 0.f; dst[u] = -1;
+                        if (e < total) {
+                            uint32_t k_l, rem, n_l, el;
+                            p.d_nsegv.divmod(e, k_l, rem);
+                            p.d_segv.divmod(rem, n_l, el);
+                            const int k = k0 + k_l, n = n0 + n_l;
+                            dst[u] = k_l * p.qp + n_l * p.seg + el;
+                            if (k < g.K && n < g.N && (int)el < valid)
+                                v[u] = load_elem<BF16>(p.dY, (((long)n * g.K + k) * g.Ho + h0) * g.Wo + el);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (dst[u] >= 0) dYs[dst[u]] = v[u];
+                }
+            }
+            // ---- element-wise staging of the input window, zero outside X ----
+            {
+                const int total = p.ctch * p.plane;
+                const int ih0 = h0 * g.sh - g.ph;
+                for (int e0 = tid; e0 < total; e0 += 4 * kBlock) {
+                    float v[4];
+                    int dst[4];
+#pragma unroll
+                    for (int u = 0; u < 4; ++u) {
+                        const int e = e0 + u * kBlock;
+                        v[u] = 0.f; dst[u] = -1;
+                        if (e < total) {
+                            uint32_t c_l, rem, n_l, rem2, ih_l, iw_l;
+                            p.d_plane.divmod(e, c_l, rem);
+                            p.d_img.divmod(rem, n_l, rem2);
+                            p.d_iwt.divmod(rem2, ih_l, iw_l);
+                            const int c = c_first + c_l, n = n0 + n_l, ih = ih0 + (int)ih_l, iw = (int)iw_l - g.pw;
+                            dst[u] = c_l * p.pp + rem;
+                            if (c < g.C && n < g.N && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
+                                v[u] = load_elem<BF16>(p.X, (((long)n * g.C + c) * g.H + ih) * g.W + iw);
+                        }
+                    }
+#pragma unroll
+                    for (int u = 0; u < 4; ++u)
+                        if (dst[u] >= 0) Xs[dst[u]] = v[u];
+                }
             }
         }
         __syncthreads();
+        if (FAST && wt + 1 < wt_end) prefetch(wt + 1);
 
-        // ---- contract: 4 positions per MFMA step, NT column tiles per A operand ----
-#pragma unroll 2
-        for (int t = wq; t < steps; t += WQ) {
-            const int q = 4 * t + kk;
-            const float a = dYs[a_row + q];
-            const int xo = xoff[q];
-            float b[NT];
+        // ---- contract: 4 positions per MFMA step, NT column tiles per A operand; the operands
+        //      of the next step are read from LDS before the MFMAs of the current one ----
+        {
+            float a0, a1, b0[NT], b1[NT];
+            int xoA = xo_ptr[0], xoB = xo_ptr[4];
+            a0 = a_ptr[0];
 #pragma unroll
-            for (int j = 0; j < NT; ++j) b[j] = Xs[coloff[j] + xo];
+            for (int j = 0; j < NT; ++j) b0[j] = Xs[coloff[j] + xoA];
+            for (int i = 0; i < spw; i += 2) {
+                xoA = xo_ptr[4 * (i + 2)];
+                a1 = a_ptr[4 * (i + 1)];
 #pragma unroll
-            for (int j = 0; j < NT; ++j)
-                acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a, b[j], acc[j], 0, 0, 0);
+                for (int j = 0; j < NT; ++j) b1[j] = Xs[coloff[j] + xoB];
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0[j], acc[j], 0, 0, 0);
+                xoB = xo_ptr[4 * (i + 3)];
+                a0 = a_ptr[4 * (i + 2)];                 // one step past the end on the last trip: read, not used
+#pragma unroll
+                for (int j = 0; j < NT; ++j) b0[j] = Xs[coloff[j] + xoA];
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[j], acc[j], 0, 0, 0);
+            }
         }
     }
 
@@ -211,11 +376,13 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_mfma(const ExactParams p)
         float *out = p.out + (long)split * g.K * CRS;
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-            if (outcol[j] < 0) continue;
+            int lo, oc;
+            column_of<NT>(p, coltile, j, i16, c_first, lo, oc);
+            if (oc < 0) continue;
 #pragma unroll
             for (int v = 0; v < 4; ++v) {
                 const int k = k0 + wk * 16 + 4 * kk + v;
-                if (k < g.K) out[(long)k * CRS + outcol[j]] = acc[j][v];
+                if (k < g.K) out[(long)k * CRS + oc] = acc[j][v];
             }
         }
     }
@@ -240,13 +407,21 @@ static int pitch_mod32(int len, int want, int multiple)
     return p;
 }
 
+static int largest_divisor_at_most(int n, int limit)
+{
+    if (limit >= n) return n;
+    for (int d = limit; d >= 1; --d)
+        if (n % d == 0) return d;
+    return 1;
+}
+
 ExactPlan plan_exact(const Geometry &g)
 {
     ExactPlan pl{};
     const int RS = g.R * g.S;
     const long CRS = g.crs();
     pl.wk = g.K <= 16 ? 1 : (g.K <= 32 ? 2 : 4);
-    const int KT = 16 * pl.wk;
+    const int KT = 16 * pl.wk, WQ = 4 / pl.wk;
     if (g.C % 16 == 0 && RS == 9) { pl.tap_mode = 1; pl.nt = 9; }
     else if (g.C % 64 == 0 && RS == 1) { pl.tap_mode = 1; pl.nt = 4; }
     else {
@@ -264,22 +439,50 @@ ExactPlan plan_exact(const Geometry &g)
         pl.ctch = (cols - 1) / RS + 2;
         if (pl.ctch > g.C) pl.ctch = g.C;
     }
+    // widest access the shape allows when staging X rows (alignment of the pointers is checked at launch)
+    const int xv_shape = g.W % 4 == 0 ? 4 : (g.W % 2 == 0 ? 2 : 0);
 
     const int L = g.Ho * g.Wo;
-    for (int qt = WGRAD_EXACT_KQ / KT; qt >= 4; qt /= 2) {
-        if (L >= qt) { pl.nti = 1; pl.ht = qt / g.Wo < 1 ? 1 : qt / g.Wo; if (pl.ht > g.Ho) pl.ht = g.Ho; }
-        else { pl.ht = g.Ho; pl.nti = qt / L < 1 ? 1 : qt / L; if (pl.nti > g.N) pl.nti = g.N; }
-        pl.q = pl.nti * pl.ht * g.Wo;
-        pl.qpad = (pl.q + 3) / 4 * 4;
-        pl.qp = pitch_mod32(pl.qpad, 4, 4);
-        pl.iht = (pl.ht - 1) * g.sh + g.R;
-        pl.iwt = (g.Wo - 1) * g.sw + g.S;
-        pl.pp = pitch_mod32(pl.nti * pl.iht * pl.iwt, 2, 1);
-        size_t lds = ((size_t)KT * pl.qp + (size_t)pl.ctch * pl.pp + pl.qpad) * 4;
-        const size_t red = (size_t)(4 / pl.wk - 1) * pl.wk * pl.nt * 64 * 16;
-        if (red > lds) lds = red;
-        pl.lds_bytes = lds;
-        if (lds <= kMaxLds) { pl.ok = true; break; }
+    // pass 0 looks for the largest tile that fits LDS and the register pipeline of the vector
+    // staging path (no ragged tiles: rows per tile divide Ho, images per tile divide N);
+    // pass 1 (element-wise staging) only needs the tile to fit LDS
+    for (int pass = 0; pass < 2 && !pl.ok; ++pass) {
+        if (pass == 0 && (!xv_shape || L % 4 != 0)) continue;
+        for (int qt = WGRAD_EXACT_KQ / KT; qt >= 4; qt /= 2) {
+            if (L >= qt) {
+                pl.nti = 1;
+                pl.ht = qt / g.Wo < 1 ? 1 : qt / g.Wo;
+                pl.ht = pass == 0 ? largest_divisor_at_most(g.Ho, pl.ht) : (pl.ht > g.Ho ? g.Ho : pl.ht);
+            } else {
+                pl.ht = g.Ho;
+                pl.nti = qt / L < 1 ? 1 : qt / L;
+                pl.nti = pass == 0 ? largest_divisor_at_most(g.N, pl.nti) : (pl.nti > g.N ? g.N : pl.nti);
+            }
+            pl.q = pl.nti * pl.ht * g.Wo;
+            pl.qpad = (pl.q + 8 * WQ - 1) / (8 * WQ) * (8 * WQ);    // an even number of 4-position steps per wavefront
+            pl.qp = pitch_mod32(pl.qpad, 4, 4);
+            pl.iht = (pl.ht - 1) * g.sh + g.R;
+            pl.iwt = (g.Wo - 1) * g.sw + g.S;
+            pl.pp = pitch_mod32(pl.nti * pl.iht * pl.iwt, 2, 1);
+            size_t lds = ((size_t)KT * pl.qp + (size_t)pl.ctch * pl.pp + pl.qpad + 8) * 4;
+            const size_t red = (size_t)(WQ - 1) * pl.wk * pl.nt * 64 * 16;
+            if (red > lds) lds = red;
+            pl.lds_bytes = lds;
+            if (lds > kMaxLds) continue;
+            pl.xv = 0;
+            if (pass == 0) {
+                const int seg = pl.ht * g.Wo;
+                const long dy_slots = (long)KT * pl.nti * (seg / 4);
+                const long x_slots = (long)pl.ctch * pl.nti * pl.iht * (g.W / xv_shape);
+                const bool fits = seg % 4 == 0 && dy_slots <= kSlotsDY * kBlock && x_slots <= kSlotsX * kBlock
+                                  && pl.iht <= 255 && (long)pl.ctch * pl.pp < (1 << 20)
+                                  && (long)pl.nti * g.K * L < (1l << 31) && (long)pl.nti * g.C * g.H * g.W < (1l << 31);
+                if (!fits) continue;
+                pl.xv = xv_shape;
+            }
+            pl.ok = true;
+            break;
+        }
     }
     if (!pl.ok) return pl;
     // fast-division bounds: dividend * divisor < 2^32
@@ -294,33 +497,36 @@ ExactPlan plan_exact(const Geometry &g)
     if (splits > tiles) splits = tiles;
     if (splits < 1) splits = 1;
     pl.splits = (int)splits;
-
-    const int seg = pl.ht * g.Wo;
-    const bool tail = g.Ho % pl.ht != 0;
-    pl.vec = (seg % 4 == 0 && L % 4 == 0 && (!tail || g.Wo % 4 == 0)) ? 4 : 1;
     pl.ws_bytes = pl.splits > 1 ? align_up((size_t)pl.splits * g.dw_elems() * 4) : 0;
     return pl;
 }
 
-template <int NT, int WK, bool BF16, int VEC>
+template <int NT, int WK, bool BF16, int XV>
 static void launch_inst(const ExactParams &p, int grid, size_t lds, hipStream_t st)
 {
-    WGRAD_LAUNCH((wgrad_exact_mfma<NT, WK, BF16, VEC>), dim3(grid), dim3(kBlock), lds, st, p);
+    WGRAD_LAUNCH((wgrad_exact_mfma<NT, WK, BF16, XV>), dim3(grid), dim3(kBlock), lds, st, p);
 }
 
 template <int NT, int WK>
-static void launch_dtype(const ExactParams &p, int grid, size_t lds, int vec, hipStream_t st)
+static void launch_dtype(const ExactParams &p, int grid, size_t lds, int xv, hipStream_t st)
 {
-    if (p.g.bf16) { if (vec == 4) launch_inst<NT, WK, true, 4>(p, grid, lds, st); else launch_inst<NT, WK, true, 1>(p, grid, lds, st); }
-    else          { if (vec == 4) launch_inst<NT, WK, false, 4>(p, grid, lds, st); else launch_inst<NT, WK, false, 1>(p, grid, lds, st); }
+    if (p.g.bf16) {
+        if (xv == 4) launch_inst<NT, WK, true, 4>(p, grid, lds, st);
+        else if (xv == 2) launch_inst<NT, WK, true, 2>(p, grid, lds, st);
+        else launch_inst<NT, WK, true, 0>(p, grid, lds, st);
+    } else {
+        if (xv == 4) launch_inst<NT, WK, false, 4>(p, grid, lds, st);
+        else if (xv == 2) launch_inst<NT, WK, false, 2>(p, grid, lds, st);
+        else launch_inst<NT, WK, false, 0>(p, grid, lds, st);
+    }
 }
 
 template <int NT>
-static void launch_wk(const ExactParams &p, int wk, int grid, size_t lds, int vec, hipStream_t st)
+static void launch_wk(const ExactParams &p, int wk, int grid, size_t lds, int xv, hipStream_t st)
 {
-    if (wk == 1) launch_dtype<NT, 1>(p, grid, lds, vec, st);
-    else if (wk == 2) launch_dtype<NT, 2>(p, grid, lds, vec, st);
-    else launch_dtype<NT, 4>(p, grid, lds, vec, st);
+    if (wk == 1) launch_dtype<NT, 1>(p, grid, lds, xv, st);
+    else if (wk == 2) launch_dtype<NT, 2>(p, grid, lds, xv, st);
+    else launch_dtype<NT, 4>(p, grid, lds, xv, st);
 }
 
 int launch_exact(const Geometry &g, const ExactPlan &pl, const void *X, const void *dY, float *dW,
@@ -336,20 +542,25 @@ int launch_exact(const Geometry &g, const ExactPlan &pl, const void *X, const vo
     p.h_tiles = pl.h_tiles; p.n_groups = pl.n_groups;
     p.seg = pl.ht * g.Wo;
     p.plane = pl.nti * pl.iht * pl.iwt;
-    // the 16-byte dY staging path also needs 16-byte aligned tensors
-    int vec = pl.vec;
-    if (vec == 4 && ((uintptr_t)dY % (g.bf16 ? 8 : 16)) != 0) vec = 1;
-    p.d_segv = FastDiv(p.seg / vec);
-    p.d_nsegv = FastDiv(pl.nti * (p.seg / vec));
+    // the vector staging path needs every access aligned: X to xv elements, dY to 4 elements
+    const int esz = g.bf16 ? 2 : 4;
+    int xv = pl.xv;
+    if (xv && (((uintptr_t)dY % (4 * esz)) != 0 || ((uintptr_t)X % (xv * esz)) != 0)) xv = 0;
+    const int dv = xv ? 4 : 1;
+    p.d_segv = FastDiv(p.seg / dv);
+    p.d_nsegv = FastDiv(pl.nti * (p.seg / dv));
     p.d_plane = FastDiv(p.plane);
     p.d_img = FastDiv(pl.iht * pl.iwt);
     p.d_iwt = FastDiv(pl.iwt);
+    p.d_wv = FastDiv(xv ? g.W / xv : 1);
+    p.d_rows = FastDiv(pl.nti * pl.iht);
+    p.d_iht = FastDiv(pl.iht);
 
     const int grid = pl.ktiles * pl.ctiles * pl.splits;
     switch (pl.nt) {
-        case 2: launch_wk<2>(p, pl.wk, grid, pl.lds_bytes, vec, st); break;
-        case 4: launch_wk<4>(p, pl.wk, grid, pl.lds_bytes, vec, st); break;
-        default: launch_wk<9>(p, pl.wk, grid, pl.lds_bytes, vec, st); break;
+        case 2: launch_wk<2>(p, pl.wk, grid, pl.lds_bytes, xv, st); break;
+        case 4: launch_wk<4>(p, pl.wk, grid, pl.lds_bytes, xv, st); break;
+        default: launch_wk<9>(p, pl.wk, grid, pl.lds_bytes, xv, st); break;
     }
     int rc = launch_status();
     if (rc != WGRAD_OK) return rc;

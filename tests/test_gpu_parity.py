@@ -27,6 +27,9 @@ SMALL = [
     (1, 1, 1, 1, 1, 1, 1, 1, 1, 0, 0),          # degenerate: a single multiply
     (2, 2, 3, 40, 3, 3, 3, 1, 1, 1, 1),         # wide and flat
     (130, 16, 8, 8, 16, 3, 3, 1, 1, 1, 1),      # long batch, many reduction splits
+    (6, 80, 4, 4, 260, 3, 3, 1, 1, 1, 1),       # many output channels on tiny planes (LDS gather, ragged tiles)
+    (5, 32, 8, 8, 64, 3, 3, 2, 2, 1, 1),        # stride 2 on small planes
+    (40, 64, 2, 2, 512, 3, 3, 1, 1, 1, 1),      # 2x2 planes: most taps fall on padding
 ]
 
 
@@ -101,6 +104,28 @@ def test_zero_dY_gives_exact_zero_and_one_hot_maps_make_approx_equal_exact():
     ex = B.conv_wgrad_exact(d, Xg, og).cpu().numpy()
     ap = B.conv_wgrad_approx(d, Xg, og).cpu().numpy()
     assert normwise_err(ap, ex.astype(np.float64)) <= 1e-5
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("t", [SMALL[0], SMALL[5], SMALL[9]])
+def test_tensors_that_are_only_element_aligned(t, dtype):
+    """X and dY start one element into their allocations: the 16-byte paths must not be taken."""
+    import torch
+    d = mk(t, dtype)
+    X, dY = rand_inputs(d, 77, dtype)
+
+    def shifted(a):
+        flat = to_gpu(np.concatenate([a.ravel()[:1], a.ravel()]))
+        return flat[1:].view(a.shape)
+    Xg, dYg = shifted(X), shifted(dY)
+    assert Xg.data_ptr() % 16 != 0 and Xg.is_contiguous()
+    g = oracle_shape(d)
+    assert normwise_err(B.conv_wgrad_exact(d, Xg, dYg).cpu().numpy(), oracle.wgrad_exact(g, X, dY)) <= TOL[dtype]
+    idx = torch.empty((d.N, d.K), dtype=torch.int32, device="cuda")
+    S = torch.empty((d.N, d.K), dtype=torch.float32, device="cuda")
+    got = B.conv_wgrad_approx(d, Xg, dYg, idx_out=idx, sum_out=S).cpu().numpy()
+    check_select(d, dY, idx.cpu().numpy(), S.cpu().numpy())
+    assert normwise_err(got, oracle.wgrad_approx(g, X, dY)[0]) <= TOL[dtype]
 
 
 # ---- selection: ties and degenerate maps, bit-exact -------------------------------------
