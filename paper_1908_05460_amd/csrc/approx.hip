@@ -349,11 +349,12 @@ ApproxPlan plan_approx(const Geometry &g, bool allow_lds)
         pl.ctiles = (g.C + kGatherCT - 1) / kGatherCT;
         pl.ktiles = (g.K + 4 * pl.m - 1) / (4 * pl.m);
         const long tiles = (long)pl.ctiles * pl.ktiles;
-        chunks = tiles >= WGRAD_GATHER_BLOCKS ? 1 : (WGRAD_GATHER_BLOCKS + tiles - 1) / tiles;
+        const int want_blocks = tune_int("WGRAD_GATHER_BLOCKS", WGRAD_GATHER_BLOCKS);
+        chunks = tiles >= want_blocks ? 1 : (want_blocks + tiles - 1) / tiles;
         const long max_chunks = (g.N + pl.nb - 1) / pl.nb;
         if (chunks > max_chunks) chunks = max_chunks;
     } else {
-        chunks = (WGRAD_APPROX_THREADS + outs - 1) / outs;
+        chunks = (tune_int("WGRAD_APPROX_THREADS", WGRAD_APPROX_THREADS) + outs - 1) / outs;
         if (chunks > g.N) chunks = g.N;
     }
     if (chunks < 1) chunks = 1;

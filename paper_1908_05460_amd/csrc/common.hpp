@@ -2,6 +2,7 @@
 #pragma once
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
 #include "wgrad.h"
 
@@ -33,6 +34,18 @@ struct Geometry {                    // validated convolution geometry
     __host__ __device__ long crs() const { return (long)C * R * S; }
     __host__ __device__ long dw_elems() const { return (long)K * C * R * S; }
 };
+
+// Tuning knob: a compile-time default; builds with -DWGRAD_TUNING (development sweeps only,
+// never the product build) let an environment variable of the same name override it.
+inline int tune_int(const char *name, int dflt)
+{
+#ifdef WGRAD_TUNING
+    if (const char *v = getenv(name)) return atoi(v);
+#else
+    (void)name;
+#endif
+    return dflt;
+}
 
 inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
 

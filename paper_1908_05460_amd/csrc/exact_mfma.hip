@@ -30,8 +30,18 @@ namespace wgrad {
 
 typedef float float4_t __attribute__((ext_vector_type(4)));
 
-constexpr int kSlotsDY = 8;     // 16-byte global loads of dY per thread and tile
-constexpr int kSlotsX = 4;      // 16- or 8-byte global loads of X per thread and tile
+#ifdef WGRAD_TUNING   // development builds only: phase timestamps of one workgroup
+__device__ long long g_trace[64];
+#define TRACE(i) do { if (blockIdx.x == TRACE_BLOCK && threadIdx.x == 0) { g_trace[i] = wall_clock64(); g_trace[32 + i] = clock64(); } } while (0)
+#define TRACE_BLOCK 37
+#else
+#define TRACE(i) do { } while (0)
+#endif
+
+// Staging slots per thread and tile (16-byte loads of dY; 16- or 8-byte loads of X).  Narrow K
+// tiles have few dY rows but the same input window, so they trade dY slots for X slots.
+__host__ __device__ constexpr int slots_dy(int wk) { return wk == 1 ? 4 : 8; }
+__host__ __device__ constexpr int slots_x(int wk) { return wk == 4 ? 4 : 6; }
 
 struct ExactParams {
     const void *X, *dY;
@@ -44,6 +54,9 @@ struct ExactParams {
     FastDiv d_segv, d_nsegv;    // dY staging: vectors per segment, per channel row
     FastDiv d_plane, d_img, d_iwt;   // X staging, element-wise mode
     FastDiv d_wv, d_rows, d_iht;     // X staging, vector modes: vectors per row, rows per channel, rows per image
+    FastDiv d_rs, d_s, d_seg, d_wo, d_htiles;
+    // tap mode, per MFMA column tile: first channel (relative to the block's), LDS offset of the tap, tap index
+    int tile_c0[9], tile_toff[9], tile_tap[9];
 };
 
 template <bool BF16>
@@ -53,24 +66,21 @@ __device__ __forceinline__ float load_elem(const void *p, long i)
     return ((const float *)p)[i];
 }
 
-// V consecutive elements starting at element i (aligned to V elements), widened to fp32.
+// V consecutive elements at a uniform base pointer plus a per-lane byte offset, widened to fp32 on use.
 template <bool BF16, int V> struct Vec;
 template <> struct Vec<false, 4> {
     float4_t r;
-    __device__ __forceinline__ void load(const void *p, long i) { r = *(const float4_t *)((const float *)p + i); }
-    __device__ __forceinline__ void zero() { r = float4_t{0.f, 0.f, 0.f, 0.f}; }
+    __device__ __forceinline__ void load(const char *base, uint32_t off) { r = *(const float4_t *)(base + off); }
     __device__ __forceinline__ float get(int u) const { return r[u]; }
 };
 template <> struct Vec<false, 2> {
     float2 r;
-    __device__ __forceinline__ void load(const void *p, long i) { r = *(const float2 *)((const float *)p + i); }
-    __device__ __forceinline__ void zero() { r = make_float2(0.f, 0.f); }
+    __device__ __forceinline__ void load(const char *base, uint32_t off) { r = *(const float2 *)(base + off); }
     __device__ __forceinline__ float get(int u) const { return u == 0 ? r.x : r.y; }
 };
 template <> struct Vec<true, 4> {
     uint2 r;
-    __device__ __forceinline__ void load(const void *p, long i) { r = *(const uint2 *)((const uint16_t *)p + i); }
-    __device__ __forceinline__ void zero() { r = make_uint2(0u, 0u); }
+    __device__ __forceinline__ void load(const char *base, uint32_t off) { r = *(const uint2 *)(base + off); }
     __device__ __forceinline__ float get(int u) const {
         const uint32_t w = u < 2 ? r.x : r.y;
         return __uint_as_float((u & 1) ? (w & 0xffff0000u) : (w << 16));
@@ -78,37 +88,45 @@ template <> struct Vec<true, 4> {
 };
 template <> struct Vec<true, 2> {
     uint32_t r;
-    __device__ __forceinline__ void load(const void *p, long i) { r = *(const uint32_t *)((const uint16_t *)p + i); }
-    __device__ __forceinline__ void zero() { r = 0u; }
+    __device__ __forceinline__ void load(const char *base, uint32_t off) { r = *(const uint32_t *)(base + off); }
     __device__ __forceinline__ float get(int u) const { return __uint_as_float(u ? (r & 0xffff0000u) : (r << 16)); }
 };
 
 // Column mapping of MFMA column tile t for lane column i16.  tap_mode: the tile covers 16
-// consecutive channels at one filter tap (bank-conflict-free operand reads); otherwise 16
-// consecutive flat columns c*R*S + r*S + s (any C, R, S).  Returns the LDS offset of the
-// column inside the staged window (0 for a padding column) and its flat output column
-// (-1 for a padding column).
+// consecutive channels at one filter tap (bank-conflict-free operand reads; the per-tile
+// constants come precomputed from the host); otherwise 16 consecutive flat columns
+// c*R*S + r*S + s (any C, R, S).  Returns the LDS offset of the column inside the staged
+// window (0 for a padding column) and the column's index local to the workgroup, in
+// output order (-1 for a padding column).
 template <int NT>
 __device__ __forceinline__ void column_of(const ExactParams &p, int coltile, int t, int i16, int c_first,
-                                          int &lds_off, int &out_col)
+                                          int &lds_off, int &local_col)
 {
     const Geometry &g = p.g;
     const int RS = g.R * g.S;
-    int c, tap;
-    bool ok;
     if (p.tap_mode) {
-        c = c_first + (t / RS) * 16 + i16;
-        tap = t % RS;
-        ok = c < g.C;
+        const int c_l = p.tile_c0[t] + i16;
+        const bool ok = c_first + c_l < g.C;
+        lds_off = ok ? c_l * p.pp + p.tile_toff[t] : 0;
+        local_col = ok ? c_l * RS + p.tile_tap[t] : -1;
     } else {
         const int col = coltile * NT * 16 + t * 16 + i16;
-        ok = col < g.C * RS;
-        c = col / RS;
-        tap = col % RS;
+        const bool ok = col < g.C * RS;
+        uint32_t c, tap, r, s;
+        p.d_rs.divmod(col, c, tap);
+        p.d_s.divmod(tap, r, s);
+        lds_off = ok ? (int)((c - c_first) * p.pp + r * p.iwt + s) : 0;
+        local_col = ok ? t * 16 + i16 : -1;
     }
-    lds_off = ok ? (c - c_first) * p.pp + (tap / g.S) * p.iwt + tap % g.S : 0;
-    out_col = ok ? c * RS + tap : -1;
 }
+
+// One tile's staging registers (vector modes).
+template <bool BF16, int XV, int DS, int XS>
+struct Stage {
+    Vec<BF16, 4> dy[DS];
+    Vec<BF16, XV> x[XS];
+    uint32_t row_ok;            // bit u: the input row of X slot u lies inside X for this tile
+};
 
 // NT: 16-column MFMA tiles per wavefront; WK: wavefronts along K (tile of 16*WK output
 // channels), the other 4/WK wavefronts split the staged positions.  XV: elements per
@@ -121,10 +139,14 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_mfma(const ExactParams p)
     constexpr int KT = 16 * WK, WQ = 4 / WK;
     constexpr bool FAST = XV != 0;
     constexpr int XVn = FAST ? XV : 2;                  // placeholder width for the unused registers
+    constexpr int ESZ = BF16 ? 2 : 4;                   // bytes per input element
+    constexpr int NCB = NT * 16;                        // columns of the workgroup's output tile
+    constexpr int kSlotsDY = slots_dy(WK), kSlotsX = slots_x(WK);
+    typedef Stage<BF16, XVn, kSlotsDY, kSlotsX> StageT;
     extern __shared__ float smem[];
     float *dYs = smem;                              // [KT][qp]
     float *Xs = dYs + KT * p.qp;                    // [ctch][pp]
-    int *xoff = (int *)(Xs + p.ctch * p.pp);        // [qpad]
+    int *xoff = (int *)(Xs + p.ctch * p.pp);        // [qpad + 16]
 
     const Geometry &g = p.g;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -139,34 +161,41 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_mfma(const ExactParams p)
     const int k0 = ktile * KT;
     const int c_first = p.tap_mode ? coltile * 16 * (NT / RS) : (coltile * NT * 16) / RS;
 
+    TRACE(0);
     int coloff[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) {
-        int oc;
-        column_of<NT>(p, coltile, t, i16, c_first, coloff[t], oc);
+        int lc;
+        column_of<NT>(p, coltile, t, i16, c_first, coloff[t], lc);
     }
 
+    TRACE(11);
     // Offset of staged position q inside a staged input channel (constant for the kernel);
-    // 8 spare entries let the contraction loop read two steps ahead.
-    for (int q = tid; q < p.qpad + 8; q += kBlock) {
+    // 16 spare entries let the contraction loop read up to three steps ahead.
+    for (int q = tid; q < p.qpad + 16; q += kBlock) {
         int off = 0;
         if (q < p.q) {
-            const int n_l = q / p.seg, rem = q % p.seg;
-            off = n_l * p.iht * p.iwt + (rem / g.Wo) * g.sh * p.iwt + (rem % g.Wo) * g.sw;
+            uint32_t n_l, rem, h_l, w;
+            p.d_seg.divmod(q, n_l, rem);
+            p.d_wo.divmod(rem, h_l, w);
+            off = n_l * p.iht * p.iwt + h_l * g.sh * p.iwt + w * g.sw;
         }
         xoff[q] = off;
     }
-    // dY columns q..qpad of every row are never staged: they must read as zero.
-    if (p.qpad > p.q)
+    TRACE(12);
+    if (FAST) {
+        // vector staging writes only cells that hold data: padding columns of the window,
+        // channels beyond C, rows of dY beyond K and positions q..qpad are zeroed once here
+        const int zn = KT * p.qp + p.ctch * p.pp;
+        for (int e = tid; e < (zn >> 2); e += kBlock) ((float4_t *)smem)[e] = float4_t{0.f, 0.f, 0.f, 0.f};
+        if (tid < (zn & 3)) smem[(zn & ~3) + tid] = 0.f;
+    } else if (p.qpad > p.q) {
+        // dY columns q..qpad of every row are never staged: they must read as zero
         for (int e = tid; e < KT * (p.qpad - p.q); e += kBlock)
             dYs[(e / (p.qpad - p.q)) * p.qp + p.q + e % (p.qpad - p.q)] = 0.f;
-    // vector staging writes only cells that can hold data: padding columns of the window,
-    // channels beyond C and rows of dY beyond K are zeroed once here
-    if (FAST) {
-        for (int e = tid; e < p.ctch * p.pp; e += kBlock) Xs[e] = 0.f;
-        for (int e = tid; e < KT * p.qp; e += kBlock) dYs[e] = 0.f;
     }
 
+    TRACE(13);
     float4_t acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -175,104 +204,162 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_mfma(const ExactParams p)
     const int wt_begin = (int)((long)split * tiles_total / p.splits);
     const int wt_end = (int)((long)(split + 1) * tiles_total / p.splits);
 
-    // ---- vector modes: this thread's staging slots, decoded once.  No tile is ragged in
-    //      these modes (ht divides Ho, nti divides N), so a slot is either always inside
-    //      the tensors or never; only the input row can fall on padding, tile by tile. ----
-    Vec<BF16, 4> dyr[FAST ? kSlotsDY : 1];
-    Vec<BF16, XVn> xr[FAST ? kSlotsX : 1];
-    int dy_dst[FAST ? kSlotsDY : 1];       // LDS float index, -1 = slot unused
-    uint32_t dy_src[FAST ? kSlotsDY : 1];  // element offset from the tile's first dY element
-    int x_pack[FAST ? kSlotsX : 1];        // LDS float index | ih_l << 20 | valid elements << 28, -1 = unused
-    uint32_t x_src[FAST ? kSlotsX : 1];    // element offset from the tile's first (possibly virtual) X row
-    if (FAST) {
-        const int L = g.Ho * g.Wo;
-        const int dy_total = KT * p.nti * (p.seg >> 2);
-#pragma unroll
-        for (int u = 0; u < kSlotsDY; ++u) {
-            const int e = tid + u * kBlock;
-            dy_dst[u] = -1; dy_src[u] = 0;
-            if (e < dy_total) {
-                uint32_t k_l, rem, n_l, ev;
-                p.d_nsegv.divmod(e, k_l, rem);
-                p.d_segv.divmod(rem, n_l, ev);
-                if (k0 + (int)k_l < g.K) {
-                    dy_dst[u] = k_l * p.qp + n_l * p.seg + ev * 4;
-                    dy_src[u] = (n_l * g.K + k_l) * L + ev * 4;
-                }
-            }
-        }
-        const int x_total = p.ctch * p.nti * p.iht * (int)p.d_wv.d;
-#pragma unroll
-        for (int u = 0; u < kSlotsX; ++u) {
-            const int e = tid + u * kBlock;
-            x_pack[u] = -1; x_src[u] = 0;
-            if (e < x_total) {
-                uint32_t row, jv, c_l, rem, n_l, ih_l;
-                p.d_wv.divmod(e, row, jv);
-                p.d_rows.divmod(row, c_l, rem);
-                p.d_iht.divmod(rem, n_l, ih_l);
-                const int col0 = g.pw + jv * XVn;            // window column of the first element
-                int nv = p.iwt - col0;                       // columns right of the window are not staged
-                nv = nv > XVn ? XVn : nv;
-                if (c_first + (int)c_l < g.C && nv > 0) {
-                    x_pack[u] = (int)(c_l * p.pp + rem * p.iwt + col0) | (int)(ih_l << 20) | (nv << 28);
-                    x_src[u] = ((n_l * g.C + c_l) * g.H + ih_l) * g.W + jv * XVn;
-                }
-            }
-        }
-    }
-
-    // issue the global loads of one tile into registers
-    auto prefetch = [&](int wt) {
-        const int n0 = (wt / p.h_tiles) * p.nti, h0 = (wt % p.h_tiles) * p.ht;
-        const long dy_base = (((long)n0 * g.K + k0) * g.Ho + h0) * g.Wo;
-#pragma unroll
-        for (int u = 0; u < kSlotsDY; ++u)
-            if (dy_dst[u] >= 0) dyr[u].load(p.dY, dy_base + dy_src[u]);
-        const int ih0 = h0 * g.sh - g.ph;
-        const long x_base = (((long)n0 * g.C + c_first) * g.H + ih0) * g.W;   // may lie before X: only rows inside X are read
-#pragma unroll
-        for (int u = 0; u < kSlotsX; ++u) {
-            xr[u].zero();
-            const int ih = ih0 + ((x_pack[u] >> 20) & 0xff);
-            if (x_pack[u] >= 0 && ih >= 0 && ih < g.H) xr[u].load(p.X, x_base + x_src[u]);
-        }
-    };
-    // registers -> LDS
-    auto commit = [&]() {
-#pragma unroll
-        for (int u = 0; u < kSlotsDY; ++u)
-            if (dy_dst[u] >= 0) {
-                float4_t v;
-#pragma unroll
-                for (int i = 0; i < 4; ++i) v[i] = dyr[u].get(i);
-                *(float4_t *)(dYs + dy_dst[u]) = v;
-            }
-#pragma unroll
-        for (int u = 0; u < kSlotsX; ++u)
-            if (x_pack[u] >= 0) {
-                float *dst = Xs + (x_pack[u] & 0xfffff);
-                const int nv = x_pack[u] >> 28;
-#pragma unroll
-                for (int i = 0; i < XVn; ++i)
-                    if (i < nv) dst[i] = xr[u].get(i);
-            }
-    };
-
-    // contraction geometry: every wavefront owns spw consecutive steps of 4 positions
+    // contraction: every wavefront owns spw consecutive steps of 4 positions; the operands of
+    // the next step are read from LDS before the MFMAs of the current one are issued
     const int spw = (p.qpad >> 2) / WQ;                // even (qpad is a multiple of 8 * WQ)
     const float *a_ptr = dYs + (wk * 16 + i16) * p.qp + 4 * wq * spw + kk;
     const int *xo_ptr = xoff + 4 * wq * spw + kk;
+    auto contract = [&]() {
+        float a0, a1, b0[NT], b1[NT];
+        int xoA = xo_ptr[0], xoB = xo_ptr[4];
+        a0 = a_ptr[0];
+#pragma unroll
+        for (int j = 0; j < NT; ++j) b0[j] = Xs[coloff[j] + xoA];
+        xoA = xo_ptr[8];
+        for (int i = 0; i < spw; i += 2) {
+            // the scheduling barriers keep the order written here: LDS reads of the next step are
+            // issued, then the MFMAs of the current step run while those reads are in flight
+            a1 = a_ptr[4 * (i + 1)];
+#pragma unroll
+            for (int j = 0; j < NT; ++j) b1[j] = Xs[coloff[j] + xoB];
+            xoB = xo_ptr[4 * (i + 3)];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0[j], acc[j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            a0 = a_ptr[4 * (i + 2)];                 // one step past the end on the last trip: read, not used
+#pragma unroll
+            for (int j = 0; j < NT; ++j) b0[j] = Xs[coloff[j] + xoA];
+            xoA = xo_ptr[4 * (i + 4)];
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int j = 0; j < NT; ++j)
+                acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[j], acc[j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
 
-    if (FAST && wt_begin < wt_end) prefetch(wt_begin);
+    if (FAST) {
+        // ---- this thread's staging slots, decoded once.  No tile is ragged in these modes (ht
+        //      divides Ho, nti divides N), so a slot is either always inside the tensors or
+        //      never; only the input row can fall on padding, tile by tile.  Every slot always
+        //      loads (unused ones re-read the tile's first element, padding rows a clamped row),
+        //      so the number of loads in flight is fixed and a tile can be waited for while the
+        //      next one is still arriving. ----
+        int dy_dst[kSlotsDY];        // LDS float index, -1 = slot unused
+        uint32_t dy_src[kSlotsDY];   // byte offset from the tile's first dY element
+        int x_pack[kSlotsX];         // LDS float index | ih_l << 20 | valid elements << 28, -1 = unused
+        uint32_t x_src[kSlotsX];     // byte offset from row 0 of the tile's first (image, channel)
+        {
+            const int L = g.Ho * g.Wo;
+            const int dy_total = KT * p.nti * (p.seg >> 2);
+#pragma unroll
+            for (int u = 0; u < kSlotsDY; ++u) {
+                const int e = tid + u * kBlock;
+                dy_dst[u] = -1; dy_src[u] = 0;
+                if (e < dy_total) {
+                    uint32_t k_l, rem, n_l, ev;
+                    p.d_nsegv.divmod(e, k_l, rem);
+                    p.d_segv.divmod(rem, n_l, ev);
+                    if (k0 + (int)k_l < g.K) {
+                        dy_dst[u] = k_l * p.qp + n_l * p.seg + ev * 4;
+                        dy_src[u] = ((n_l * g.K + k_l) * L + ev * 4) * ESZ;
+                    }
+                }
+            }
+            const int x_total = p.ctch * p.nti * p.iht * (int)p.d_wv.d;
+#pragma unroll
+            for (int u = 0; u < kSlotsX; ++u) {
+                const int e = tid + u * kBlock;
+                x_pack[u] = -1; x_src[u] = 0;
+                if (e < x_total) {
+                    uint32_t row, jv, c_l, rem, n_l, ih_l;
+                    p.d_wv.divmod(e, row, jv);
+                    p.d_rows.divmod(row, c_l, rem);
+                    p.d_iht.divmod(rem, n_l, ih_l);
+                    const int col0 = g.pw + jv * XVn;            // window column of the first element
+                    int nv = p.iwt - col0;                       // columns right of the window are not staged
+                    nv = nv > XVn ? XVn : nv;
+                    if (c_first + (int)c_l < g.C && nv > 0) {
+                        x_pack[u] = (int)(c_l * p.pp + rem * p.iwt + col0) | (int)(ih_l << 20) | (nv << 28);
+                        x_src[u] = ((n_l * g.C + c_l) * (g.H * g.W) + jv * XVn) * ESZ;
+                    }
+                }
+            }
+        }
+        // issue the global loads of tile wt into a register stage
+        auto prefetch = [&](int wt, StageT &st) {
+            uint32_t ng, hti;
+            p.d_htiles.divmod(wt, ng, hti);
+            const int n0 = ng * p.nti, h0 = hti * p.ht;
+            // uniform tile origins: the loads below are scalar base + 32-bit lane offset
+            const char *dy_base = (const char *)p.dY + (((long)n0 * g.K + k0) * g.Ho + h0) * g.Wo * ESZ;
+#pragma unroll
+            for (int u = 0; u < kSlotsDY; ++u) st.dy[u].load(dy_base, dy_src[u]);
+            const int ih0 = h0 * g.sh - g.ph;
+            const char *x_base = (const char *)p.X + ((long)n0 * g.C + c_first) * g.H * g.W * ESZ;
+            st.row_ok = 0;
+#pragma unroll
+            for (int u = 0; u < kSlotsX; ++u) {
+                int ih = ih0 + ((x_pack[u] >> 20) & 0xff);
+                if (ih >= 0 && ih < g.H) st.row_ok |= 1u << u;
+                ih = ih < 0 ? 0 : (ih >= g.H ? g.H - 1 : ih);
+                st.x[u].load(x_base, x_src[u] + ih * (g.W * ESZ));
+            }
+        };
+        // register stage -> LDS
+        auto commit = [&](const StageT &st) {
+#pragma unroll
+            for (int u = 0; u < kSlotsDY; ++u)
+                if (dy_dst[u] >= 0) {
+                    float4_t v;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) v[i] = st.dy[u].get(i);
+                    *(float4_t *)(dYs + dy_dst[u]) = v;
+                }
+#pragma unroll
+            for (int u = 0; u < kSlotsX; ++u)
+                if (x_pack[u] >= 0) {
+                    float *dst = Xs + (x_pack[u] & 0xfffff);
+                    const int nv = x_pack[u] >> 28;
+                    const bool ok = (st.row_ok >> u) & 1;
+#pragma unroll
+                    for (int i = 0; i < XVn; ++i)
+                        if (i < nv) dst[i] = ok ? st.x[u].get(i) : 0.f;
+                }
+        };
 
-    for (int wt = wt_begin; wt < wt_end; ++wt) {
-        const int n0 = (wt / p.h_tiles) * p.nti, h0 = (wt % p.h_tiles) * p.ht;
-        __syncthreads();   // everyone is done reading the previous tile (and the tables are written)
-
-        if (FAST) {
-            commit();
-        } else {
+        // two register stages: tiles wt and wt+1 are in flight while tile wt-1 is contracted
+        StageT sa, sb;
+        TRACE(1);
+        if (wt_begin < wt_end) prefetch(wt_begin, sa);
+        if (wt_begin + 1 < wt_end) prefetch(wt_begin + 1, sb);
+        TRACE(2);
+        for (int wt = wt_begin; wt < wt_end; wt += 2) {
+            __syncthreads();   // everyone is done reading the previous tile (and the tables are written)
+            if (wt == wt_begin) TRACE(3);
+            commit(sa);
+            __syncthreads();
+            if (wt == wt_begin) TRACE(4);
+            if (wt + 2 < wt_end) prefetch(wt + 2, sa);
+            contract();
+            if (wt == wt_begin) TRACE(5);
+            if (wt + 1 < wt_end) {
+                __syncthreads();
+                commit(sb);
+                __syncthreads();
+                if (wt == wt_begin) TRACE(6);
+                if (wt + 3 < wt_end) prefetch(wt + 3, sb);
+                contract();
+                if (wt == wt_begin) TRACE(7);
+            }
+        }
+        TRACE(8);
+    } else {
+        for (int wt = wt_begin; wt < wt_end; ++wt) {
+            const int n0 = (wt / p.h_tiles) * p.nti, h0 = (wt % p.h_tiles) * p.ht;
+            __syncthreads();   // everyone is done reading the previous tile (and the tables are written)
             // ---- element-wise staging of dY[k0..k0+KT, n0..n0+nti, h0..h0+ht, :] ----
             {
                 const int valid = (g.Ho - h0 < p.ht ? g.Ho - h0 : p.ht) * g.Wo;
@@ -326,67 +413,48 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_mfma(const ExactParams p)
                         if (dst[u] >= 0) Xs[dst[u]] = v[u];
                 }
             }
-        }
-        __syncthreads();
-        if (FAST && wt + 1 < wt_end) prefetch(wt + 1);
-
-        // ---- contract: 4 positions per MFMA step, NT column tiles per A operand; the operands
-        //      of the next step are read from LDS before the MFMAs of the current one ----
-        {
-            float a0, a1, b0[NT], b1[NT];
-            int xoA = xo_ptr[0], xoB = xo_ptr[4];
-            a0 = a_ptr[0];
-#pragma unroll
-            for (int j = 0; j < NT; ++j) b0[j] = Xs[coloff[j] + xoA];
-            for (int i = 0; i < spw; i += 2) {
-                xoA = xo_ptr[4 * (i + 2)];
-                a1 = a_ptr[4 * (i + 1)];
-#pragma unroll
-                for (int j = 0; j < NT; ++j) b1[j] = Xs[coloff[j] + xoB];
-#pragma unroll
-                for (int j = 0; j < NT; ++j)
-                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a0, b0[j], acc[j], 0, 0, 0);
-                xoB = xo_ptr[4 * (i + 3)];
-                a0 = a_ptr[4 * (i + 2)];                 // one step past the end on the last trip: read, not used
-#pragma unroll
-                for (int j = 0; j < NT; ++j) b0[j] = Xs[coloff[j] + xoA];
-#pragma unroll
-                for (int j = 0; j < NT; ++j)
-                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a1, b1[j], acc[j], 0, 0, 0);
-            }
+            __syncthreads();
+            contract();
         }
     }
 
-    // ---- wavefronts that split the positions add their accumulators through LDS ----
-    if (WQ > 1) {
-        __syncthreads();
-        float4_t *red = (float4_t *)smem;   // [(WQ-1)][WK][NT][64]
-        if (wq > 0) {
-#pragma unroll
-            for (int j = 0; j < NT; ++j) red[(((wq - 1) * WK + wk) * NT + j) * 64 + lane] = acc[j];
-        }
-        __syncthreads();
-        if (wq == 0) {
-            for (int w = 0; w < WQ - 1; ++w)
-#pragma unroll
-                for (int j = 0; j < NT; ++j) acc[j] += red[((w * WK + wk) * NT + j) * 64 + lane];
-        }
-    }
-    if (wq == 0) {
-        float *out = p.out + (long)split * g.K * CRS;
+    // ---- epilogue: every wavefront parks its accumulators in LDS in output order; then all
+    //      threads add the WQ position slices and write rows of the result, coalesced ----
+    __syncthreads();
+    TRACE(9);
+    {
+        constexpr int RP = NCB + 1;                         // row pitch of the exchange buffer
+        float *red = smem;                                  // [WQ][KT][RP]
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
-            int lo, oc;
-            column_of<NT>(p, coltile, j, i16, c_first, lo, oc);
-            if (oc < 0) continue;
+            int lo, lc;
+            column_of<NT>(p, coltile, j, i16, c_first, lo, lc);
+            if (lc < 0) lc = p.tap_mode ? (p.tile_c0[j] + i16) * RS + p.tile_tap[j] : j * 16 + i16;   // padding column: parked, never written out
 #pragma unroll
-            for (int v = 0; v < 4; ++v) {
-                const int k = k0 + wk * 16 + 4 * kk + v;
-                if (k < g.K) out[(long)k * CRS + oc] = acc[j][v];
-            }
+            for (int v = 0; v < 4; ++v) red[(wq * KT + wk * 16 + 4 * kk + v) * RP + lc] = acc[j][v];
+        }
+        __syncthreads();
+        TRACE(14);
+        const int colbase = p.tap_mode ? c_first * RS : coltile * NCB;
+        float *out = p.out + (long)split * g.K * CRS;
+        for (int o = tid; o < KT * NCB; o += kBlock) {
+            const int row = o / NCB, lc = o % NCB;
+            float sum = red[row * RP + lc];
+#pragma unroll
+            for (int w = 1; w < WQ; ++w) sum += red[(w * KT + row) * RP + lc];
+            const int k = k0 + row, col = colbase + lc;
+            if (k < g.K && col < CRS) out[(long)k * CRS + col] = sum;
         }
     }
+    TRACE(10);
 }
+
+#ifdef WGRAD_TUNING
+extern "C" int wgrad_debug_read_trace(long long *host_out)
+{
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace), sizeof(long long) * 64);
+}
+#endif
 
 // ------------------------------------------------------------------------------------
 // Host side: tile plan and launch.
@@ -395,7 +463,7 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_mfma(const ExactParams p)
 #define WGRAD_EXACT_KQ 8192
 #endif
 #ifndef WGRAD_EXACT_BLOCKS   // workgroups to aim for when splitting the reduction
-#define WGRAD_EXACT_BLOCKS 1024
+#define WGRAD_EXACT_BLOCKS 512
 #endif
 constexpr size_t kMaxLds = 64 * 1024;
 
@@ -448,7 +516,7 @@ ExactPlan plan_exact(const Geometry &g)
     // pass 1 (element-wise staging) only needs the tile to fit LDS
     for (int pass = 0; pass < 2 && !pl.ok; ++pass) {
         if (pass == 0 && (!xv_shape || L % 4 != 0)) continue;
-        for (int qt = WGRAD_EXACT_KQ / KT; qt >= 4; qt /= 2) {
+        for (int qt = tune_int("WGRAD_EXACT_KQ", WGRAD_EXACT_KQ) / KT; qt >= 4; qt /= 2) {
             if (L >= qt) {
                 pl.nti = 1;
                 pl.ht = qt / g.Wo < 1 ? 1 : qt / g.Wo;
@@ -464,8 +532,8 @@ ExactPlan plan_exact(const Geometry &g)
             pl.iht = (pl.ht - 1) * g.sh + g.R;
             pl.iwt = (g.Wo - 1) * g.sw + g.S;
             pl.pp = pitch_mod32(pl.nti * pl.iht * pl.iwt, 2, 1);
-            size_t lds = ((size_t)KT * pl.qp + (size_t)pl.ctch * pl.pp + pl.qpad + 8) * 4;
-            const size_t red = (size_t)(WQ - 1) * pl.wk * pl.nt * 64 * 16;
+            size_t lds = ((size_t)KT * pl.qp + (size_t)pl.ctch * pl.pp + pl.qpad + 16) * 4;
+            const size_t red = (size_t)4 * 16 * (pl.nt * 16 + 1) * 4;        // epilogue exchange buffer [WQ][KT][NT*16 + 1]
             if (red > lds) lds = red;
             pl.lds_bytes = lds;
             if (lds > kMaxLds) continue;
@@ -474,7 +542,7 @@ ExactPlan plan_exact(const Geometry &g)
                 const int seg = pl.ht * g.Wo;
                 const long dy_slots = (long)KT * pl.nti * (seg / 4);
                 const long x_slots = (long)pl.ctch * pl.nti * pl.iht * (g.W / xv_shape);
-                const bool fits = seg % 4 == 0 && dy_slots <= kSlotsDY * kBlock && x_slots <= kSlotsX * kBlock
+                const bool fits = seg % 4 == 0 && dy_slots <= slots_dy(pl.wk) * kBlock && x_slots <= slots_x(pl.wk) * kBlock
                                   && pl.iht <= 255 && (long)pl.ctch * pl.pp < (1 << 20)
                                   && (long)pl.nti * g.K * L < (1l << 31) && (long)pl.nti * g.C * g.H * g.W < (1l << 31);
                 if (!fits) continue;
@@ -493,7 +561,8 @@ ExactPlan plan_exact(const Geometry &g)
     pl.n_groups = (g.N + pl.nti - 1) / pl.nti;
     const long tiles = (long)pl.h_tiles * pl.n_groups;
     long out_tiles = (long)pl.ktiles * pl.ctiles;
-    long splits = (WGRAD_EXACT_BLOCKS + out_tiles - 1) / out_tiles;
+    const int want_blocks = tune_int("WGRAD_EXACT_BLOCKS", WGRAD_EXACT_BLOCKS);
+    long splits = (want_blocks + out_tiles - 1) / out_tiles;
     if (splits > tiles) splits = tiles;
     if (splits < 1) splits = 1;
     pl.splits = (int)splits;
@@ -555,6 +624,18 @@ int launch_exact(const Geometry &g, const ExactPlan &pl, const void *X, const vo
     p.d_wv = FastDiv(xv ? g.W / xv : 1);
     p.d_rows = FastDiv(pl.nti * pl.iht);
     p.d_iht = FastDiv(pl.iht);
+    p.d_rs = FastDiv(g.R * g.S);
+    p.d_s = FastDiv(g.S);
+    p.d_seg = FastDiv(p.seg);
+    p.d_wo = FastDiv(g.Wo);
+    p.d_htiles = FastDiv(pl.h_tiles);
+    if (pl.tap_mode)
+        for (int t = 0; t < pl.nt; ++t) {
+            const int RS = g.R * g.S, tap = t % RS;
+            p.tile_c0[t] = (t / RS) * 16;
+            p.tile_toff[t] = (tap / g.S) * pl.iwt + tap % g.S;
+            p.tile_tap[t] = tap;
+        }
 
     const int grid = pl.ktiles * pl.ctiles * pl.splits;
     switch (pl.nt) {
