@@ -44,6 +44,8 @@ def main():
     ap.add_argument("--layer-reps", type=int, default=20, help="back-to-back launches per layer in the per-layer pass")
     ap.add_argument("--cpu-budget-s", type=float, default=20.0, help="CPU seconds to spend on the oracle baseline (0 = skip)")
     ap.add_argument("--scale", type=float, default=1.0 / 128)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="run a plain 256 MiB device copy 10 times and exit (reference for HBM byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on exactly one GPU (the path has no multi-GPU part); "
@@ -57,6 +59,14 @@ def main():
     B.load()   # raises if libwgrad.so is missing: there is no fallback
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        a = torch.ones(64 * 1024 * 1024, dtype=torch.float32, device="cuda")   # 256 MiB read + 256 MiB written
+        b = torch.empty_like(a)
+        for _ in range(10):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read": a.numel() * 4, "bytes_written": a.numel() * 4, "launches": 10}}))
+        return
     cfg, stack_fn, N, dtype = inputs.WORKLOADS[args.workload]
     stack = stack_fn()
     e = 2 if dtype == "bf16" else 4
