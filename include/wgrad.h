@@ -100,11 +100,14 @@ size_t conv_wgrad_workspace_bytes(const wgrad_conv_desc *desc, wgrad_method meth
 
 /* One batch of an approximation schedule (Section 2.5): layer i uses
  * method[i] (a wgrad_method).  layers, X, dY, dW and method are host arrays of
- * nlayers entries; X[i], dY[i], dW[i] are device pointers.  All layers are
- * enqueued back to back on `stream` and share `ws`, which must hold the largest
- * per-layer requirement (conv_wgrad_schedule_workspace_bytes).  A random layer i
- * uses offset + (sum of K*C*R*S of the layers before it).  Validation of every
- * layer happens before the first launch. */
+ * nlayers entries (at most 4096); X[i], dY[i], dW[i] are device pointers.  All
+ * layers are enqueued on `stream` without any host synchronisation; exact or
+ * approximated layers that share one descriptor (up to 8 of them) are folded
+ * into a single launch sequence, each working in its own slice of `ws`, which
+ * must hold conv_wgrad_schedule_workspace_bytes(layers, method, nlayers).  The
+ * results are those of the individual calls.  A random layer i uses
+ * offset + (sum of K*C*R*S of the layers before it).  Validation of every layer
+ * happens before the first launch. */
 int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void *const *X,
                             const void *const *dY, float *const *dW, const uint8_t *method,
                             int32_t nlayers, float scale, float sigma, uint64_t seed,

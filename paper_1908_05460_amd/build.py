@@ -8,7 +8,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwgrad.so")
-SOURCES = ["api.hip", "exact_mfma.hip", "approx.hip", "fill.hip"]
+SOURCES = ["api.hip", "exact_mfma.hip", "exact_stream.hip", "exact_stream_w1.hip", "exact_stream_w2.hip",
+           "exact_stream_w4.hip", "approx.hip", "fill.hip"]
 # packed fp32 VALU forms are switched off on purpose (they have misbehaved on the test machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -39,7 +40,7 @@ def build(extra_flags=(), out=LIB, objdir=None, verbose=False):
             print(msgs, file=sys.stderr)
         return obj
 
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=8) as ex:
         objs = list(ex.map(compile_one, SOURCES))
     # -no-hip-rt: the library does not name a HIP runtime of its own; it binds to the one the
     # host process has already loaded (a process must never run two HIP runtimes side by side,

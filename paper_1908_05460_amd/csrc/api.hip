@@ -43,7 +43,9 @@ int conv_wgrad_exact(const wgrad_conv_desc *desc, const void *X, const void *dY,
     const ExactPlan pl = plan_exact(g);
     if (!pl.ok) return WGRAD_UNSUPPORTED;
     if (!ws_ok(ws, ws_bytes, pl.ws_bytes)) return WGRAD_WORKSPACE_TOO_SMALL;
-    return launch_exact(g, pl, X, dY, dW, ws, (hipStream_t)stream);
+    Batch b{};
+    b.n = 1; b.X[0] = X; b.dY[0] = dY; b.dW[0] = dW;
+    return launch_exact(g, pl, b, ws, (hipStream_t)stream);
 }
 
 int conv_wgrad_approx(const wgrad_conv_desc *desc, const void *X, const void *dY, float *dW,
@@ -56,7 +58,9 @@ int conv_wgrad_approx(const wgrad_conv_desc *desc, const void *X, const void *dY
     if (!X || !dY || !dW) return WGRAD_INVALID_ARG;
     const ApproxPlan pl = plan_approx(g);
     if (!ws_ok(ws, ws_bytes, pl.ws_bytes)) return WGRAD_WORKSPACE_TOO_SMALL;
-    return launch_approx(g, pl, X, dY, dW, scale, idx_out, sum_out, ws, (hipStream_t)stream);
+    Batch b{};
+    b.n = 1; b.X[0] = X; b.dY[0] = dY; b.dW[0] = dW;
+    return launch_approx(g, pl, b, scale, idx_out, sum_out, ws, (hipStream_t)stream);
 }
 
 int conv_wgrad_select(const wgrad_conv_desc *desc, const void *dY, int32_t *idx, float *sum, void *stream)
@@ -96,23 +100,66 @@ size_t conv_wgrad_workspace_bytes(const wgrad_conv_desc *desc, wgrad_method meth
     return 0;
 }
 
-size_t conv_wgrad_schedule_workspace_bytes(const wgrad_conv_desc *layers, const uint8_t *method, int32_t nlayers)
+}  // extern "C"
+
+// ---- schedule: layers with the same geometry and method are folded into one launch ----
+namespace {
+
+bool same_desc(const wgrad_conv_desc &a, const wgrad_conv_desc &b)
 {
-    if (!layers || !method || nlayers <= 0) return 0;
+    return a.N == b.N && a.C == b.C && a.H == b.H && a.W == b.W && a.K == b.K && a.R == b.R && a.S == b.S &&
+           a.stride_h == b.stride_h && a.stride_w == b.stride_w && a.pad_h == b.pad_h && a.pad_w == b.pad_w &&
+           a.dtype == b.dtype;
+}
+
+// group[i] = index of the first layer of i's group; a group holds at most kMaxBatch exact or
+// approx layers of identical descriptor (zero and random layers are never grouped)
+void make_groups(const wgrad_conv_desc *layers, const uint8_t *method, int n, int *group)
+{
+    for (int i = 0; i < n; ++i) group[i] = -1;
+    for (int i = 0; i < n; ++i) {
+        if (group[i] >= 0) continue;
+        group[i] = i;
+        if (method[i] != WGRAD_EXACT && method[i] != WGRAD_APPROX) continue;
+        int members = 1;
+        for (int j = i + 1; j < n && members < kMaxBatch; ++j)
+            if (group[j] < 0 && method[j] == method[i] && same_desc(layers[i], layers[j])) { group[j] = i; ++members; }
+    }
+}
+
+size_t method_ws(const Geometry &g, int method)
+{
+    if (method == WGRAD_EXACT) { const ExactPlan pl = plan_exact(g); return pl.ok ? pl.ws_bytes : 0; }
+    if (method == WGRAD_APPROX) return plan_approx(g).ws_bytes;
+    return 0;
+}
+
+}  // namespace
+
+extern "C" size_t conv_wgrad_schedule_workspace_bytes(const wgrad_conv_desc *layers, const uint8_t *method, int32_t nlayers)
+{
+    if (!layers || !method || nlayers <= 0 || nlayers > 4096) return 0;
+    int group[4096];
+    make_groups(layers, method, nlayers, group);
     size_t need = 0;
     for (int i = 0; i < nlayers; ++i) {
-        const size_t b = conv_wgrad_workspace_bytes(&layers[i], (wgrad_method)method[i]);
+        if (group[i] != i) continue;
+        Geometry g;
+        if (make_geometry(&layers[i], g) != WGRAD_OK) return 0;
+        int members = 0;
+        for (int j = i; j < nlayers; ++j) members += group[j] == i;
+        const size_t b = align_up(method_ws(g, method[i])) * members;
         if (b > need) need = b;
     }
     return need;
 }
 
-int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void *const *X, const void *const *dY,
+extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void *const *X, const void *const *dY,
                             float *const *dW, const uint8_t *method, int32_t nlayers, float scale,
                             float sigma, uint64_t seed, uint64_t offset, void *ws, size_t ws_bytes,
                             void *stream)
 {
-    if (!layers || !X || !dY || !dW || !method || nlayers <= 0) return WGRAD_INVALID_ARG;
+    if (!layers || !X || !dY || !dW || !method || nlayers <= 0 || nlayers > 4096) return WGRAD_INVALID_ARG;
     // pass 1: validate every layer before anything is enqueued
     for (int i = 0; i < nlayers; ++i) {
         Geometry g;
@@ -122,34 +169,37 @@ int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void *const *X,
         if (!dW[i]) return WGRAD_INVALID_ARG;
         if (method[i] == WGRAD_EXACT || method[i] == WGRAD_APPROX) {
             if (!X[i] || !dY[i]) return WGRAD_INVALID_ARG;
-            size_t need;
-            if (method[i] == WGRAD_EXACT) {
-                const ExactPlan pl = plan_exact(g);
-                if (!pl.ok) return WGRAD_UNSUPPORTED;
-                need = pl.ws_bytes;
-            } else {
-                need = plan_approx(g).ws_bytes;
-            }
-            if (!ws_ok(ws, ws_bytes, need)) return WGRAD_WORKSPACE_TOO_SMALL;
+            if (method[i] == WGRAD_EXACT && !plan_exact(g).ok) return WGRAD_UNSUPPORTED;
         } else if (method[i] == WGRAD_RANDOM && !(sigma >= 0.0f)) {
             return WGRAD_INVALID_ARG;
         }
     }
-    // pass 2: enqueue back to back on the caller's stream
+    if (!ws_ok(ws, ws_bytes, conv_wgrad_schedule_workspace_bytes(layers, method, nlayers))) return WGRAD_WORKSPACE_TOO_SMALL;
+
+    // pass 2: enqueue on the caller's stream, one launch sequence per group
+    int group[4096];
+    make_groups(layers, method, nlayers, group);
     uint64_t off = offset;
     for (int i = 0; i < nlayers; ++i) {
         int rc = WGRAD_OK;
-        switch (method[i]) {
-            case WGRAD_EXACT: rc = conv_wgrad_exact(&layers[i], X[i], dY[i], dW[i], ws, ws_bytes, stream); break;
-            case WGRAD_APPROX: rc = conv_wgrad_approx(&layers[i], X[i], dY[i], dW[i], scale, nullptr, nullptr, ws, ws_bytes, stream); break;
-            case WGRAD_ZERO: rc = conv_wgrad_zero(&layers[i], dW[i], stream); break;
-            default: rc = conv_wgrad_random(&layers[i], dW[i], sigma, seed, off, stream); break;
+        if (method[i] == WGRAD_ZERO) rc = conv_wgrad_zero(&layers[i], dW[i], stream);
+        else if (method[i] == WGRAD_RANDOM) rc = conv_wgrad_random(&layers[i], dW[i], sigma, seed, off, stream);
+        else if (group[i] == i) {
+            Geometry g;
+            make_geometry(&layers[i], g);
+            Batch b{};
+            for (int j = i; j < nlayers; ++j)
+                if (group[j] == i) { b.X[b.n] = X[j]; b.dY[b.n] = dY[j]; b.dW[b.n] = dW[j]; ++b.n; }
+            if (method[i] == WGRAD_EXACT) rc = launch_exact(g, plan_exact(g), b, ws, (hipStream_t)stream);
+            else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws, (hipStream_t)stream);
         }
         if (rc != WGRAD_OK) return rc;
         off += (uint64_t)layers[i].K * layers[i].C * layers[i].R * layers[i].S;
     }
     return WGRAD_OK;
 }
+
+extern "C" {
 
 const char *conv_wgrad_status_string(int status)
 {

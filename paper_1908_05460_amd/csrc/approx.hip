@@ -30,12 +30,24 @@ __device__ __forceinline__ uint32_t mag_key(uint32_t bits)   // bits of the valu
     return m > 0x7f800000u ? 0u : m;
 }
 
+// Per-problem pointers of a batched approximation launch (problem = blockIdx.y or .z).
+struct ApproxBatch {
+    const void *X[kMaxBatch];
+    const void *dY[kMaxBatch];
+    int32_t *hw[kMaxBatch];      // packed (row << 16 | col) of every map
+    float *sum[kMaxBatch];       // signed sum of every map
+    float *out[kMaxBatch];       // dW, or the batch-chunk partials
+};
+
 template <bool BF16, int VEC>
-__global__ __launch_bounds__(kBlock) void approx_select(const void *__restrict__ dY, long maps, int len,
+__global__ __launch_bounds__(kBlock) void approx_select(ApproxBatch ab, long maps, int len,
                                                         int Wo, int G, int32_t *__restrict__ flat_out,
-                                                        int32_t *__restrict__ hw_out,
-                                                        float *__restrict__ sum_a, float *__restrict__ sum_b)
+                                                        float *__restrict__ sum_b)
 {
+    // flat_out / sum_b: optional user outputs, single-problem launches only
+    const void *__restrict__ dY = ab.dY[blockIdx.y];
+    int32_t *__restrict__ hw_out = ab.hw[blockIdx.y];
+    float *__restrict__ sum_a = ab.sum[blockIdx.y];
     const int lane = threadIdx.x & 63;
     const int maps_per_wave = 64 / G;
     const long wave_global = (long)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
@@ -87,20 +99,21 @@ __global__ __launch_bounds__(kBlock) void approx_select(const void *__restrict__
     }
 }
 
-static int launch_select_impl(const Geometry &g, const void *dY, int32_t *flat_out, int32_t *hw_out,
-                              float *sum_a, float *sum_b, hipStream_t st)
+static int launch_select_impl(const Geometry &g, const ApproxBatch &ab, int nprob, int32_t *flat_out,
+                              float *sum_b, hipStream_t st)
 {
     const int len = g.Ho * g.Wo;
     const long maps = (long)g.N * g.K;
     const int full = g.bf16 ? 8 : 4;                      // elements per 16-byte access
-    const bool vec_ok = len % full == 0 && ((uintptr_t)dY % 16) == 0;
+    bool vec_ok = len % full == 0;
+    for (int i = 0; i < nprob; ++i) vec_ok = vec_ok && ((uintptr_t)ab.dY[i] % 16) == 0;
     const int vec = vec_ok ? full : 1;
     // lanes per map: enough that each lane issues about four accesses
     int G = 1;
     while (G < 64 && G * vec * 4 < len) G <<= 1;
     const long waves = (maps + 64 / G - 1) / (64 / G);
     const int grid = (int)((waves + kBlock / 64 - 1) / (kBlock / 64));
-#define SEL_ARGS dim3(grid), dim3(kBlock), 0, st, dY, maps, len, g.Wo, G, flat_out, hw_out, sum_a, sum_b
+#define SEL_ARGS dim3(grid, nprob), dim3(kBlock), 0, st, ab, maps, len, g.Wo, G, flat_out, sum_b
     if (g.bf16) {
         if (vec == 8) WGRAD_LAUNCH((approx_select<true, 8>), SEL_ARGS);
         else          WGRAD_LAUNCH((approx_select<true, 1>), SEL_ARGS);
@@ -114,7 +127,9 @@ static int launch_select_impl(const Geometry &g, const void *dY, int32_t *flat_o
 
 int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, hipStream_t st)
 {
-    return launch_select_impl(g, dY, idx, nullptr, sum, nullptr, st);
+    ApproxBatch ab{};
+    ab.dY[0] = dY; ab.sum[0] = sum;           // no packed positions wanted
+    return launch_select_impl(g, ab, 1, idx, nullptr, st);
 }
 
 // ------------------------------------------------------------------------------------
@@ -124,12 +139,13 @@ int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, h
 // (few output channels, large planes) and for filters other than 3x3.
 // ------------------------------------------------------------------------------------
 template <bool BF16>
-__global__ __launch_bounds__(kBlock) void approx_gather_direct(const void *__restrict__ X,
-                                                               const int32_t *__restrict__ hw,
-                                                               const float *__restrict__ sum,
-                                                               float *__restrict__ out, Geometry g,
+__global__ __launch_bounds__(kBlock) void approx_gather_direct(ApproxBatch ab, Geometry g,
                                                                int chunk_n, float scale)
 {
+    const void *__restrict__ X = ab.X[blockIdx.z];
+    const int32_t *__restrict__ hw = ab.hw[blockIdx.z];
+    const float *__restrict__ sum = ab.sum[blockIdx.z];
+    float *__restrict__ out = ab.out[blockIdx.z];
     const long o = (long)blockIdx.x * kBlock + threadIdx.x;
     const int RS = g.R * g.S, CRS = g.C * RS;
     if (o >= (long)g.K * CRS) return;
@@ -184,12 +200,12 @@ struct GatherParams {
 };
 
 template <bool BF16, int M>
-__global__ __launch_bounds__(kBlock) void approx_gather_lds3x3(const void *__restrict__ X,
-                                                               const int32_t *__restrict__ hw,
-                                                               const float *__restrict__ sum,
-                                                               float *__restrict__ out, Geometry g,
-                                                               GatherParams gp)
+__global__ __launch_bounds__(kBlock) void approx_gather_lds3x3(ApproxBatch ab, Geometry g, GatherParams gp)
 {
+    const void *__restrict__ X = ab.X[blockIdx.z];
+    const int32_t *__restrict__ hw = ab.hw[blockIdx.z];
+    const float *__restrict__ sum = ab.sum[blockIdx.z];
+    float *__restrict__ out = ab.out[blockIdx.z];
     typedef typename Raw4<BF16>::type raw4;
     extern __shared__ float xs[];                         // [2][nb][64][pitch]
     const int tid = threadIdx.x, lane = tid & 63;
@@ -207,6 +223,7 @@ __global__ __launch_bounds__(kBlock) void approx_gather_lds3x3(const void *__res
     FastDiv d_run4;                                       // run4 differs for the last channel tile
     d_run4.d = run4;
     d_run4.m = run4 > 1 ? (uint32_t)((1ull << 32) / (uint32_t)run4) + 1u : 0u;
+    d_run4.one = run4 > 1 ? 0u : 0xffffffffu;
 
     for (int e = tid; e < 2 * buf_floats; e += kBlock) xs[e] = 0.f;   // halo (and everything else) = 0
 
@@ -374,48 +391,57 @@ ApproxPlan plan_approx(const Geometry &g, bool allow_lds)
 }
 
 template <bool BF16>
-static void launch_gather_lds(const ApproxPlan &pl, dim3 grid, size_t lds, hipStream_t st, const void *X,
-                              const int32_t *hw, const float *sum, float *out, const Geometry &g, float scale)
+static void launch_gather_lds(const ApproxPlan &pl, dim3 grid, size_t lds, hipStream_t st, const ApproxBatch &ab,
+                              const Geometry &g, float scale)
 {
     GatherParams gp;
     gp.ctiles = pl.ctiles; gp.nb = pl.nb; gp.chunk_n = pl.chunk_n; gp.wp = pl.wp; gp.pitch = pl.pitch;
     gp.d_hw4 = FastDiv(g.H * g.W / 4);        // dividends stay below 64 * H*W, far under the 2^32 bound
     gp.d_w = FastDiv(g.W);
     gp.scale = scale;
-#define GL_ARGS grid, dim3(kBlock), lds, st, X, hw, sum, out, g, gp
+#define GL_ARGS grid, dim3(kBlock), lds, st, ab, g, gp
     if (pl.m == 4) WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 4>), GL_ARGS);
     else if (pl.m == 2) WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 2>), GL_ARGS);
     else WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 1>), GL_ARGS);
 #undef GL_ARGS
 }
 
-int launch_approx(const Geometry &g, const ApproxPlan &plan, const void *X, const void *dY, float *dW,
-                  float scale, int32_t *idx_out, float *sum_out, void *ws, hipStream_t st)
+int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, float scale,
+                  int32_t *idx_out, float *sum_out, void *ws, hipStream_t st)
 {
-    const bool aligned = ((uintptr_t)X % (g.bf16 ? 8 : 16)) == 0;
+    bool aligned = true;
+    for (int i = 0; i < b.n; ++i) aligned = aligned && ((uintptr_t)b.X[i] % (g.bf16 ? 8 : 16)) == 0;
     const ApproxPlan pl = (plan.use_lds && !aligned) ? plan_approx(g, false) : plan;
-    int32_t *hw = (int32_t *)((char *)ws + pl.off_idx);
-    float *sum = (float *)((char *)ws + pl.off_sum);
-    float *part = (float *)((char *)ws + pl.off_part);
-    int rc = launch_select_impl(g, dY, idx_out, hw, sum, sum_out, st);
+    const long outs = g.dw_elems();
+    // problem i owns the i-th slice (plan.ws_bytes each) of the workspace
+    ApproxBatch ab{};
+    for (int i = 0; i < kMaxBatch; ++i) {
+        const int j = i < b.n ? i : 0;
+        char *slice = (char *)ws + (size_t)j * plan.ws_bytes;
+        ab.X[i] = b.X[j]; ab.dY[i] = b.dY[j];
+        ab.hw[i] = (int32_t *)(slice + pl.off_idx);
+        ab.sum[i] = (float *)(slice + pl.off_sum);
+        ab.out[i] = pl.chunks > 1 ? (float *)(slice + pl.off_part) : b.dW[j];
+    }
+    int rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st);
     if (rc != WGRAD_OK) return rc;
 
-    const long outs = g.dw_elems();
-    float *out = pl.chunks > 1 ? part : dW;
     const float kscale = pl.chunks > 1 ? 1.0f : scale;
     if (pl.use_lds) {
-        const dim3 grid((unsigned)(pl.ctiles * pl.ktiles), (unsigned)pl.chunks);
+        const dim3 grid((unsigned)(pl.ctiles * pl.ktiles), (unsigned)pl.chunks, (unsigned)b.n);
         const size_t lds = (size_t)2 * pl.nb * kGatherCT * pl.pitch * 4;
-        if (g.bf16) launch_gather_lds<true>(pl, grid, lds, st, X, hw, sum, out, g, kscale);
-        else        launch_gather_lds<false>(pl, grid, lds, st, X, hw, sum, out, g, kscale);
+        if (g.bf16) launch_gather_lds<true>(pl, grid, lds, st, ab, g, kscale);
+        else        launch_gather_lds<false>(pl, grid, lds, st, ab, g, kscale);
     } else {
-        const dim3 grid((unsigned)((outs + kBlock - 1) / kBlock), (unsigned)pl.chunks);
-        if (g.bf16) WGRAD_LAUNCH((approx_gather_direct<true>), grid, dim3(kBlock), 0, st, X, hw, sum, out, g, pl.chunk_n, kscale);
-        else        WGRAD_LAUNCH((approx_gather_direct<false>), grid, dim3(kBlock), 0, st, X, hw, sum, out, g, pl.chunk_n, kscale);
+        const dim3 grid((unsigned)((outs + kBlock - 1) / kBlock), (unsigned)pl.chunks, (unsigned)b.n);
+        if (g.bf16) WGRAD_LAUNCH((approx_gather_direct<true>), grid, dim3(kBlock), 0, st, ab, g, pl.chunk_n, kscale);
+        else        WGRAD_LAUNCH((approx_gather_direct<false>), grid, dim3(kBlock), 0, st, ab, g, pl.chunk_n, kscale);
     }
     rc = launch_status();
     if (rc != WGRAD_OK) return rc;
-    if (pl.chunks > 1) return launch_combine(part, pl.chunks, outs, scale, dW, st);
+    if (pl.chunks > 1)
+        return launch_combine((const float *)((char *)ws + pl.off_part), (long)(plan.ws_bytes / 4), pl.chunks, outs,
+                              scale, b.dW, b.n, st);
     return WGRAD_OK;
 }
 
@@ -424,12 +450,16 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const void *X, cons
 // partials pl, pl+PL, ... in ascending order, then the PL sub-sums are added in
 // ascending pl through LDS -- a fixed order, so the result is deterministic.
 // ------------------------------------------------------------------------------------
+struct CombineOut { float *dW[kMaxBatch]; };
+
 template <int PL>
-__global__ __launch_bounds__(kBlock) void combine_partials(const float *__restrict__ part, int nparts,
-                                                           long elems, float scale, float *__restrict__ dW)
+__global__ __launch_bounds__(kBlock) void combine_partials(const float *__restrict__ part_base, long prob_stride,
+                                                           int nparts, long elems, float scale, CombineOut outs)
 {
     constexpr int OB = kBlock / PL;                       // outputs per workgroup
     __shared__ float red[PL][OB];
+    const float *__restrict__ part = part_base + blockIdx.y * prob_stride;
+    float *__restrict__ dW = outs.dW[blockIdx.y];
     const int ol = threadIdx.x % OB, pl = threadIdx.x / OB;
     const long o = (long)blockIdx.x * OB + ol;
     float acc = 0.f;
@@ -458,15 +488,20 @@ __global__ __launch_bounds__(kBlock) void combine_partials(const float *__restri
     }
 }
 
-int launch_combine(const float *partials, int nparts, long elems, float scale, float *dW, hipStream_t st)
+int launch_combine(const float *partials, long prob_stride, int nparts, long elems, float scale,
+                   float *const *dW, int nprob, hipStream_t st)
 {
+    CombineOut outs{};
+    for (int i = 0; i < kMaxBatch; ++i) outs.dW[i] = dW[i < nprob ? i : 0];
     // spread the partial index over lanes when there are few outputs and many partials
     const int pl = (elems <= 16 * 1024 && nparts >= 64) ? 16 : ((elems <= 256 * 1024 && nparts >= 16) ? 4 : 1);
     const int ob = kBlock / pl;
-    const int grid = (int)((elems + ob - 1) / ob);
-    if (pl == 16) WGRAD_LAUNCH(combine_partials<16>, dim3(grid), dim3(kBlock), 0, st, partials, nparts, elems, scale, dW);
-    else if (pl == 4) WGRAD_LAUNCH(combine_partials<4>, dim3(grid), dim3(kBlock), 0, st, partials, nparts, elems, scale, dW);
-    else WGRAD_LAUNCH(combine_partials<1>, dim3(grid), dim3(kBlock), 0, st, partials, nparts, elems, scale, dW);
+    const dim3 grid((unsigned)((elems + ob - 1) / ob), (unsigned)nprob);
+#define CB_ARGS grid, dim3(kBlock), 0, st, partials, prob_stride, nparts, elems, scale, outs
+    if (pl == 16) WGRAD_LAUNCH(combine_partials<16>, CB_ARGS);
+    else if (pl == 4) WGRAD_LAUNCH(combine_partials<4>, CB_ARGS);
+    else WGRAD_LAUNCH(combine_partials<1>, CB_ARGS);
+#undef CB_ARGS
     return launch_status();
 }
 

@@ -13,15 +13,25 @@ constexpr int kWave = 64;
 constexpr int kNumXCD = 8;           // MI355X: 8 accelerator dies, each with its own L2
 constexpr int kNumCU = 256;
 constexpr size_t kAlign = 256;       // workspace carve-out alignment
+constexpr int kMaxBatch = 8;         // layers of identical shape a schedule run folds into one launch
+
+// Tensors of up to kMaxBatch problems of identical geometry handled by one launch.
+struct Batch {
+    int n;
+    const void *X[kMaxBatch];
+    const void *dY[kMaxBatch];
+    float *dW[kMaxBatch];
+};
 
 // Division of a small unsigned number by a run-time constant: q = umulhi(n, m)
 // with m = floor(2^32/d) + 1 is exact while n*d < 2^32 (the host checks that
 // bound for every divisor it builds).
 struct FastDiv {
-    uint32_t d, m;
-    __host__ __device__ FastDiv() : d(1), m(0) {}
-    __host__ explicit FastDiv(uint32_t div) : d(div), m(div > 1 ? (uint32_t)((1ull << 32) / div) + 1u : 0u) {}
-    __device__ __forceinline__ uint32_t div(uint32_t n) const { return d == 1 ? n : __umulhi(n, m); }
+    uint32_t d, m, one;              // one = all ones when d == 1 (then m = 0), else 0: keeps div() branch-free
+    __host__ __device__ FastDiv() : d(1), m(0), one(0xffffffffu) {}
+    __host__ explicit FastDiv(uint32_t div)
+        : d(div), m(div > 1 ? (uint32_t)((1ull << 32) / div) + 1u : 0u), one(div > 1 ? 0u : 0xffffffffu) {}
+    __device__ __forceinline__ uint32_t div(uint32_t n) const { return __umulhi(n, m) | (n & one); }
     __device__ __forceinline__ void divmod(uint32_t n, uint32_t &q, uint32_t &r) const {
         q = div(n);
         r = n - q * d;
@@ -69,12 +79,15 @@ struct ExactPlan {
     int iht, iwt, pp, ctch;          // staged input rows / cols, LDS pitch of an X channel, channels staged
     int h_tiles, n_groups;
     int xv;                          // elements per staging access (4, 2; 0 = element-wise staging)
+    int stream, gpw, xbuf, rowp;           // streaming form: A operand from global memory, window double-buffered
     size_t lds_bytes, ws_bytes;
     bool ok;
 };
-ExactPlan plan_exact(const Geometry &g);
-int launch_exact(const Geometry &g, const ExactPlan &pl, const void *X, const void *dY, float *dW,
-                 void *ws, hipStream_t st);
+ExactPlan plan_exact(const Geometry &g, bool allow_stream = true);
+bool plan_exact_stream(const Geometry &g, ExactPlan &pl);
+int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st);
+int launch_exact(const Geometry &g, const ExactPlan &pl, const Batch &b, void *ws, hipStream_t st);
+size_t exact_ws_per_problem(const Geometry &g, const ExactPlan &pl);
 
 struct ApproxPlan {
     int chunks, chunk_n;             // batch chunks whose partial sums are combined afterwards
@@ -83,10 +96,12 @@ struct ApproxPlan {
 };
 ApproxPlan plan_approx(const Geometry &g, bool allow_lds = true);
 int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, hipStream_t st);
-int launch_approx(const Geometry &g, const ApproxPlan &pl, const void *X, const void *dY, float *dW,
-                  float scale, int32_t *idx_out, float *sum_out, void *ws, hipStream_t st);
+int launch_approx(const Geometry &g, const ApproxPlan &pl, const Batch &b, float scale,
+                  int32_t *idx_out, float *sum_out, void *ws, hipStream_t st);
 
-int launch_combine(const float *partials, int nparts, long elems, float scale, float *dW, hipStream_t st);
+// dW[i][o] = scale * sum_j partials[i * prob_stride + j * elems + o] for the nprob problems of a batch
+int launch_combine(const float *partials, long prob_stride, int nparts, long elems, float scale,
+                   float *const *dW, int nprob, hipStream_t st);
 int launch_zero(float *dW, long elems, hipStream_t st);
 int launch_random(float *dW, long elems, float sigma, uint64_t seed, uint64_t offset, hipStream_t st);
 

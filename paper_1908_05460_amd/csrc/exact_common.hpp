@@ -1,0 +1,52 @@
+// Pieces shared by the two exact-gradient kernels (gfx950).
+#pragma once
+#include "common.hpp"
+
+namespace wgrad {
+
+typedef float float4_t __attribute__((ext_vector_type(4)));
+
+// Development builds (-DWGRAD_TUNING) can record phase timestamps of one workgroup; a file that
+// wants them defines WGRAD_TRACE_HERE before including this header.
+#if defined(WGRAD_TUNING) && defined(WGRAD_TRACE_HERE)
+static __device__ long long g_trace[64];
+#define TRACE_BLOCK 37
+#define TRACE(i) do { if (blockIdx.x == TRACE_BLOCK && threadIdx.x == 0) { g_trace[i] = wall_clock64(); g_trace[32 + i] = clock64(); } } while (0)
+#else
+#define TRACE(i) do { } while (0)
+#endif
+
+template <bool BF16>
+__device__ __forceinline__ float load_elem(const void *p, long i)
+{
+    if (BF16) return bf16_bits_to_float(((const uint16_t *)p)[i]);
+    return ((const float *)p)[i];
+}
+
+// V consecutive elements at a uniform base pointer plus a per-lane byte offset, widened to fp32 on use.
+template <bool BF16, int V> struct Vec;
+template <> struct Vec<false, 4> {
+    float4_t r;
+    __device__ __forceinline__ void load(const char *base, uint32_t off) { r = *(const float4_t *)(base + off); }
+    __device__ __forceinline__ float get(int u) const { return r[u]; }
+};
+template <> struct Vec<false, 2> {
+    float2 r;
+    __device__ __forceinline__ void load(const char *base, uint32_t off) { r = *(const float2 *)(base + off); }
+    __device__ __forceinline__ float get(int u) const { return u == 0 ? r.x : r.y; }
+};
+template <> struct Vec<true, 4> {
+    uint2 r;
+    __device__ __forceinline__ void load(const char *base, uint32_t off) { r = *(const uint2 *)(base + off); }
+    __device__ __forceinline__ float get(int u) const {
+        const uint32_t w = u < 2 ? r.x : r.y;
+        return __uint_as_float((u & 1) ? (w & 0xffff0000u) : (w << 16));
+    }
+};
+template <> struct Vec<true, 2> {
+    uint32_t r;
+    __device__ __forceinline__ void load(const char *base, uint32_t off) { r = *(const uint32_t *)(base + off); }
+    __device__ __forceinline__ float get(int u) const { return __uint_as_float(u ? (r & 0xffff0000u) : (r << 16)); }
+};
+
+}  // namespace wgrad

@@ -24,19 +24,9 @@
 // MFMA: v_mfma_f32_16x16x4_f32.  Lane l supplies A[i = l%16][kk = l/16] and
 // B[kk = l/16][j = l%16]; the 4 reduction slots kk are 4 consecutive staged
 // positions.  The accumulator registers v = 0..3 of lane l hold D[4*(l/16) + v][l%16].
-#include "common.hpp"
+#include "exact_common.hpp"
 
 namespace wgrad {
-
-typedef float float4_t __attribute__((ext_vector_type(4)));
-
-#ifdef WGRAD_TUNING   // development builds only: phase timestamps of one workgroup
-__device__ long long g_trace[64];
-#define TRACE(i) do { if (blockIdx.x == TRACE_BLOCK && threadIdx.x == 0) { g_trace[i] = wall_clock64(); g_trace[32 + i] = clock64(); } } while (0)
-#define TRACE_BLOCK 37
-#else
-#define TRACE(i) do { } while (0)
-#endif
 
 // Staging slots per thread and tile (16-byte loads of dY; 16- or 8-byte loads of X).  Narrow K
 // tiles have few dY rows but the same input window, so they trade dY slots for X slots.
@@ -57,39 +47,6 @@ struct ExactParams {
     FastDiv d_rs, d_s, d_seg, d_wo, d_htiles;
     // tap mode, per MFMA column tile: first channel (relative to the block's), LDS offset of the tap, tap index
     int tile_c0[9], tile_toff[9], tile_tap[9];
-};
-
-template <bool BF16>
-__device__ __forceinline__ float load_elem(const void *p, long i)
-{
-    if (BF16) return bf16_bits_to_float(((const uint16_t *)p)[i]);
-    return ((const float *)p)[i];
-}
-
-// V consecutive elements at a uniform base pointer plus a per-lane byte offset, widened to fp32 on use.
-template <bool BF16, int V> struct Vec;
-template <> struct Vec<false, 4> {
-    float4_t r;
-    __device__ __forceinline__ void load(const char *base, uint32_t off) { r = *(const float4_t *)(base + off); }
-    __device__ __forceinline__ float get(int u) const { return r[u]; }
-};
-template <> struct Vec<false, 2> {
-    float2 r;
-    __device__ __forceinline__ void load(const char *base, uint32_t off) { r = *(const float2 *)(base + off); }
-    __device__ __forceinline__ float get(int u) const { return u == 0 ? r.x : r.y; }
-};
-template <> struct Vec<true, 4> {
-    uint2 r;
-    __device__ __forceinline__ void load(const char *base, uint32_t off) { r = *(const uint2 *)(base + off); }
-    __device__ __forceinline__ float get(int u) const {
-        const uint32_t w = u < 2 ? r.x : r.y;
-        return __uint_as_float((u & 1) ? (w & 0xffff0000u) : (w << 16));
-    }
-};
-template <> struct Vec<true, 2> {
-    uint32_t r;
-    __device__ __forceinline__ void load(const char *base, uint32_t off) { r = *(const uint32_t *)(base + off); }
-    __device__ __forceinline__ float get(int u) const { return __uint_as_float(u ? (r & 0xffff0000u) : (r << 16)); }
 };
 
 // Column mapping of MFMA column tile t for lane column i16.  tap_mode: the tile covers 16
@@ -449,13 +406,6 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_mfma(const ExactParams p)
     TRACE(10);
 }
 
-#ifdef WGRAD_TUNING
-extern "C" int wgrad_debug_read_trace(long long *host_out)
-{
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace), sizeof(long long) * 64);
-}
-#endif
-
 // ------------------------------------------------------------------------------------
 // Host side: tile plan and launch.
 // ------------------------------------------------------------------------------------
@@ -483,7 +433,7 @@ static int largest_divisor_at_most(int n, int limit)
     return 1;
 }
 
-ExactPlan plan_exact(const Geometry &g)
+ExactPlan plan_exact(const Geometry &g, bool allow_stream)
 {
     ExactPlan pl{};
     const int RS = g.R * g.S;
@@ -507,6 +457,9 @@ ExactPlan plan_exact(const Geometry &g)
         pl.ctch = (cols - 1) / RS + 2;
         if (pl.ctch > g.C) pl.ctch = g.C;
     }
+    // the streaming form (A operand straight from global memory) takes every shape it can
+    if (allow_stream && tune_int("WGRAD_EXACT_STREAM", 1) && plan_exact_stream(g, pl)) pl.ok = true;
+
     // widest access the shape allows when staging X rows (alignment of the pointers is checked at launch)
     const int xv_shape = g.W % 4 == 0 ? 4 : (g.W % 2 == 0 ? 2 : 0);
 
@@ -567,6 +520,11 @@ ExactPlan plan_exact(const Geometry &g)
     if (splits < 1) splits = 1;
     pl.splits = (int)splits;
     pl.ws_bytes = pl.splits > 1 ? align_up((size_t)pl.splits * g.dw_elems() * 4) : 0;
+    // tensors that are not 16-byte aligned fall back to the staged form at launch: size for both
+    if (pl.stream) {
+        const size_t alt = plan_exact(g, false).ws_bytes;
+        if (alt > pl.ws_bytes) pl.ws_bytes = alt;
+    }
     return pl;
 }
 
@@ -598,8 +556,46 @@ static void launch_wk(const ExactParams &p, int wk, int grid, size_t lds, int xv
     else launch_dtype<NT, 4>(p, grid, lds, xv, st);
 }
 
-int launch_exact(const Geometry &g, const ExactPlan &pl, const void *X, const void *dY, float *dW,
-                 void *ws, hipStream_t st)
+size_t exact_ws_per_problem(const Geometry &g, const ExactPlan &pl)
+{
+    (void)g;
+    return pl.ws_bytes;
+}
+
+static bool batch_aligned(const Geometry &g, const Batch &b, int xv)
+{
+    const int esz = g.bf16 ? 2 : 4;
+    for (int i = 0; i < b.n; ++i)
+        if (((uintptr_t)b.dY[i] % (4 * esz)) != 0 || ((uintptr_t)b.X[i] % (xv * esz)) != 0) return false;
+    return true;
+}
+
+static int launch_exact_staged(const Geometry &g, const ExactPlan &pl, const void *X, const void *dY, float *dW,
+                               void *ws, hipStream_t st);
+
+int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void *ws, hipStream_t st)
+{
+    if (plan.stream && batch_aligned(g, b, plan.xv)) {
+        // one launch for the whole batch; problem i owns the i-th slice of the workspace
+        float *out[kMaxBatch];
+        const long prob_stride = (long)plan.splits * g.dw_elems();
+        for (int i = 0; i < b.n; ++i) out[i] = plan.splits > 1 ? (float *)ws + i * prob_stride : b.dW[i];
+        int rc = launch_exact_stream(g, plan, b, out, st);
+        if (rc != WGRAD_OK) return rc;
+        if (plan.splits > 1) return launch_combine((const float *)ws, prob_stride, plan.splits, g.dw_elems(), 1.0f, b.dW, b.n, st);
+        return WGRAD_OK;
+    }
+    // staged form: one problem at a time (shapes or alignments the streaming form does not take)
+    const ExactPlan pl = plan.stream ? plan_exact(g, false) : plan;
+    for (int i = 0; i < b.n; ++i) {
+        int rc = launch_exact_staged(g, pl, b.X[i], b.dY[i], b.dW[i], ws, st);
+        if (rc != WGRAD_OK) return rc;
+    }
+    return WGRAD_OK;
+}
+
+static int launch_exact_staged(const Geometry &g, const ExactPlan &pl, const void *X, const void *dY, float *dW,
+                               void *ws, hipStream_t st)
 {
     ExactParams p{};
     p.X = X; p.dY = dY;
@@ -645,7 +641,7 @@ int launch_exact(const Geometry &g, const ExactPlan &pl, const void *X, const vo
     }
     int rc = launch_status();
     if (rc != WGRAD_OK) return rc;
-    if (pl.splits > 1) return launch_combine((const float *)ws, pl.splits, g.dw_elems(), 1.0f, dW, st);
+    if (pl.splits > 1) return launch_combine((const float *)ws, 0, pl.splits, g.dw_elems(), 1.0f, &dW, 1, st);
     return WGRAD_OK;
 }
 

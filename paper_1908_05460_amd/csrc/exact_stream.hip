@@ -1,0 +1,108 @@
+// Host side of the streaming exact-gradient kernel: tile plan and launch.
+#include "exact_stream_kernel.hpp"
+
+namespace wgrad {
+
+// ------------------------------------------------------------------------------------
+// Host side
+// ------------------------------------------------------------------------------------
+static int stream_pitch(int len)   // smallest pitch >= len with pitch % 32 == 1
+{
+    int p = len;
+    while (p % 32 != 1) ++p;
+    return p;
+}
+
+static int largest_divisor_le(int n, int limit)
+{
+    if (limit >= n) return n;
+    for (int d = limit; d >= 1; --d)
+        if (n % d == 0) return d;
+    return 1;
+}
+
+// Fills the streaming-form fields of the plan; returns false if the shape is outside what the
+// streaming kernel handles (the staged kernel then takes it).
+bool plan_exact_stream(const Geometry &g, ExactPlan &pl)
+{
+    const int WQ = 4 / pl.wk;
+    const int L = g.Ho * g.Wo;
+    const int xv = g.W % 4 == 0 ? 4 : (g.W % 2 == 0 ? 2 : 0);
+    if (!xv || L % 4 != 0) return false;
+    const int XS = stream_xslots(pl.wk);
+    for (int gpw = 8; gpw >= 4; gpw -= 4) {
+        const int qt = 16 * gpw * WQ;
+        int nti, ht;
+        if (L >= qt) { nti = 1; ht = largest_divisor_le(g.Ho, qt / g.Wo < 1 ? 1 : qt / g.Wo); }
+        else { ht = g.Ho; nti = largest_divisor_le(g.N, qt / L < 1 ? 1 : qt / L); }
+        const int q = nti * ht * g.Wo;
+        if (q > qt || (ht * g.Wo) % 4 != 0) continue;
+        if (q * 2 <= qt && gpw == 8) continue;             // more than half the tile would be padding: try the smaller one
+        const int iht = (ht - 1) * g.sh + g.R, iwt = (g.Wo - 1) * g.sw + g.S;
+        // 3x3 tap mode: a fixed row pitch (4 mod 8, so that rows too spread over the banks) makes the
+        // tap offsets compile-time constants; otherwise rows are packed
+        int rowp = iwt;
+        if (pl.tap_mode && pl.nt == 9) {
+            const int fixed = iwt <= 4 ? 4 : (iwt <= 12 ? 12 : (iwt <= 20 ? 20 : (iwt <= 36 ? 36 : 0)));
+            if (fixed && stream_has_rowp(fixed, xv)) rowp = fixed;
+        }
+        const int pp = stream_pitch(nti * iht * rowp);
+        const int xbuf = (pl.ctch + 3) / 4 * (4 * pp + 4);        // quads of channels, see stream_chan_off
+        size_t lds = ((size_t)2 * xbuf + qt) * 4;
+        const size_t red = (size_t)4 * 16 * (pl.nt * 16 + 1) * 4;
+        if (red > lds) lds = red;
+        const long x_slots = (long)pl.ctch * nti * iht * (g.W / xv);
+        if (lds > 64 * 1024 || x_slots > (long)XS * kBlock || iht > 255 || (long)xbuf >= (1 << 20)) continue;
+        if ((long)nti * g.K * L * 4 >= (1l << 31) || (long)nti * g.C * g.H * g.W * 4 >= (1l << 31)) continue;
+        pl.stream = 1; pl.gpw = gpw; pl.xv = xv;
+        pl.nti = nti; pl.ht = ht; pl.q = q; pl.qpad = qt; pl.qp = 0;
+        pl.iht = iht; pl.iwt = iwt; pl.pp = pp; pl.xbuf = xbuf; pl.rowp = rowp;
+        pl.lds_bytes = lds;
+        return true;
+    }
+    return false;
+}
+
+// Enqueues the streaming kernel (not the combine); the caller has checked pointer alignment.
+int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st)
+{
+    StreamParams p{};
+    for (int i = 0; i < kMaxBatch; ++i) {          // unused slots repeat problem 0
+        const int j = i < b.n ? i : 0;
+        p.X[i] = b.X[j]; p.dY[i] = b.dY[j]; p.out[i] = out[j];
+    }
+    p.per_prob = pl.ktiles * pl.ctiles * pl.splits;
+    p.g = g;
+    p.tap_mode = pl.tap_mode; p.ktiles = pl.ktiles; p.ctiles = pl.ctiles; p.splits = pl.splits;
+    p.nti = pl.nti; p.ht = pl.ht; p.q = pl.q; p.iht = pl.iht; p.iwt = pl.iwt; p.pp = pl.pp; p.ctch = pl.ctch;
+    p.h_tiles = pl.h_tiles; p.n_groups = pl.n_groups;
+    p.seg = pl.ht * g.Wo;
+    p.xbuf = pl.xbuf;
+    p.rowp = pl.rowp;
+#ifdef WGRAD_TUNING
+    p.repeat = tune_int("WGRAD_REPEAT", 1);
+#endif
+    p.d_wv = FastDiv(g.W / pl.xv);
+    p.d_rows = FastDiv(pl.nti * pl.iht);
+    p.d_iht = FastDiv(pl.iht);
+    p.d_rs = FastDiv(g.R * g.S);
+    p.d_s = FastDiv(g.S);
+    p.d_seg = FastDiv(p.seg);
+    p.d_wo = FastDiv(g.Wo);
+    p.d_htiles = FastDiv(pl.h_tiles);
+    if (pl.tap_mode)
+        for (int t = 0; t < pl.nt; ++t) {
+            const int RS = g.R * g.S, tap = t % RS;
+            p.tile_c0[t] = (t / RS) * 16;
+            p.tile_toff[t] = (tap / g.S) * pl.rowp + tap % g.S;
+            p.tile_tap[t] = tap;
+        }
+    const int grid = pl.ktiles * pl.ctiles * pl.splits * b.n;
+    const int rowp_inst = stream_has_rowp(pl.rowp, pl.xv) && pl.nt == 9 && pl.tap_mode ? pl.rowp : 0;
+    if (pl.wk == 1) stream_launch_w1(p, pl.nt, pl.xv, pl.gpw, rowp_inst, grid, pl.lds_bytes, st);
+    else if (pl.wk == 2) stream_launch_w2(p, pl.nt, pl.xv, pl.gpw, rowp_inst, grid, pl.lds_bytes, st);
+    else stream_launch_w4(p, pl.nt, pl.xv, pl.gpw, rowp_inst, grid, pl.lds_bytes, st);
+    return launch_status();
+}
+
+}  // namespace wgrad

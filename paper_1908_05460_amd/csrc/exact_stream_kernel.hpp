@@ -1,0 +1,402 @@
+// Exact filter gradient, streaming form of the implicit GEMM (see exact_mfma.hip for the
+// mathematics and the column mapping).  Differences from the staged form:
+//
+//   - dY, the A operand, never touches LDS.  MFMA 16x16x4 wants A[i][kk] from lane
+//     (i = l%16, kk = l/16); the order of the reduction is free, so lane (i, kk) loads ONE
+//     16-byte piece dY[k0+i][q0 + 4*kk .. +3] straight from global memory and feeds element
+//     s of it to step s of a group of four steps.  (B must follow the same order: step s of
+//     the group contracts positions q0 + 4*kk + s, kk = 0..3.)  A wavefront keeps one tile of
+//     its A rows in registers (GPW pieces per lane); piece g of the next tile is requested
+//     right after piece g of the current tile has been used, so the loads of a whole tile are
+//     in flight behind the MFMAs.
+//   - only the zero-haloed input window lives in LDS, double-buffered: the window of tile
+//     t+1 is written (from registers loaded one tile earlier) at the start of tile t, so
+//     there is a single barrier per tile.
+//
+// Every load is issued unconditionally (a lane or tile that has nothing to fetch re-reads
+// the first element of a valid tile), which keeps the number of loads in flight fixed so a
+// piece can be waited for while younger loads are still arriving.
+#pragma once
+#include "exact_common.hpp"
+
+namespace wgrad {
+
+// Instruction order inside one step of the MFMA pipeline (its region holds the LDS reads of
+// step t+1 and the MFMAs of step t).  WGRAD_STREAM_SCHED = 2 (default): the reads are spread
+// between the MFMAs (read, two MFMAs, read, two MFMAs, ...), so a wavefront never waits on an
+// LDS read it has just issued; 1: all reads, then all MFMAs; 0: left to the compiler, which
+// places each read right before its use.
+#ifndef WGRAD_STREAM_SCHED
+#define WGRAD_STREAM_SCHED 2
+#endif
+#if WGRAD_STREAM_SCHED == 1
+#define WGRAD_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
+#else
+#define WGRAD_SCHED_FENCE() do { } while (0)
+#endif
+#if WGRAD_STREAM_SCHED == 2
+#define WGRAD_STEP_PATTERN(NT)                                                        \
+    do {                                                                                \
+        __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);   /* the address add      */ \
+        for (int gsb = 0; gsb < (NT + 1) / 2; ++gsb) {                                  \
+            __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);   /* one LDS read     */ \
+            __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);   /* two MFMAs        */ \
+        }                                                                               \
+        __builtin_amdgcn_sched_barrier(0);                                              \
+    } while (0)
+#else
+#define WGRAD_STEP_PATTERN(NT) do { } while (0)
+#endif
+
+struct StreamParams {
+    const void *X[kMaxBatch], *dY[kMaxBatch];
+    float *out[kMaxBatch];      // per problem: dW when splits == 1, else partials [splits][K][C*R*S]
+    int per_prob;               // workgroups per problem
+    Geometry g;
+    int tap_mode, ktiles, ctiles, splits;
+    int nti, ht, q, iht, iwt, pp, ctch, h_tiles, n_groups;
+    int seg;                    // ht * Wo : contiguous dY elements per (image, channel) in a tile
+    int xbuf;                   // floats per LDS window buffer (multiple of 4)
+    int rowp;                   // LDS pitch of a window row (>= iwt)
+    FastDiv d_wv, d_rows, d_iht, d_rs, d_s, d_seg, d_wo, d_htiles;
+    int tile_c0[9], tile_toff[9], tile_tap[9];
+#ifdef WGRAD_TUNING
+    int repeat;                 // development builds: contract every tile this many times (timing experiments only)
+#endif
+};
+
+__host__ __device__ constexpr int stream_xslots(int wk) { return wk == 1 ? 9 : (wk == 2 ? 5 : 4); }
+
+// LDS offset (floats) of staged channel c_l.  In a step the four lane groups kk of an MFMA
+// operand read positions 4 apart, so channels are placed such that
+//   bank(c_l, kk) = (c_l & 3) + 8 * (c_l >> 2) + 4 * kk   (mod 32)
+// is a bijection over 16 channels x 2 lane groups: pp = 1 (mod 32) is the pitch of a channel
+// inside a quad, 4 * pp + 4 the pitch of a quad.
+__device__ __forceinline__ int stream_chan_off(int c_l, int pp) { return (c_l & 3) * pp + (c_l >> 2) * (4 * pp + 4); }
+
+template <int NT>
+__device__ __forceinline__ void stream_column_of(const StreamParams &p, int coltile, int t, int i16, int c_first,
+                                                 int &lds_off, int &local_col)
+{
+    const Geometry &g = p.g;
+    const int RS = g.R * g.S;
+    if (p.tap_mode) {
+        const int c_l = p.tile_c0[t] + i16;
+        const bool ok = c_first + c_l < g.C;
+        lds_off = ok ? stream_chan_off(c_l, p.pp) + p.tile_toff[t] : 0;
+        local_col = ok ? c_l * RS + p.tile_tap[t] : -1;
+    } else {
+        const int col = coltile * NT * 16 + t * 16 + i16;
+        const bool ok = col < g.C * RS;
+        uint32_t c, tap, r, s;
+        p.d_rs.divmod(col, c, tap);
+        p.d_s.divmod(tap, r, s);
+        lds_off = ok ? (int)(stream_chan_off(c - c_first, p.pp) + r * p.iwt + s) : 0;
+        local_col = ok ? t * 16 + i16 : -1;
+    }
+}
+
+// NT: 16-column MFMA tiles per wavefront; WK: wavefronts along K; XV: elements per access
+// when staging rows of X (4 or 2); GPW: 16-position groups per wavefront and tile (a tile
+// has 16 * GPW * (4/WK) positions, padded with zero positions if the shape gives fewer).
+// ROWP: for 3x3 filters in tap mode, the LDS pitch of a window row as a compile-time constant:
+// the nine taps of a step are then one per-lane address plus nine immediate offsets, and the
+// loop has one VALU instruction per nine MFMAs instead of nine (the adds, not LDS or the matrix
+// core, bound the loop otherwise).  ROWP = 0: run-time pitch and tap offsets (any filter).
+template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP>
+__global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams p)
+{
+    static_assert(ROWP == 0 || NT == 9, "immediate tap offsets are for 3x3 filters in tap mode");
+    const int rowp = ROWP ? ROWP : p.rowp;
+    constexpr int KT = 16 * WK, WQ = 4 / WK;
+    constexpr int ESZ = BF16 ? 2 : 4;
+    constexpr int NCB = NT * 16;
+    constexpr int QT = 16 * GPW * WQ;                   // positions per tile, padded
+    constexpr int XS = stream_xslots(WK);
+    extern __shared__ float smem[];
+    float *Xs0 = smem;                                  // [2][xbuf]
+    int *xoff = (int *)(smem + 2 * p.xbuf);             // [QT] byte offsets
+
+    const Geometry &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wk = wave % WK, wq = wave / WK;
+    const int i16 = lane & 15, kk = lane >> 4;
+    const int RS = g.R * g.S, CRS = g.C * RS;
+    const int L = g.Ho * g.Wo;
+
+    // a launch may carry several problems of identical shape (layers of a schedule run)
+    const int logical_all = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    const int prob = logical_all / p.per_prob;
+    const int logical = logical_all - prob * p.per_prob;
+    const char *const Xp = (const char *)p.X[prob];
+    const char *const dYp = (const char *)p.dY[prob];
+    const int coltile = logical % p.ctiles;
+    const int ktile = (logical / p.ctiles) % p.ktiles;
+    const int split = logical / (p.ctiles * p.ktiles);
+    const int k0 = ktile * KT;
+    const int c_first = p.tap_mode ? coltile * 16 * (NT / RS) : (coltile * NT * 16) / RS;
+
+    TRACE(0);
+    int coloff[NT];                                     // byte offsets into a window buffer
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        int lc;
+        stream_column_of<NT>(p, coltile, t, i16, c_first, coloff[t], lc);
+        coloff[t] *= 4;
+    }
+    // ROWP != 0: one channel per lane; the taps are immediates (a padding channel reads channel 0, unused)
+    const int lane_base = (c_first + i16 < g.C ? stream_chan_off(i16, p.pp) : 0) * 4;
+    auto read_b = [&](const char *Xw, int xo, float (&b)[NT]) {
+        if (ROWP) {
+            const float *q = (const float *)(Xw + lane_base + xo);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) b[j] = q[(j / 3) * ROWP + j % 3];
+        } else {
+#pragma unroll
+            for (int j = 0; j < NT; ++j) b[j] = *(const float *)(Xw + coloff[j] + xo);
+        }
+    };
+    // byte offset of staged position q inside a staged input channel; padded positions read offset 0
+    for (int q = tid; q < QT; q += kBlock) {
+        int off = 0;
+        if (q < p.q) {
+            uint32_t n_l, rem, h_l, w;
+            p.d_seg.divmod(q, n_l, rem);
+            p.d_wo.divmod(rem, h_l, w);
+            off = (n_l * p.iht * rowp + h_l * g.sh * rowp + w * g.sw) * 4;
+        }
+        xoff[q] = off;
+    }
+    // staging writes only cells that hold data: halo columns and unused channels stay zero
+    for (int e = tid; e < (2 * p.xbuf) >> 2; e += kBlock) ((float4_t *)smem)[e] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    float4_t acc[NT];
+#pragma unroll
+    for (int t = 0; t < NT; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    const int tiles_total = p.h_tiles * p.n_groups;
+    const int wt_begin = (int)((long)split * tiles_total / p.splits);
+    const int wt_end = (int)((long)(split + 1) * tiles_total / p.splits);
+
+    // ---- A operand: this lane's pieces of a tile, as byte offsets from the tile's first element ----
+    const int k_row = k0 + wk * 16 + i16;
+    uint32_t a_off[GPW];
+    uint32_t a_live = 0;                                // bit g: piece g holds real data for this lane
+#pragma unroll
+    for (int gi = 0; gi < GPW; ++gi) {
+        const int q = 16 * (wq * GPW + gi) + 4 * kk;
+        a_off[gi] = 0;
+        if (q < p.q && k_row < g.K) {
+            uint32_t n_l, rem;
+            p.d_seg.divmod(q, n_l, rem);
+            a_off[gi] = ((n_l * g.K + (wk * 16 + i16)) * L + rem) * ESZ;
+            a_live |= 1u << gi;
+        }
+    }
+    // ---- X window: this thread's staging slots (row pieces), decoded once ----
+    int x_pack[XS];              // LDS float index | ih_l << 20 | valid elements << 28, -1 = unused
+    uint32_t x_src[XS];          // byte offset from row 0 of the tile's first (image, channel)
+    {
+        const int x_total = p.ctch * p.nti * p.iht * (int)p.d_wv.d;
+#pragma unroll
+        for (int u = 0; u < XS; ++u) {
+            const int e = tid + u * kBlock;
+            x_pack[u] = -1; x_src[u] = 0;
+            if (e < x_total) {
+                uint32_t row, jv, c_l, rem, n_l, ih_l;
+                p.d_wv.divmod(e, row, jv);
+                p.d_rows.divmod(row, c_l, rem);
+                p.d_iht.divmod(rem, n_l, ih_l);
+                const int col0 = g.pw + jv * XV;             // window column of the first element
+                int nv = p.iwt - col0;                       // columns right of the window are not staged
+                nv = nv > XV ? XV : nv;
+                if (c_first + (int)c_l < g.C && nv > 0) {
+                    x_pack[u] = (int)(stream_chan_off(c_l, p.pp) + rem * rowp + col0) | (int)(ih_l << 20) | (nv << 28);
+                    x_src[u] = ((n_l * g.C + c_l) * (g.H * g.W) + jv * XV) * ESZ;
+                }
+            }
+        }
+    }
+    TRACE(1);
+
+    Vec<BF16, 4> ring[GPW];
+    Vec<BF16, XV> xr[XS];
+    uint32_t x_row_ok = 0;
+
+    // tile wt (or, past the end, a dummy re-read of the first element of the last tile)
+    auto tile_origin = [&](int wt, bool live, const char *&dy_base, const char *&x_base, int &ih0) {
+        const int w = live ? wt : wt_end - 1;
+        uint32_t ng, hti;
+        p.d_htiles.divmod(w, ng, hti);
+        const int n0 = ng * p.nti, h0 = hti * p.ht;
+        dy_base = dYp + (((long)n0 * g.K + k0) * g.Ho + h0) * g.Wo * ESZ;
+        x_base = Xp + ((long)n0 * g.C + c_first) * g.H * g.W * ESZ;
+        ih0 = h0 * g.sh - g.ph;
+    };
+    auto load_x = [&](int wt) {
+        const bool live = wt < wt_end;
+        const char *dyb, *xb;
+        int ih0;
+        tile_origin(wt, live, dyb, xb, ih0);
+        x_row_ok = 0;
+#pragma unroll
+        for (int u = 0; u < XS; ++u) {
+            int ih = ih0 + ((x_pack[u] >> 20) & 0xff);
+            if (ih >= 0 && ih < g.H) x_row_ok |= 1u << u;
+            ih = ih < 0 ? 0 : (ih >= g.H ? g.H - 1 : ih);
+            xr[u].load(xb, live ? x_src[u] + ih * (g.W * ESZ) : 0u);
+        }
+    };
+    auto commit_x = [&](float *buf) {
+#pragma unroll
+        for (int u = 0; u < XS; ++u)
+            if (x_pack[u] >= 0) {
+                float *dst = buf + (x_pack[u] & 0xfffff);
+                const int nv = x_pack[u] >> 28;
+                const bool ok = (x_row_ok >> u) & 1;
+#pragma unroll
+                for (int i = 0; i < XV; ++i)
+                    if (i < nv) dst[i] = ok ? xr[u].get(i) : 0.f;
+            }
+    };
+
+    // ---- prologue: window and A pieces of the first tile, window registers of the second ----
+    {
+        const char *dyb, *xb;
+        int ih0;
+        load_x(wt_begin);
+        tile_origin(wt_begin, true, dyb, xb, ih0);
+#pragma unroll
+        for (int gi = 0; gi < GPW; ++gi) ring[gi].load(dyb, a_off[gi]);
+        __syncthreads();                      // zero fill and tables complete
+        commit_x(Xs0);
+        load_x(wt_begin + 1);
+    }
+    TRACE(2);
+
+    const int xo_base = 16 * wq * GPW + 4 * kk;           // this lane's first position in a tile
+    int par = 0;
+    for (int wt = wt_begin; wt < wt_end; ++wt, par ^= 1) {
+        __syncthreads();   // window of tile wt is complete; everyone has left the buffer tile wt+1 goes to
+        if (wt == wt_begin) TRACE(3);
+        const char *Xw = (const char *)(Xs0 + par * p.xbuf);
+        // window of the next tile: registers -> the other buffer, then request the one after it
+        commit_x(Xs0 + (par ^ 1) * p.xbuf);
+        load_x(wt + 2);
+        const bool has_next = wt + 1 < wt_end;
+        const char *dyb, *xb;
+        int ih0;
+        tile_origin(wt + 1, has_next, dyb, xb, ih0);
+
+#ifdef WGRAD_TUNING
+        for (int rep = 0; rep < p.repeat; ++rep)
+#endif
+        {
+            // The 4 * GPW steps of the tile form one software pipeline: the LDS reads of step t+1
+            // (and the position offsets of the next group) are issued before the MFMAs of step t,
+            // across group boundaries too.  Everything below is unrolled; indices are constants.
+            constexpr int T = 4 * GPW;
+            float bq[2][NT];
+            float a_cur[4];
+            int4 xo_cur = *(const int4 *)(xoff + xo_base), xo_nxt = xo_cur;
+            {
+                const bool live = a_live & 1u;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a_cur[e] = live ? ring[0].get(e) : 0.f;
+                ring[0].load(dyb, has_next ? a_off[0] : 0u);      // piece 0 of the next tile
+            }
+            read_b(Xw, xo_cur.x, bq[0]);
+#pragma unroll
+            for (int t = 0; t < T; ++t) {
+                const int gi = t >> 2, st = t & 3;
+                if (st == 0 && gi + 1 < GPW) xo_nxt = *(const int4 *)(xoff + xo_base + 16 * (gi + 1));
+                if (t + 1 < T) {
+                    const int xo = st == 0 ? xo_cur.y : (st == 1 ? xo_cur.z : (st == 2 ? xo_cur.w : xo_nxt.x));
+                    read_b(Xw, xo, bq[(t + 1) & 1]);
+                }
+                WGRAD_SCHED_FENCE();
+#pragma unroll
+                for (int j = 0; j < NT; ++j)
+                    acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[st], bq[t & 1][j], acc[j], 0, 0, 0);
+                WGRAD_SCHED_FENCE();
+                WGRAD_STEP_PATTERN(NT);
+                if (st == 3 && gi + 1 < GPW) {
+                    // next group: its A piece leaves the ring (which is refilled for the next tile)
+                    xo_cur = xo_nxt;
+                    const bool live = (a_live >> (gi + 1)) & 1u;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) a_cur[e] = live ? ring[gi + 1].get(e) : 0.f;
+                    ring[gi + 1].load(dyb, has_next ? a_off[gi + 1] : 0u);
+                }
+            }
+        }
+        if (wt == wt_begin) TRACE(4);
+    }
+    TRACE(8);
+
+    // ---- epilogue: every wavefront parks its accumulators in LDS in output order; then all
+    //      threads add the WQ position slices and write rows of the result, coalesced ----
+    __syncthreads();
+    TRACE(9);
+    {
+        constexpr int EP = NCB + 1;                         // row pitch of the exchange buffer
+        float *red = smem;                                  // [WQ][KT][EP]
+#pragma unroll
+        for (int j = 0; j < NT; ++j) {
+            int lo, lc;
+            stream_column_of<NT>(p, coltile, j, i16, c_first, lo, lc);
+            if (lc < 0) lc = p.tap_mode ? (p.tile_c0[j] + i16) * RS + p.tile_tap[j] : j * 16 + i16;   // padding column: parked, never written out
+#pragma unroll
+            for (int v = 0; v < 4; ++v) red[(wq * KT + wk * 16 + 4 * kk + v) * EP + lc] = acc[j][v];
+        }
+        __syncthreads();
+        TRACE(14);
+        const int colbase = p.tap_mode ? c_first * RS : coltile * NCB;
+        float *out = p.out[prob] + (long)split * g.K * CRS;
+        for (int o = tid; o < KT * NCB; o += kBlock) {
+            const int row = o / NCB, lc = o % NCB;
+            float sum = red[row * EP + lc];
+#pragma unroll
+            for (int w = 1; w < WQ; ++w) sum += red[(w * KT + row) * EP + lc];
+            const int k = k0 + row, col = colbase + lc;
+            if (k < g.K && col < CRS) out[(long)k * CRS + col] = sum;
+        }
+    }
+    TRACE(10);
+}
+
+// Per-K-tile-width launchers, each instantiated in its own translation unit.
+void stream_launch_w1(const StreamParams &p, int nt, int xv, int gpw, int rowp, int grid, size_t lds, hipStream_t st);
+void stream_launch_w2(const StreamParams &p, int nt, int xv, int gpw, int rowp, int grid, size_t lds, hipStream_t st);
+void stream_launch_w4(const StreamParams &p, int nt, int xv, int gpw, int rowp, int grid, size_t lds, hipStream_t st);
+
+template <int NT, int WK, bool BF16, int XV, int ROWP>
+static void stream_inst(const StreamParams &p, int gpw, int grid, size_t lds, hipStream_t st)
+{
+    if (gpw == 8) WGRAD_LAUNCH((wgrad_exact_stream<NT, WK, BF16, XV, 8, ROWP>), dim3(grid), dim3(kBlock), lds, st, p);
+    else WGRAD_LAUNCH((wgrad_exact_stream<NT, WK, BF16, XV, 4, ROWP>), dim3(grid), dim3(kBlock), lds, st, p);
+}
+
+template <int WK, bool BF16>
+static void stream_pick(const StreamParams &p, int nt, int xv, int gpw, int rowp, int grid, size_t lds, hipStream_t st)
+{
+    if (nt == 9) {
+        if (rowp == 4 && xv == 2) stream_inst<9, WK, BF16, 2, 4>(p, gpw, grid, lds, st);
+        else if (rowp == 12 && xv == 4) stream_inst<9, WK, BF16, 4, 12>(p, gpw, grid, lds, st);
+        else if (rowp == 20 && xv == 4) stream_inst<9, WK, BF16, 4, 20>(p, gpw, grid, lds, st);
+        else if (rowp == 36 && xv == 4) stream_inst<9, WK, BF16, 4, 36>(p, gpw, grid, lds, st);
+        else if (xv == 4) stream_inst<9, WK, BF16, 4, 0>(p, gpw, grid, lds, st);
+        else stream_inst<9, WK, BF16, 2, 0>(p, gpw, grid, lds, st);
+    } else if (nt == 4) {
+        if (xv == 4) stream_inst<4, WK, BF16, 4, 0>(p, gpw, grid, lds, st);
+        else stream_inst<4, WK, BF16, 2, 0>(p, gpw, grid, lds, st);
+    } else {
+        if (xv == 4) stream_inst<2, WK, BF16, 4, 0>(p, gpw, grid, lds, st);
+        else stream_inst<2, WK, BF16, 2, 0>(p, gpw, grid, lds, st);
+    }
+}
+
+// pairs (rowp, xv) that have an immediate-offset instantiation
+inline bool stream_has_rowp(int rowp, int xv) { return (rowp == 4 && xv == 2) || ((rowp == 12 || rowp == 20 || rowp == 36) && xv == 4); }
+
+}  // namespace wgrad

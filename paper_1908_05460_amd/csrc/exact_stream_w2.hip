@@ -1,0 +1,20 @@
+// Instantiations of the streaming exact-gradient kernel for K tiles of 32 output channels.
+
+#include "exact_stream_kernel.hpp"
+
+namespace wgrad {
+
+void stream_launch_w2(const StreamParams &p, int nt, int xv, int gpw, int rowp, int grid, size_t lds, hipStream_t st)
+{
+    if (p.g.bf16) stream_pick<2, true>(p, nt, xv, gpw, rowp, grid, lds, st);
+    else stream_pick<2, false>(p, nt, xv, gpw, rowp, grid, lds, st);
+}
+
+
+
+
+
+
+
+
+}  // namespace wgrad
