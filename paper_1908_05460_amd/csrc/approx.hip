@@ -333,6 +333,141 @@ __global__ __launch_bounds__(kBlock) void approx_gather_lds3x3(ApproxBatch ab, G
     }
 }
 
+// ------------------------------------------------------------------------------------
+// fused form (large maps, few output channels: the regime of the direct gather).  One
+// workgroup = one output channel k and one chunk of the batch; each wavefront walks its
+// images: it scans the map dY[n,k,:,:] (16-byte pieces, all 64 lanes; the next image's map
+// is already in flight), reduces (|v| bits, position) and the sum across the wavefront,
+// and immediately gathers the C*R*S patch the selected position sees, one or more dW
+// entries per lane, accumulating in registers over its images.  The four wavefronts'
+// sums are added through LDS.  Position and sum never travel through memory; dY is read
+// exactly once.  Requires Ho*Wo <= 1024 (a multiple of 4) and C*R*S <= 576.
+// ------------------------------------------------------------------------------------
+constexpr int kFusedJ = 9;       // dW entries of one output channel per lane
+constexpr int kFusedV = 4;       // 4-element pieces of one map per lane
+
+struct FusedParams {
+    int chunk_n;
+    float scale;
+    FastDiv d_rs, d_s, d_wo;
+    int32_t *flat_out;           // optional user outputs (single-problem launches only)
+    float *sum_out;
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void approx_fused(ApproxBatch ab, Geometry g, FusedParams fp)
+{
+    typedef typename Raw4<BF16>::type raw4;
+    constexpr int ESZ = BF16 ? 2 : 4;
+    __shared__ float red[4][kFusedJ * 64];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int k = blockIdx.x;
+    const char *__restrict__ X = (const char *)ab.X[blockIdx.z];
+    const char *__restrict__ dY = (const char *)ab.dY[blockIdx.z];
+    float *__restrict__ out = ab.out[blockIdx.z];
+    const int L = g.Ho * g.Wo, RS = g.R * g.S, CRS = g.C * RS, HW = g.H * g.W;
+    const int n_begin = blockIdx.y * fp.chunk_n;
+    const int n_end = n_begin + fp.chunk_n < g.N ? n_begin + fp.chunk_n : g.N;
+
+    // the dW entries j = lane + 64*jj of channel k that this lane accumulates
+    int xo[kFusedJ], rs[kFusedJ];
+    float acc[kFusedJ];
+#pragma unroll
+    for (int jj = 0; jj < kFusedJ; ++jj) {
+        const int j = lane + 64 * jj;
+        uint32_t c, tap, r, s2;
+        fp.d_rs.divmod(j, c, tap);
+        fp.d_s.divmod(tap, r, s2);
+        xo[jj] = (int)(c * HW + r * g.W + s2);
+        rs[jj] = j < CRS ? (int)(r << 16 | s2) : -1;
+        acc[jj] = 0.f;
+    }
+
+    float x_pend[kFusedJ], S_pend = 0.f;       // patch and sum of the previous image, not yet accumulated
+#pragma unroll
+    for (int jj = 0; jj < kFusedJ; ++jj) x_pend[jj] = 0.f;
+    raw4 cur[kFusedV], nxt[kFusedV];
+    auto load_map = [&](int n, raw4 (&m)[kFusedV]) {
+        const char *base = dY + ((long)n * g.K + k) * L * ESZ;
+#pragma unroll
+        for (int v = 0; v < kFusedV; ++v) {
+            const int e = (lane + 64 * v) * 4;
+            if (e < L) m[v] = *(const raw4 *)(base + (long)e * ESZ);
+        }
+    };
+    if (n_begin + wave < n_end) load_map(n_begin + wave, nxt);
+    for (int n = n_begin + wave; n < n_end; n += 4) {
+#pragma unroll
+        for (int v = 0; v < kFusedV; ++v) cur[v] = nxt[v];
+        if (n + 4 < n_end) load_map(n + 4, nxt);
+
+        // ---- select: per-lane scan in ascending position, then a butterfly over the wavefront ----
+        uint32_t best_key = 0, best_pos = 0;
+        bool have = false;
+        float sum = 0.f;
+#pragma unroll
+        for (int v = 0; v < kFusedV; ++v) {
+            const int e = (lane + 64 * v) * 4;
+            if (e < L) {
+                uint32_t bits[4];
+                if (BF16) {
+                    const uint2 r2 = *(const uint2 *)&cur[v];
+                    bits[0] = r2.x << 16; bits[1] = r2.x & 0xffff0000u; bits[2] = r2.y << 16; bits[3] = r2.y & 0xffff0000u;
+                } else {
+                    const uint4 r4 = *(const uint4 *)&cur[v];
+                    bits[0] = r4.x; bits[1] = r4.y; bits[2] = r4.z; bits[3] = r4.w;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t key = mag_key<BF16>(bits[i]);
+                    if (!have || key > best_key) { best_key = key; best_pos = e + i; have = true; }
+                    sum += __uint_as_float(bits[i]);
+                }
+            }
+        }
+        unsigned long long packed = have ? ((unsigned long long)best_key << 32) | (uint32_t)~best_pos : 0ull;
+#pragma unroll
+        for (int d = 32; d > 0; d >>= 1) {
+            const unsigned long long other = __shfl_xor(packed, d, 64);
+            const float osum = __shfl_xor(sum, d, 64);
+            packed = other > packed ? other : packed;
+            sum += osum;
+        }
+        const int pos = __builtin_amdgcn_readfirstlane((int)~(uint32_t)packed);
+        const float S = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sum)));
+        if (lane == 0) {
+            if (fp.flat_out) fp.flat_out[(long)n * g.K + k] = pos;
+            if (fp.sum_out) fp.sum_out[(long)n * g.K + k] = S;
+        }
+        // ---- the patch of the previous image has had this image's scan to arrive: accumulate it ----
+#pragma unroll
+        for (int jj = 0; jj < kFusedJ; ++jj) acc[jj] = fmaf(S_pend, x_pend[jj], acc[jj]);
+        // ---- request the patch of the selected position; it is accumulated one image later ----
+        uint32_t h, w;
+        fp.d_wo.divmod(pos, h, w);
+        const int ihb = (int)h * g.sh - g.ph, iwb = (int)w * g.sw - g.pw;
+        const char *Xn = X + ((long)n * g.C * HW + (long)ihb * g.W + iwb) * ESZ;   // may lie before X: only taps inside X are read
+#pragma unroll
+        for (int jj = 0; jj < kFusedJ; ++jj) {
+            const int ih = ihb + (rs[jj] >> 16), iw = iwb + (rs[jj] & 0xffff);
+            x_pend[jj] = 0.f;
+            if (rs[jj] >= 0 && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
+                x_pend[jj] = BF16 ? bf16_bits_to_float(*(const uint16_t *)(Xn + (long)xo[jj] * ESZ))
+                                  : *(const float *)(Xn + (long)xo[jj] * ESZ);
+        }
+        S_pend = S;
+    }
+#pragma unroll
+    for (int jj = 0; jj < kFusedJ; ++jj) acc[jj] = fmaf(S_pend, x_pend[jj], acc[jj]);
+    // ---- add the four wavefronts' sums and write this chunk's row of the result ----
+#pragma unroll
+    for (int jj = 0; jj < kFusedJ; ++jj) red[wave][jj * 64 + lane] = acc[jj];
+    __syncthreads();
+    float *o = out + ((long)blockIdx.y * g.K + k) * CRS;
+    for (int j = tid; j < CRS; j += kBlock) o[j] = (red[0][j] + red[1][j] + red[2][j] + red[3][j]) * fp.scale;
+}
+
 #ifndef WGRAD_APPROX_THREADS   // threads to aim for when chunking the batch (direct form)
 #define WGRAD_APPROX_THREADS (256 * 1024)
 #endif
@@ -340,7 +475,7 @@ __global__ __launch_bounds__(kBlock) void approx_gather_lds3x3(ApproxBatch ab, G
 #define WGRAD_GATHER_BLOCKS 256
 #endif
 
-ApproxPlan plan_approx(const Geometry &g, bool allow_lds)
+ApproxPlan plan_approx(const Geometry &g, bool allow_lds, bool allow_fused)
 {
     ApproxPlan pl{};
     const long outs = g.dw_elems();
@@ -349,7 +484,7 @@ ApproxPlan plan_approx(const Geometry &g, bool allow_lds)
     // haloed plane: rows/cols -pad .. max(last tap the positions can reach, last row/col of X)
     const int hp = std::max((g.Ho - 1) * g.sh + 3, g.H + g.ph), wp = std::max((g.Wo - 1) * g.sw + 3, g.W + g.pw);
     const int pitch = (hp * wp) | 1;
-    pl.use_lds = allow_lds && g.R == 3 && g.S == 3 && g.C >= 16 && (long)g.K * 9 >= 2l * HW && HW % 4 == 0
+    pl.use_lds = allow_lds && g.R == 3 && g.S == 3 && g.C >= 16 && g.K >= 128 && (long)g.K * 9 >= 2l * HW && HW % 4 == 0
                  && kGatherCT * HW <= kGatherSlots * kBlock * 4
                  && (size_t)2 * kGatherCT * pitch * 4 <= kGatherLds;
     long chunks;
@@ -370,6 +505,12 @@ ApproxPlan plan_approx(const Geometry &g, bool allow_lds)
         chunks = tiles >= want_blocks ? 1 : (want_blocks + tiles - 1) / tiles;
         const long max_chunks = (g.N + pl.nb - 1) / pl.nb;
         if (chunks > max_chunks) chunks = max_chunks;
+    } else if (allow_fused && tune_int("WGRAD_APPROX_FUSED", 1) && (g.Ho * g.Wo) % 4 == 0
+               && g.Ho * g.Wo <= 64 * kFusedV * 4 && g.crs() <= 64 * kFusedJ) {
+        // fused form: one workgroup per (output channel, batch chunk); four images at a time
+        pl.fused = 1;
+        chunks = (tune_int("WGRAD_FUSED_BLOCKS", 768) + g.K - 1) / g.K;
+        if (chunks > (g.N + 7) / 8) chunks = (g.N + 7) / 8;         // at least two images per wavefront
     } else {
         chunks = (tune_int("WGRAD_APPROX_THREADS", WGRAD_APPROX_THREADS) + outs - 1) / outs;
         if (chunks > g.N) chunks = g.N;
@@ -382,9 +523,9 @@ ApproxPlan plan_approx(const Geometry &g, bool allow_lds)
     pl.off_sum = off; off += align_up((size_t)g.N * g.K * 4);
     pl.off_part = off; off += pl.chunks > 1 ? align_up((size_t)pl.chunks * outs * 4) : 0;
     pl.ws_bytes = off;
-    // a caller whose X is not 16-byte aligned gets the direct form: size the workspace for both
-    if (pl.use_lds) {
-        const size_t alt = plan_approx(g, false).ws_bytes;
+    // tensors that are not 16-byte aligned get the three-kernel direct form: size the workspace for both
+    if (pl.use_lds || pl.fused) {
+        const size_t alt = plan_approx(g, false, false).ws_bytes;
         if (alt > pl.ws_bytes) pl.ws_bytes = alt;
     }
     return pl;
@@ -410,9 +551,19 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
                   int32_t *idx_out, float *sum_out, void *ws, hipStream_t st)
 {
     bool aligned = true;
-    for (int i = 0; i < b.n; ++i) aligned = aligned && ((uintptr_t)b.X[i] % (g.bf16 ? 8 : 16)) == 0;
-    const ApproxPlan pl = (plan.use_lds && !aligned) ? plan_approx(g, false) : plan;
+    for (int i = 0; i < b.n; ++i)
+        aligned = aligned && ((uintptr_t)b.X[i] % (g.bf16 ? 8 : 16)) == 0 && ((uintptr_t)b.dY[i] % (g.bf16 ? 8 : 16)) == 0;
+    ApproxPlan pl = ((plan.use_lds || plan.fused) && !aligned) ? plan_approx(g, false, false) : plan;
     const long outs = g.dw_elems();
+    if (pl.fused && b.n > 1) {
+        // the workgroup target is for the whole launch: a batch chunks each problem less finely
+        long chunks = (tune_int("WGRAD_FUSED_BLOCKS", 768) + (long)g.K * b.n - 1) / ((long)g.K * b.n);
+        if (chunks < 1) chunks = 1;
+        if (chunks < pl.chunks) {
+            pl.chunk_n = (int)((g.N + chunks - 1) / chunks);
+            pl.chunks = (g.N + pl.chunk_n - 1) / pl.chunk_n;
+        }
+    }
     // problem i owns the i-th slice (plan.ws_bytes each) of the workspace
     ApproxBatch ab{};
     for (int i = 0; i < kMaxBatch; ++i) {
@@ -423,10 +574,26 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         ab.sum[i] = (float *)(slice + pl.off_sum);
         ab.out[i] = pl.chunks > 1 ? (float *)(slice + pl.off_part) : b.dW[j];
     }
-    int rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st);
+    const float kscale = pl.chunks > 1 ? 1.0f : scale;
+    int rc;
+    if (pl.fused) {
+        FusedParams fp;
+        fp.chunk_n = pl.chunk_n; fp.scale = kscale;
+        fp.d_rs = FastDiv(g.R * g.S); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
+        fp.flat_out = idx_out; fp.sum_out = sum_out;
+        const dim3 grid((unsigned)g.K, (unsigned)pl.chunks, (unsigned)b.n);
+        if (g.bf16) WGRAD_LAUNCH((approx_fused<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
+        else        WGRAD_LAUNCH((approx_fused<false>), grid, dim3(kBlock), 0, st, ab, g, fp);
+        rc = launch_status();
+        if (rc != WGRAD_OK) return rc;
+        if (pl.chunks > 1)
+            return launch_combine((const float *)((char *)ws + pl.off_part), (long)(plan.ws_bytes / 4), pl.chunks, outs,
+                                  scale, b.dW, b.n, st);
+        return WGRAD_OK;
+    }
+    rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st);
     if (rc != WGRAD_OK) return rc;
 
-    const float kscale = pl.chunks > 1 ? 1.0f : scale;
     if (pl.use_lds) {
         const dim3 grid((unsigned)(pl.ctiles * pl.ktiles), (unsigned)pl.chunks, (unsigned)b.n);
         const size_t lds = (size_t)2 * pl.nb * kGatherCT * pl.pitch * 4;

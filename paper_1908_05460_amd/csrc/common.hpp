@@ -91,10 +91,10 @@ size_t exact_ws_per_problem(const Geometry &g, const ExactPlan &pl);
 
 struct ApproxPlan {
     int chunks, chunk_n;             // batch chunks whose partial sums are combined afterwards
-    int use_lds, m, nb, pitch, wp, ctiles, ktiles;   // LDS form of the gather: tile shape
+    int use_lds, fused, m, nb, pitch, wp, ctiles, ktiles;   // LDS form of the gather: tile shape
     size_t off_idx, off_sum, off_part, ws_bytes;
 };
-ApproxPlan plan_approx(const Geometry &g, bool allow_lds = true);
+ApproxPlan plan_approx(const Geometry &g, bool allow_lds = true, bool allow_fused = true);
 int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, hipStream_t st);
 int launch_approx(const Geometry &g, const ApproxPlan &pl, const Batch &b, float scale,
                   int32_t *idx_out, float *sum_out, void *ws, hipStream_t st);

@@ -576,13 +576,20 @@ static int launch_exact_staged(const Geometry &g, const ExactPlan &pl, const voi
 int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void *ws, hipStream_t st)
 {
     if (plan.stream && batch_aligned(g, b, plan.xv)) {
-        // one launch for the whole batch; problem i owns the i-th slice of the workspace
+        // one launch for the whole batch; problem i owns the i-th slice of the workspace.  The
+        // workgroup target is for the whole launch: a batch splits each reduction less finely.
+        ExactPlan pl = plan;
+        if (b.n > 1) {
+            const long out_tiles = (long)pl.ktiles * pl.ctiles * b.n;
+            long splits = (tune_int("WGRAD_EXACT_BLOCKS", WGRAD_EXACT_BLOCKS) + out_tiles - 1) / out_tiles;
+            if (splits < pl.splits) pl.splits = (int)(splits < 1 ? 1 : splits);
+        }
         float *out[kMaxBatch];
-        const long prob_stride = (long)plan.splits * g.dw_elems();
-        for (int i = 0; i < b.n; ++i) out[i] = plan.splits > 1 ? (float *)ws + i * prob_stride : b.dW[i];
-        int rc = launch_exact_stream(g, plan, b, out, st);
+        const long prob_stride = (long)pl.splits * g.dw_elems();
+        for (int i = 0; i < b.n; ++i) out[i] = pl.splits > 1 ? (float *)ws + i * prob_stride : b.dW[i];
+        int rc = launch_exact_stream(g, pl, b, out, st);
         if (rc != WGRAD_OK) return rc;
-        if (plan.splits > 1) return launch_combine((const float *)ws, prob_stride, plan.splits, g.dw_elems(), 1.0f, b.dW, b.n, st);
+        if (pl.splits > 1) return launch_combine((const float *)ws, prob_stride, pl.splits, g.dw_elems(), 1.0f, b.dW, b.n, st);
         return WGRAD_OK;
     }
     // staged form: one problem at a time (shapes or alignments the streaming form does not take)

@@ -29,7 +29,6 @@ bool plan_exact_stream(const Geometry &g, ExactPlan &pl)
     const int L = g.Ho * g.Wo;
     const int xv = g.W % 4 == 0 ? 4 : (g.W % 2 == 0 ? 2 : 0);
     if (!xv || L % 4 != 0) return false;
-    const int XS = stream_xslots(pl.wk);
     for (int gpw = 8; gpw >= 4; gpw -= 4) {
         const int qt = 16 * gpw * WQ;
         int nti, ht;
@@ -52,7 +51,9 @@ bool plan_exact_stream(const Geometry &g, ExactPlan &pl)
         const size_t red = (size_t)4 * 16 * (pl.nt * 16 + 1) * 4;
         if (red > lds) lds = red;
         const long x_slots = (long)pl.ctch * nti * iht * (g.W / xv);
-        if (lds > 64 * 1024 || x_slots > (long)XS * kBlock || iht > 255 || (long)xbuf >= (1 << 20)) continue;
+        // up to 64 KB two workgroups share a CU; a larger window (strided layers) gets a CU to itself
+        const size_t lds_cap = (size_t)tune_int("WGRAD_STREAM_LDS_KB", 64) * 1024;
+        if (lds > lds_cap || x_slots > (long)stream_xslots(pl.wk, gpw) * kBlock || iht > 255 || (long)xbuf >= (1 << 20)) continue;
         if ((long)nti * g.K * L * 4 >= (1l << 31) || (long)nti * g.C * g.H * g.W * 4 >= (1l << 31)) continue;
         pl.stream = 1; pl.gpw = gpw; pl.xv = xv;
         pl.nti = nti; pl.ht = ht; pl.q = q; pl.qpad = qt; pl.qp = 0;

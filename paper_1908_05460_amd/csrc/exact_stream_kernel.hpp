@@ -65,7 +65,11 @@ struct StreamParams {
 #endif
 };
 
-__host__ __device__ constexpr int stream_xslots(int wk) { return wk == 1 ? 9 : (wk == 2 ? 5 : 4); }
+// Window staging slots (16- or 8-byte row pieces) per thread and tile.
+__host__ __device__ constexpr int stream_xslots(int wk, int gpw)
+{
+    return wk == 1 ? (gpw == 8 ? 9 : 5) : (wk == 2 ? (gpw == 8 ? 5 : 3) : 4);
+}
 
 // LDS offset (floats) of staged channel c_l.  In a step the four lane groups kk of an MFMA
 // operand read positions 4 apart, so channels are placed such that
@@ -112,7 +116,7 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams 
     constexpr int ESZ = BF16 ? 2 : 4;
     constexpr int NCB = NT * 16;
     constexpr int QT = 16 * GPW * WQ;                   // positions per tile, padded
-    constexpr int XS = stream_xslots(WK);
+    constexpr int XS = stream_xslots(WK, GPW);
     extern __shared__ float smem[];
     float *Xs0 = smem;                                  // [2][xbuf]
     int *xoff = (int *)(smem + 2 * p.xbuf);             // [QT] byte offsets
@@ -279,14 +283,17 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams 
     for (int wt = wt_begin; wt < wt_end; ++wt, par ^= 1) {
         __syncthreads();   // window of tile wt is complete; everyone has left the buffer tile wt+1 goes to
         if (wt == wt_begin) TRACE(3);
+        if (wt == wt_begin + 1) TRACE(5);
         const char *Xw = (const char *)(Xs0 + par * p.xbuf);
         // window of the next tile: registers -> the other buffer, then request the one after it
         commit_x(Xs0 + (par ^ 1) * p.xbuf);
+        if (wt == wt_begin + 1) TRACE(6);
         load_x(wt + 2);
         const bool has_next = wt + 1 < wt_end;
         const char *dyb, *xb;
         int ih0;
         tile_origin(wt + 1, has_next, dyb, xb, ih0);
+        if (wt == wt_begin + 1) TRACE(7);
 
 #ifdef WGRAD_TUNING
         for (int rep = 0; rep < p.repeat; ++rep)
@@ -331,6 +338,7 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams 
             }
         }
         if (wt == wt_begin) TRACE(4);
+        if (wt == wt_begin + 1) TRACE(11);
     }
     TRACE(8);
 
@@ -373,8 +381,16 @@ void stream_launch_w4(const StreamParams &p, int nt, int xv, int gpw, int rowp, 
 template <int NT, int WK, bool BF16, int XV, int ROWP>
 static void stream_inst(const StreamParams &p, int gpw, int grid, size_t lds, hipStream_t st)
 {
-    if (gpw == 8) WGRAD_LAUNCH((wgrad_exact_stream<NT, WK, BF16, XV, 8, ROWP>), dim3(grid), dim3(kBlock), lds, st, p);
-    else WGRAD_LAUNCH((wgrad_exact_stream<NT, WK, BF16, XV, 4, ROWP>), dim3(grid), dim3(kBlock), lds, st, p);
+    // more than 64 KB of dynamic LDS has to be granted per kernel function (the CU has 160 KB)
+    if (gpw == 8) {
+        if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)wgrad_exact_stream<NT, WK, BF16, XV, 8, ROWP>,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return;
+        WGRAD_LAUNCH((wgrad_exact_stream<NT, WK, BF16, XV, 8, ROWP>), dim3(grid), dim3(kBlock), lds, st, p);
+    } else {
+        if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)wgrad_exact_stream<NT, WK, BF16, XV, 4, ROWP>,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return;
+        WGRAD_LAUNCH((wgrad_exact_stream<NT, WK, BF16, XV, 4, ROWP>), dim3(grid), dim3(kBlock), lds, st, p);
+    }
 }
 
 template <int WK, bool BF16>
