@@ -170,8 +170,8 @@ __global__ __launch_bounds__(kBlock) void approx_gather_direct(ApproxBatch ab, G
 
 // ------------------------------------------------------------------------------------
 // gather, LDS form (3x3 filters): used when the K patches of an image cover its input
-// planes many times over (small planes, many output channels).  A workgroup owns
-// 4*M output channels x 64 input channels and walks a chunk of the batch in groups of
+// planes many times over (small planes, many output channels).  A workgroup (8 wavefronts) owns
+// 8*M output channels x 64 input channels and walks a chunk of the batch in groups of
 // `nb` images; every wavefront handles M output channels with one input channel per
 // lane and keeps its 9*M sums in registers.
 //
@@ -186,6 +186,7 @@ __global__ __launch_bounds__(kBlock) void approx_gather_direct(ApproxBatch ab, G
 // the window origin is scalar arithmetic and S is a scalar multiplier.
 // ------------------------------------------------------------------------------------
 constexpr int kGatherCT = 64;
+constexpr int kGatherBlock = 512;   // 8 wavefronts: two per SIMD, so one hides the LDS and scalar latencies of the other
 constexpr int kGatherSlots = 8;      // 16-byte loads per thread and group
 constexpr size_t kGatherLds = 64 * 1024;
 
@@ -200,7 +201,7 @@ struct GatherParams {
 };
 
 template <bool BF16, int M>
-__global__ __launch_bounds__(kBlock) void approx_gather_lds3x3(ApproxBatch ab, Geometry g, GatherParams gp)
+__global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch ab, Geometry g, GatherParams gp)
 {
     const void *__restrict__ X = ab.X[blockIdx.z];
     const int32_t *__restrict__ hw = ab.hw[blockIdx.z];
@@ -212,7 +213,7 @@ __global__ __launch_bounds__(kBlock) void approx_gather_lds3x3(ApproxBatch ab, G
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int ctile = blockIdx.x % gp.ctiles, ktile = blockIdx.x / gp.ctiles;
     const int c0 = ctile * kGatherCT;
-    const int k_base = ktile * (4 * M) + wave * M;
+    const int k_base = ktile * (kGatherBlock / 64 * M) + wave * M;
     const int HW = g.H * g.W, hw4 = HW >> 2;
     const int nb = gp.nb, pitch = gp.pitch, WP = gp.wp;
     const int n_begin = blockIdx.y * gp.chunk_n;
@@ -225,7 +226,7 @@ __global__ __launch_bounds__(kBlock) void approx_gather_lds3x3(ApproxBatch ab, G
     d_run4.m = run4 > 1 ? (uint32_t)((1ull << 32) / (uint32_t)run4) + 1u : 0u;
     d_run4.one = run4 > 1 ? 0u : 0xffffffffu;
 
-    for (int e = tid; e < 2 * buf_floats; e += kBlock) xs[e] = 0.f;   // halo (and everything else) = 0
+    for (int e = tid; e < 2 * buf_floats; e += kGatherBlock) xs[e] = 0.f;   // halo (and everything else) = 0
 
     float acc[M][9];
 #pragma unroll
@@ -249,7 +250,7 @@ __global__ __launch_bounds__(kBlock) void approx_gather_lds3x3(ApproxBatch ab, G
         const int total = nb_cur * run4;
 #pragma unroll
         for (int u = 0; u < kGatherSlots; ++u) {
-            const int e = tid + u * kBlock;
+            const int e = tid + u * kGatherBlock;
             if (e < total) {
                 uint32_t n_l, rem;
                 d_run4.divmod(e, n_l, rem);
@@ -269,7 +270,7 @@ __global__ __launch_bounds__(kBlock) void approx_gather_lds3x3(ApproxBatch ab, G
             const int total = nb_cur * run4;
 #pragma unroll
             for (int u = 0; u < kGatherSlots; ++u) {
-                const int e = tid + u * kBlock;
+                const int e = tid + u * kGatherBlock;
                 if (e < total) {
                     uint32_t n_l, rem, c_l, q4;
                     d_run4.divmod(e, n_l, rem);
@@ -485,21 +486,21 @@ ApproxPlan plan_approx(const Geometry &g, bool allow_lds, bool allow_fused)
     const int hp = std::max((g.Ho - 1) * g.sh + 3, g.H + g.ph), wp = std::max((g.Wo - 1) * g.sw + 3, g.W + g.pw);
     const int pitch = (hp * wp) | 1;
     pl.use_lds = allow_lds && g.R == 3 && g.S == 3 && g.C >= 16 && g.K >= 128 && (long)g.K * 9 >= 2l * HW && HW % 4 == 0
-                 && kGatherCT * HW <= kGatherSlots * kBlock * 4
+                 && kGatherCT * HW <= kGatherSlots * kGatherBlock * 4
                  && (size_t)2 * kGatherCT * pitch * 4 <= kGatherLds;
     long chunks;
     if (pl.use_lds) {
-        pl.m = g.K >= 256 ? 4 : (g.K >= 32 ? 2 : 1);
+        pl.m = g.K >= 256 ? 2 : 1;
         pl.pitch = pitch;
         pl.wp = wp;
         // images per group: at most 8 16-byte loads per thread, one lane per (image, channel) pair
-        pl.nb = kGatherSlots * kBlock * 4 / (kGatherCT * HW);
+        pl.nb = kGatherSlots * kGatherBlock * 4 / (kGatherCT * HW);
         if (pl.nb > 64 / pl.m) pl.nb = 64 / pl.m;
         const int lds_cap = (int)(kGatherLds / ((size_t)2 * kGatherCT * pl.pitch * 4));   // double buffered
         if (pl.nb > lds_cap) pl.nb = lds_cap;
         if (pl.nb > g.N) pl.nb = g.N;
         pl.ctiles = (g.C + kGatherCT - 1) / kGatherCT;
-        pl.ktiles = (g.K + 4 * pl.m - 1) / (4 * pl.m);
+        pl.ktiles = (g.K + 8 * pl.m - 1) / (8 * pl.m);
         const long tiles = (long)pl.ctiles * pl.ktiles;
         const int want_blocks = tune_int("WGRAD_GATHER_BLOCKS", WGRAD_GATHER_BLOCKS);
         chunks = tiles >= want_blocks ? 1 : (want_blocks + tiles - 1) / tiles;
@@ -540,9 +541,8 @@ static void launch_gather_lds(const ApproxPlan &pl, dim3 grid, size_t lds, hipSt
     gp.d_hw4 = FastDiv(g.H * g.W / 4);        // dividends stay below 64 * H*W, far under the 2^32 bound
     gp.d_w = FastDiv(g.W);
     gp.scale = scale;
-#define GL_ARGS grid, dim3(kBlock), lds, st, ab, g, gp
-    if (pl.m == 4) WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 4>), GL_ARGS);
-    else if (pl.m == 2) WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 2>), GL_ARGS);
+#define GL_ARGS grid, dim3(kGatherBlock), lds, st, ab, g, gp
+    if (pl.m == 2) WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 2>), GL_ARGS);
     else WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 1>), GL_ARGS);
 #undef GL_ARGS
 }
