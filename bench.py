@@ -44,6 +44,9 @@ def main():
     ap.add_argument("--layer-reps", type=int, default=20, help="back-to-back launches per layer in the per-layer pass")
     ap.add_argument("--cpu-budget-s", type=float, default=20.0, help="CPU seconds to spend on the oracle baseline (0 = skip)")
     ap.add_argument("--scale", type=float, default=1.0 / 128)
+    ap.add_argument("--phases", default="exact,approx,zero,random",
+                    help="phases a step enqueues; anything but the default is for counter runs that must "
+                         "attribute every dispatch to one phase, and the printed line then says so")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 256 MiB device copy 10 times and exit (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -100,18 +103,20 @@ def main():
     dw_total = sum(l.K * l.C * l.R * l.S for l in stack)
 
     phases = ("exact", "approx", "zero", "random")
+    on = set(args.phases.split(","))
+    assert on <= set(phases) and on, "--phases takes a comma list of exact,approx,zero,random"
     ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
 
     def step(i, events=None):
         s = sets[i % copies]
         if events: events[0].record()
-        s.run(m_exact, ws)
+        if "exact" in on: s.run(m_exact, ws)
         if events: events[1].record()
-        s.run(m_approx, ws, scale=args.scale)
+        if "approx" in on: s.run(m_approx, ws, scale=args.scale)
         if events: events[2].record()
-        s.run(m_zero, ws)
+        if "zero" in on: s.run(m_zero, ws)
         if events: events[3].record()
-        s.run(m_random, ws, sigma=1.0 / 128, seed=inputs.ROOT_SEED, offset=i * dw_total)
+        if "random" in on: s.run(m_random, ws, sigma=1.0 / 128, seed=inputs.ROOT_SEED, offset=i * dw_total)
         if events: events[4].record()
 
     for i in range(args.warmup):
@@ -147,7 +152,9 @@ def main():
     tot = {"exact_us": 0.0, "approx_us": 0.0, "flops": 0.0, "approx_bytes": 0.0}
     for i, l in enumerate(stack):
         d = descs[i]
-        get = lambda r, arr: arr[r % copies]._keep
+        if reps <= 0:       # counter runs: no single-layer calls; keep the sums defined
+            tot["flops"] += l.flops(N); tot["approx_bytes"] += approx_algorithmic_bytes(l, N, e)
+            continue
         t_ex = time_layer(lambda r: B.conv_wgrad_exact(d, sets[r % copies]._keep[0][i], sets[r % copies]._keep[1][i],
                                                        dW=sets[r % copies]._keep[2][i], ws=ws_l))
         t_ap = time_layer(lambda r: B.conv_wgrad_approx(d, sets[r % copies]._keep[0][i], sets[r % copies]._keep[1][i],
@@ -169,6 +176,8 @@ def main():
     tpath = os.path.join(ROOT, "paper_1908_05460_amd", "hbm_traffic.json")
     if os.path.exists(tpath):
         traffic = json.load(open(tpath)).get(args.workload)
+    phase_ms = {k: max(v, 1e-6) for k, v in phase_ms.items()}
+    single = reps > 0
     achieved_tf = tot["flops"] / phase_ms["exact"] / 1e9
     roofline = {"kernel": "exact phase = wgrad_exact_stream (layers of one shape per launch) + combine_partials",
                 "bound": "mfma", "achieved": round(achieved_tf, 3), "peak": MFMA_PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
@@ -177,7 +186,7 @@ def main():
                 "algorithmic_flops": tot["flops"], "algorithmic_min_bytes": sum(exact_min_bytes(l, N, e) for l in stack),
                 "layers": nl, "phase_us": round(phase_ms["exact"] * 1e3, 1),
                 "single_layer_calls": {"sum_us": round(tot["exact_us"], 1),
-                                       "tflops": round(tot["flops"] / tot["exact_us"] / 1e6, 2)}}
+                                       "tflops": round(tot["flops"] / tot["exact_us"] / 1e6, 2)} if single else None}
     achieved_gbs = tot["approx_bytes"] / phase_ms["approx"] / 1e6
     roofline_approx = {"kernel": "approx phase = approx_fused | approx_select + approx_gather_lds3x3, + combine_partials",
                        "bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
@@ -186,7 +195,7 @@ def main():
                        "algorithmic_bytes": tot["approx_bytes"], "layers": nl,
                        "phase_us": round(phase_ms["approx"] * 1e3, 1),
                        "single_layer_calls": {"sum_us": round(tot["approx_us"], 1),
-                                              "gbs": round(tot["approx_bytes"] / tot["approx_us"] / 1e3, 1)}}
+                                              "gbs": round(tot["approx_bytes"] / tot["approx_us"] / 1e3, 1)} if single else None}
 
     # ---- the oracle on the host cores, bounded sample of the same workload ----
     cpu = None
@@ -218,7 +227,8 @@ def main():
         "higher_is_better": False, "scaling": "weak", "vs_baseline": None, "dtype": "f32" if dtype == "fp32" else "bf16 in, f32 accumulate",
         "data": "synthetic",
         "config": {"workload": args.workload, "layers": nl, "batch": N, "input_sets_rotated": copies,
-                   "step": "exact + approx + zero + random gradient of every layer"},
+                   "step": " + ".join(p for p in phases if p in on) + " gradient of every layer"
+                           + ("" if len(on) == 4 else "  (PARTIAL STEP: not a benchmark result)")},
         "phase_ms": {k: round(v, 4) for k, v in phase_ms.items()},
         "speedup_approx_vs_exact": round(phase_ms["exact"] / phase_ms["approx"], 3),
         "roofline": roofline, "roofline_approx": roofline_approx, "cpu_baseline": cpu,
