@@ -100,14 +100,17 @@ size_t conv_wgrad_workspace_bytes(const wgrad_conv_desc *desc, wgrad_method meth
 
 /* One batch of an approximation schedule (Section 2.5): layer i uses
  * method[i] (a wgrad_method).  layers, X, dY, dW and method are host arrays of
- * nlayers entries (at most 4096); X[i], dY[i], dW[i] are device pointers.  All
- * layers are enqueued on `stream` without any host synchronisation; exact or
- * approximated layers that share one descriptor (up to 8 of them) are folded
- * into a single launch sequence, each working in its own slice of `ws`, which
- * must hold conv_wgrad_schedule_workspace_bytes(layers, method, nlayers).  The
- * results are those of the individual calls.  A random layer i uses
- * offset + (sum of K*C*R*S of the layers before it).  Validation of every layer
- * happens before the first launch. */
+ * nlayers entries (at most 4096); X[i], dY[i], dW[i] are device pointers, and
+ * the dW tensors must not overlap one another.  All layers are enqueued on
+ * `stream` without any host synchronisation, in this order: exact and
+ * approximated layers, where those that share one descriptor (up to 8) are
+ * folded into a single launch; one reduction of all their partial results;
+ * one launch for the zero layers and one for the random layers (32 tensors per
+ * launch).  Every layer works in its own slice of `ws`, which must hold
+ * conv_wgrad_schedule_workspace_bytes(layers, method, nlayers): the sum over
+ * the layers, not their maximum.  The results are those of the individual
+ * calls.  A random layer i uses offset + (sum of K*C*R*S of the layers before
+ * it).  Validation of every layer happens before the first launch. */
 int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void *const *X,
                             const void *const *dY, float *const *dW, const uint8_t *method,
                             int32_t nlayers, float scale, float sigma, uint64_t seed,

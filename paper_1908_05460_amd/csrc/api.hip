@@ -148,8 +148,7 @@ extern "C" size_t conv_wgrad_schedule_workspace_bytes(const wgrad_conv_desc *lay
         if (make_geometry(&layers[i], g) != WGRAD_OK) return 0;
         int members = 0;
         for (int j = i; j < nlayers; ++j) members += group[j] == i;
-        const size_t b = align_up(method_ws(g, method[i])) * members;
-        if (b > need) need = b;
+        need += align_up(method_ws(g, method[i])) * members;       // every group keeps its partials until the final reduction
     }
     return need;
 }
@@ -176,27 +175,46 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
     }
     if (!ws_ok(ws, ws_bytes, conv_wgrad_schedule_workspace_bytes(layers, method, nlayers))) return WGRAD_WORKSPACE_TOO_SMALL;
 
-    // pass 2: enqueue on the caller's stream, one launch sequence per group
+    // pass 2: enqueue on the caller's stream: one launch sequence per group of exact or approximated
+    // layers, then one reduction of all their partial results, then the zero and the random fills
+    hipStream_t st = (hipStream_t)stream;
     int group[4096];
     make_groups(layers, method, nlayers, group);
-    uint64_t off = offset;
-    for (int i = 0; i < nlayers; ++i) {
-        int rc = WGRAD_OK;
-        if (method[i] == WGRAD_ZERO) rc = conv_wgrad_zero(&layers[i], dW[i], stream);
-        else if (method[i] == WGRAD_RANDOM) rc = conv_wgrad_random(&layers[i], dW[i], sigma, seed, off, stream);
-        else if (group[i] == i) {
-            Geometry g;
-            make_geometry(&layers[i], g);
-            Batch b{};
-            for (int j = i; j < nlayers; ++j)
-                if (group[j] == i) { b.X[b.n] = X[j]; b.dY[b.n] = dY[j]; b.dW[b.n] = dW[j]; ++b.n; }
-            if (method[i] == WGRAD_EXACT) rc = launch_exact(g, plan_exact(g), b, ws, (hipStream_t)stream);
-            else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws, (hipStream_t)stream);
-        }
-        if (rc != WGRAD_OK) return rc;
-        off += (uint64_t)layers[i].K * layers[i].C * layers[i].R * layers[i].S;
+    CombineQueue queue;
+    char *ws_next = (char *)ws;
+    int rc = WGRAD_OK;
+    for (int i = 0; i < nlayers && rc == WGRAD_OK; ++i) {
+        if ((method[i] != WGRAD_EXACT && method[i] != WGRAD_APPROX) || group[i] != i) continue;
+        Geometry g;
+        make_geometry(&layers[i], g);
+        Batch b{};
+        for (int j = i; j < nlayers; ++j)
+            if (group[j] == i) { b.X[b.n] = X[j]; b.dY[b.n] = dY[j]; b.dW[b.n] = dW[j]; ++b.n; }
+        if (method[i] == WGRAD_EXACT) rc = launch_exact(g, plan_exact(g), b, ws_next, st, &queue);
+        else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue);
+        ws_next += align_up(method_ws(g, method[i])) * b.n;
     }
-    return WGRAD_OK;
+    if (rc == WGRAD_OK) rc = combine_flush(queue, st);
+    // fills, kTableMax tensors per launch
+    for (int which = WGRAD_ZERO; which <= WGRAD_RANDOM && rc == WGRAD_OK; ++which) {
+        float *dst[kTableMax];
+        long elems[kTableMax];
+        uint64_t offs[kTableMax];
+        int n = 0;
+        uint64_t off = offset;
+        for (int i = 0; i <= nlayers && rc == WGRAD_OK; ++i) {
+            if (n == kTableMax || (i == nlayers && n > 0)) {
+                rc = which == WGRAD_ZERO ? launch_zero_table(dst, elems, n, st)
+                                         : launch_random_table(dst, elems, offs, n, sigma, seed, st);
+                n = 0;
+            }
+            if (i == nlayers) break;
+            const long e = (long)layers[i].K * layers[i].C * layers[i].R * layers[i].S;
+            if (method[i] == which) { dst[n] = dW[i]; elems[n] = e; offs[n] = off; ++n; }
+            off += (uint64_t)e;
+        }
+    }
+    return rc;
 }
 
 extern "C" {

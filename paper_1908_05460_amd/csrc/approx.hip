@@ -548,7 +548,7 @@ static void launch_gather_lds(const ApproxPlan &pl, dim3 grid, size_t lds, hipSt
 }
 
 int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, float scale,
-                  int32_t *idx_out, float *sum_out, void *ws, hipStream_t st)
+                  int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer)
 {
     bool aligned = true;
     for (int i = 0; i < b.n; ++i)
@@ -588,7 +588,7 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         if (rc != WGRAD_OK) return rc;
         if (pl.chunks > 1)
             return launch_combine((const float *)((char *)ws + pl.off_part), (long)(plan.ws_bytes / 4), pl.chunks, outs,
-                                  scale, b.dW, b.n, st);
+                                  scale, b.dW, b.n, st, defer);
         return WGRAD_OK;
     }
     rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st);
@@ -608,68 +608,8 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
     if (rc != WGRAD_OK) return rc;
     if (pl.chunks > 1)
         return launch_combine((const float *)((char *)ws + pl.off_part), (long)(plan.ws_bytes / 4), pl.chunks, outs,
-                              scale, b.dW, b.n, st);
+                              scale, b.dW, b.n, st, defer);
     return WGRAD_OK;
-}
-
-// ------------------------------------------------------------------------------------
-// combine: dW[o] = scale * sum_i partial[i][o].  PL lanes share one output: lane pl adds
-// partials pl, pl+PL, ... in ascending order, then the PL sub-sums are added in
-// ascending pl through LDS -- a fixed order, so the result is deterministic.
-// ------------------------------------------------------------------------------------
-struct CombineOut { float *dW[kMaxBatch]; };
-
-template <int PL>
-__global__ __launch_bounds__(kBlock) void combine_partials(const float *__restrict__ part_base, long prob_stride,
-                                                           int nparts, long elems, float scale, CombineOut outs)
-{
-    constexpr int OB = kBlock / PL;                       // outputs per workgroup
-    __shared__ float red[PL][OB];
-    const float *__restrict__ part = part_base + blockIdx.y * prob_stride;
-    float *__restrict__ dW = outs.dW[blockIdx.y];
-    const int ol = threadIdx.x % OB, pl = threadIdx.x / OB;
-    const long o = (long)blockIdx.x * OB + ol;
-    float acc = 0.f;
-    if (o < elems) {
-        int i = pl;
-        for (; i + 7 * PL < nparts; i += 8 * PL) {
-            float v[8];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) v[u] = part[(long)(i + u * PL) * elems + o];
-#pragma unroll
-            for (int u = 0; u < 8; ++u) acc += v[u];
-        }
-        for (; i < nparts; i += PL) acc += part[(long)i * elems + o];
-    }
-    if (PL == 1) {
-        if (o < elems) dW[o] = acc * scale;
-        return;
-    }
-    red[pl][ol] = acc;
-    __syncthreads();
-    if (pl == 0 && o < elems) {
-        float t = 0.f;
-#pragma unroll
-        for (int q = 0; q < PL; ++q) t += red[q][ol];
-        dW[o] = t * scale;
-    }
-}
-
-int launch_combine(const float *partials, long prob_stride, int nparts, long elems, float scale,
-                   float *const *dW, int nprob, hipStream_t st)
-{
-    CombineOut outs{};
-    for (int i = 0; i < kMaxBatch; ++i) outs.dW[i] = dW[i < nprob ? i : 0];
-    // spread the partial index over lanes when there are few outputs and many partials
-    const int pl = (elems <= 16 * 1024 && nparts >= 64) ? 16 : ((elems <= 256 * 1024 && nparts >= 16) ? 4 : 1);
-    const int ob = kBlock / pl;
-    const dim3 grid((unsigned)((elems + ob - 1) / ob), (unsigned)nprob);
-#define CB_ARGS grid, dim3(kBlock), 0, st, partials, prob_stride, nparts, elems, scale, outs
-    if (pl == 16) WGRAD_LAUNCH(combine_partials<16>, CB_ARGS);
-    else if (pl == 4) WGRAD_LAUNCH(combine_partials<4>, CB_ARGS);
-    else WGRAD_LAUNCH(combine_partials<1>, CB_ARGS);
-#undef CB_ARGS
-    return launch_status();
 }
 
 }  // namespace wgrad

@@ -86,7 +86,9 @@ struct ExactPlan {
 ExactPlan plan_exact(const Geometry &g, bool allow_stream = true);
 bool plan_exact_stream(const Geometry &g, ExactPlan &pl);
 int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st);
-int launch_exact(const Geometry &g, const ExactPlan &pl, const Batch &b, void *ws, hipStream_t st);
+struct CombineQueue;
+int launch_exact(const Geometry &g, const ExactPlan &pl, const Batch &b, void *ws, hipStream_t st,
+                 CombineQueue *defer = nullptr);
 size_t exact_ws_per_problem(const Geometry &g, const ExactPlan &pl);
 
 struct ApproxPlan {
@@ -97,13 +99,34 @@ struct ApproxPlan {
 ApproxPlan plan_approx(const Geometry &g, bool allow_lds = true, bool allow_fused = true);
 int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, hipStream_t st);
 int launch_approx(const Geometry &g, const ApproxPlan &pl, const Batch &b, float scale,
-                  int32_t *idx_out, float *sum_out, void *ws, hipStream_t st);
+                  int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer = nullptr);
 
-// dW[i][o] = scale * sum_j partials[i * prob_stride + j * elems + o] for the nprob problems of a batch
+// Reductions of partial results that a run of several layers postpones: every producer writes
+// its partials into a workspace region of its own, and one table-driven launch at the end
+// reduces all of them (a launch per layer group costs more than the reduction itself).
+constexpr int kTableMax = 32;        // tensors one table-driven launch handles
+struct CombineItem {
+    const float *part;               // [nparts][elems]
+    float *dW;
+    int nparts, elems;
+    float scale;
+};
+struct CombineQueue {
+    int n = 0;
+    CombineItem item[kTableMax];
+};
+int combine_flush(CombineQueue &q, hipStream_t st);
+
+// dW[i][o] = scale * sum_j partials[i * prob_stride + j * elems + o] for the nprob problems of a batch;
+// with a queue the work is only recorded there (and the queue flushed when full)
 int launch_combine(const float *partials, long prob_stride, int nparts, long elems, float scale,
-                   float *const *dW, int nprob, hipStream_t st);
+                   float *const *dW, int nprob, hipStream_t st, CombineQueue *defer = nullptr);
 int launch_zero(float *dW, long elems, hipStream_t st);
 int launch_random(float *dW, long elems, float sigma, uint64_t seed, uint64_t offset, hipStream_t st);
+// the same for up to kTableMax tensors in one launch (offset[i]: first counter of tensor i)
+int launch_zero_table(float *const *dW, const long *elems, int n, hipStream_t st);
+int launch_random_table(float *const *dW, const long *elems, const uint64_t *offset, int n, float sigma,
+                        uint64_t seed, hipStream_t st);
 
 // hipGetLastError() reports the last error of ANY earlier runtime call on this thread, so it
 // is cleared before a launch and read right after it.

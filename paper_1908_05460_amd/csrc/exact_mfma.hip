@@ -571,9 +571,9 @@ static bool batch_aligned(const Geometry &g, const Batch &b, int xv)
 }
 
 static int launch_exact_staged(const Geometry &g, const ExactPlan &pl, const void *X, const void *dY, float *dW,
-                               void *ws, hipStream_t st);
+                               void *ws, hipStream_t st, CombineQueue *defer);
 
-int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void *ws, hipStream_t st)
+int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void *ws, hipStream_t st, CombineQueue *defer)
 {
     if (plan.stream && batch_aligned(g, b, plan.xv)) {
         // one launch for the whole batch; problem i owns the i-th slice of the workspace.  The
@@ -589,20 +589,22 @@ int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void 
         for (int i = 0; i < b.n; ++i) out[i] = pl.splits > 1 ? (float *)ws + i * prob_stride : b.dW[i];
         int rc = launch_exact_stream(g, pl, b, out, st);
         if (rc != WGRAD_OK) return rc;
-        if (pl.splits > 1) return launch_combine((const float *)ws, prob_stride, pl.splits, g.dw_elems(), 1.0f, b.dW, b.n, st);
+        if (pl.splits > 1)
+            return launch_combine((const float *)ws, prob_stride, pl.splits, g.dw_elems(), 1.0f, b.dW, b.n, st, defer);
         return WGRAD_OK;
     }
-    // staged form: one problem at a time (shapes or alignments the streaming form does not take)
+    // staged form: one problem at a time (shapes or alignments the streaming form does not take),
+    // each in its own slice of the workspace
     const ExactPlan pl = plan.stream ? plan_exact(g, false) : plan;
     for (int i = 0; i < b.n; ++i) {
-        int rc = launch_exact_staged(g, pl, b.X[i], b.dY[i], b.dW[i], ws, st);
+        int rc = launch_exact_staged(g, pl, b.X[i], b.dY[i], b.dW[i], (char *)ws + (size_t)i * align_up(plan.ws_bytes), st, defer);
         if (rc != WGRAD_OK) return rc;
     }
     return WGRAD_OK;
 }
 
 static int launch_exact_staged(const Geometry &g, const ExactPlan &pl, const void *X, const void *dY, float *dW,
-                               void *ws, hipStream_t st)
+                               void *ws, hipStream_t st, CombineQueue *defer)
 {
     ExactParams p{};
     p.X = X; p.dY = dY;
@@ -648,7 +650,7 @@ static int launch_exact_staged(const Geometry &g, const ExactPlan &pl, const voi
     }
     int rc = launch_status();
     if (rc != WGRAD_OK) return rc;
-    if (pl.splits > 1) return launch_combine((const float *)ws, 0, pl.splits, g.dw_elems(), 1.0f, &dW, 1, st);
+    if (pl.splits > 1) return launch_combine((const float *)ws, 0, pl.splits, g.dw_elems(), 1.0f, &dW, 1, st, defer);
     return WGRAD_OK;
 }
 

@@ -21,6 +21,50 @@ int launch_zero(float *dW, long elems, hipStream_t st)
     return launch_status();
 }
 
+// Up to kTableMax tensors per launch: a workgroup finds its tensor by its first-workgroup table.
+struct FillTable {
+    int n;
+    int begin[kTableMax + 1];
+    float *dst[kTableMax];
+    long elems[kTableMax];
+    uint64_t offset[kTableMax];
+};
+
+__device__ __forceinline__ int table_entry(const FillTable &t)
+{
+    int it = 0;
+    for (int i = 1; i < t.n; ++i) it += (int)blockIdx.x >= t.begin[i];
+    return it;
+}
+
+__global__ __launch_bounds__(kBlock) void fill_zero_table(const FillTable t)
+{
+    const int it = table_entry(t);
+    float *dW = t.dst[it];
+    const long elems = t.elems[it];
+    const long i = ((long)((int)blockIdx.x - t.begin[it]) * kBlock + threadIdx.x) * 4;
+    if (i + 3 < elems && ((uintptr_t)dW % 16) == 0) {
+        *(float4 *)(dW + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+    } else {
+        for (long j = i; j < elems && j < i + 4; ++j) dW[j] = 0.f;
+    }
+}
+
+int launch_zero_table(float *const *dW, const long *elems, int n, hipStream_t st)
+{
+    FillTable t{};
+    t.n = n;
+    long blocks = 0;
+    for (int i = 0; i < n; ++i) {
+        t.dst[i] = dW[i]; t.elems[i] = elems[i]; t.begin[i] = (int)blocks;
+        blocks += ((elems[i] + 3) / 4 + kBlock - 1) / kBlock;
+    }
+    if (blocks >= (1l << 31)) return WGRAD_UNSUPPORTED;
+    t.begin[n] = (int)blocks;
+    WGRAD_LAUNCH(fill_zero_table, dim3((unsigned)blocks), dim3(kBlock), 0, st, t);
+    return launch_status();
+}
+
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64
 // multiplications with the key bumped by the Weyl constants after each round.
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
@@ -44,17 +88,45 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 // dW[i] = sigma * sqrt(-2 ln u1) * cos(2 pi u2), with (u1, u2) from the first two
 // Philox words of counter (offset + i) under key seed; u = ((word >> 8) + 0.5) / 2^24
 // lies strictly inside (0,1) and is exact in fp32.
+__device__ __forceinline__ float normal_at(uint64_t gidx, float sigma, uint64_t seed)
+{
+    uint32_t w0, w1;
+    philox4x32_10((uint32_t)gidx, (uint32_t)(gidx >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), w0, w1);
+    const float u1 = ((float)(w0 >> 8) + 0.5f) * (1.0f / 16777216.0f);
+    const float u2 = ((float)(w1 >> 8) + 0.5f) * (1.0f / 16777216.0f);
+    return sigma * sqrtf(-2.0f * logf(u1)) * cospif(2.0f * u2);
+}
+
 __global__ __launch_bounds__(kBlock) void fill_normal(float *__restrict__ dW, long elems, float sigma,
                                                       uint64_t seed, uint64_t offset)
 {
     const long i = (long)blockIdx.x * kBlock + threadIdx.x;
     if (i >= elems) return;
-    const uint64_t gidx = offset + (uint64_t)i;
-    uint32_t w0, w1;
-    philox4x32_10((uint32_t)gidx, (uint32_t)(gidx >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), w0, w1);
-    const float u1 = ((float)(w0 >> 8) + 0.5f) * (1.0f / 16777216.0f);
-    const float u2 = ((float)(w1 >> 8) + 0.5f) * (1.0f / 16777216.0f);
-    dW[i] = sigma * sqrtf(-2.0f * logf(u1)) * cospif(2.0f * u2);
+    dW[i] = normal_at(offset + (uint64_t)i, sigma, seed);
+}
+
+__global__ __launch_bounds__(kBlock) void fill_normal_table(const FillTable t, float sigma, uint64_t seed)
+{
+    const int it = table_entry(t);
+    const long i = (long)((int)blockIdx.x - t.begin[it]) * kBlock + threadIdx.x;
+    if (i >= t.elems[it]) return;
+    t.dst[it][i] = normal_at(t.offset[it] + (uint64_t)i, sigma, seed);
+}
+
+int launch_random_table(float *const *dW, const long *elems, const uint64_t *offset, int n, float sigma,
+                        uint64_t seed, hipStream_t st)
+{
+    FillTable t{};
+    t.n = n;
+    long blocks = 0;
+    for (int i = 0; i < n; ++i) {
+        t.dst[i] = dW[i]; t.elems[i] = elems[i]; t.offset[i] = offset[i]; t.begin[i] = (int)blocks;
+        blocks += (elems[i] + kBlock - 1) / kBlock;
+    }
+    if (blocks >= (1l << 31)) return WGRAD_UNSUPPORTED;
+    t.begin[n] = (int)blocks;
+    WGRAD_LAUNCH(fill_normal_table, dim3((unsigned)blocks), dim3(kBlock), 0, st, t, sigma, seed);
+    return launch_status();
 }
 
 int launch_random(float *dW, long elems, float sigma, uint64_t seed, uint64_t offset, hipStream_t st)
