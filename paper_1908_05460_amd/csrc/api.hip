@@ -217,6 +217,20 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
     return rc;
 }
 
+#ifdef WGRAD_TUNING
+// development builds: the exact plan of a descriptor for a launch of nprob problems
+extern "C" int wgrad_debug_plan(const wgrad_conv_desc *desc, int nprob, int *out)
+{
+    Geometry g;
+    if (make_geometry(desc, g) != WGRAD_OK) return -1;
+    const ExactPlan pl = plan_exact(g);
+    out[0] = pl.stream; out[1] = pl.nt; out[2] = pl.wk; out[3] = pl.gpw; out[4] = (int)pl.lds_bytes;
+    out[5] = pl.ktiles * pl.ctiles; out[6] = pl.h_tiles * pl.n_groups; out[7] = pl.splits;
+    out[8] = nprob > 1 ? choose_splits(pl, nprob) : pl.splits; out[9] = pl.rowp; out[10] = pl.q; out[11] = pl.nti; out[12] = pl.ht;
+    return 0;
+}
+#endif
+
 extern "C" {
 
 const char *conv_wgrad_status_string(int status)

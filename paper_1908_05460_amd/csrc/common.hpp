@@ -89,6 +89,7 @@ int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, 
 struct CombineQueue;
 int launch_exact(const Geometry &g, const ExactPlan &pl, const Batch &b, void *ws, hipStream_t st,
                  CombineQueue *defer = nullptr);
+int choose_splits(const ExactPlan &pl, int nprob);
 size_t exact_ws_per_problem(const Geometry &g, const ExactPlan &pl);
 
 struct ApproxPlan {

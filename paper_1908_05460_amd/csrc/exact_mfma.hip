@@ -433,6 +433,47 @@ static int largest_divisor_at_most(int n, int limit)
     return 1;
 }
 
+// Number of slices the reduction over positions is cut into, for a launch of nprob problems of
+// this plan.  The baseline aims at a fixed number of workgroups.  The streaming form also weighs
+// alternatives with a small model of a workgroup's life: a fixed cost (tables, first loads,
+// epilogue), then its tiles one after another, each bounded by the matrix core shared with the
+// other workgroups resident on the CU (as many as their LDS windows allow) plus a barrier's worth
+// of skew; it matters for short reductions, where an uneven split (some workgroups with one tile
+// more) or a second round of workgroups costs a large part of the whole.
+int choose_splits(const ExactPlan &pl, int nprob)
+{
+    const long tiles = (long)pl.h_tiles * pl.n_groups;
+    const long out_tiles = (long)pl.ktiles * pl.ctiles * nprob;
+    long base = (tune_int("WGRAD_EXACT_BLOCKS", WGRAD_EXACT_BLOCKS) + out_tiles - 1) / out_tiles;
+    if (base > tiles) base = tiles;
+    if (base < 1) base = 1;
+    // (layers with a handful of input channels are bound by their loads, not by the matrix core)
+    if (!pl.stream || pl.nt != 9 || !tune_int("WGRAD_EXACT_MODEL", 1)) return (int)base;
+
+    int per_cu_max = (int)((size_t)160 * 1024 / (pl.lds_bytes ? pl.lds_bytes : 1));
+    per_cu_max = per_cu_max > 4 ? 4 : (per_cu_max < 1 ? 1 : per_cu_max);
+    const double t_mfma = pl.nt * 4.0 * pl.gpw * 32.0 / 2400.0 / 0.86;    // us per tile and wavefront, loop efficiency included
+    const double fixed = 9.0, skew = 0.5;                                  // skew: per resident workgroup
+    auto cost = [&](long splits) {
+        const long blocks = out_tiles * splits;
+        const long rounds = (blocks + (long)kNumCU * per_cu_max - 1) / ((long)kNumCU * per_cu_max);
+        // workgroups per CU: between the busiest CU and the average one (short launches behave like
+        // the average, long ones like the busiest)
+        double per_cu = 0.5 * ((blocks + kNumCU - 1) / kNumCU + (double)blocks / kNumCU);
+        if (per_cu > per_cu_max) per_cu = per_cu_max;
+        if (per_cu < 1) per_cu = 1;
+        const long max_tiles = (tiles + splits - 1) / splits;
+        return rounds * (fixed + max_tiles * per_cu * (t_mfma + skew)) + 0.002 * splits;   // slight preference for fewer partials
+    };
+    long best = base;
+    double best_cost = cost(base) * 0.97;                                   // deviate only for a clear gain
+    for (long s = 1; s <= tiles && s <= 1024; ++s) {
+        const double c = cost(s);
+        if (c < best_cost) { best_cost = c; best = s; }
+    }
+    return (int)best;
+}
+
 ExactPlan plan_exact(const Geometry &g, bool allow_stream)
 {
     ExactPlan pl{};
@@ -512,13 +553,7 @@ ExactPlan plan_exact(const Geometry &g, bool allow_stream)
 
     pl.h_tiles = (g.Ho + pl.ht - 1) / pl.ht;
     pl.n_groups = (g.N + pl.nti - 1) / pl.nti;
-    const long tiles = (long)pl.h_tiles * pl.n_groups;
-    long out_tiles = (long)pl.ktiles * pl.ctiles;
-    const int want_blocks = tune_int("WGRAD_EXACT_BLOCKS", WGRAD_EXACT_BLOCKS);
-    long splits = (want_blocks + out_tiles - 1) / out_tiles;
-    if (splits > tiles) splits = tiles;
-    if (splits < 1) splits = 1;
-    pl.splits = (int)splits;
+    pl.splits = choose_splits(pl, 1);
     pl.ws_bytes = pl.splits > 1 ? align_up((size_t)pl.splits * g.dw_elems() * 4) : 0;
     // tensors that are not 16-byte aligned fall back to the staged form at launch: size for both
     if (pl.stream) {
@@ -580,9 +615,8 @@ int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void 
         // workgroup target is for the whole launch: a batch splits each reduction less finely.
         ExactPlan pl = plan;
         if (b.n > 1) {
-            const long out_tiles = (long)pl.ktiles * pl.ctiles * b.n;
-            long splits = (tune_int("WGRAD_EXACT_BLOCKS", WGRAD_EXACT_BLOCKS) + out_tiles - 1) / out_tiles;
-            if (splits < pl.splits) pl.splits = (int)(splits < 1 ? 1 : splits);
+            const int splits = choose_splits(pl, b.n);
+            if (splits < pl.splits) pl.splits = splits;
         }
         float *out[kMaxBatch];
         const long prob_stride = (long)pl.splits * g.dw_elems();

@@ -29,7 +29,7 @@ bool plan_exact_stream(const Geometry &g, ExactPlan &pl)
     const int L = g.Ho * g.Wo;
     const int xv = g.W % 4 == 0 ? 4 : (g.W % 2 == 0 ? 2 : 0);
     if (!xv || L % 4 != 0) return false;
-    for (int gpw = 8; gpw >= 4; gpw -= 4) {
+    for (int gpw = 8; gpw >= 2; gpw /= 2) {
         const int qt = 16 * gpw * WQ;
         int nti, ht;
         if (L >= qt) { nti = 1; ht = largest_divisor_le(g.Ho, qt / g.Wo < 1 ? 1 : qt / g.Wo); }
@@ -48,7 +48,7 @@ bool plan_exact_stream(const Geometry &g, ExactPlan &pl)
         const int pp = stream_pitch(nti * iht * rowp);
         const int xbuf = (pl.ctch + 3) / 4 * (4 * pp + 4);        // quads of channels, see stream_chan_off
         size_t lds = ((size_t)2 * xbuf + qt) * 4;
-        const size_t red = (size_t)4 * 16 * (pl.nt * 16 + 1) * 4;
+        const size_t red = (size_t)WQ * (pl.nt * 16) * (16 * pl.wk + 4) * 4;    // epilogue exchange buffer [WQ][NT*16][KT + 4]
         if (red > lds) lds = red;
         const long x_slots = (long)pl.ctch * nti * iht * (g.W / xv);
         // up to 64 KB two workgroups share a CU; a larger window (strided layers) gets a CU to itself

@@ -29,6 +29,10 @@ namespace wgrad {
 #ifndef WGRAD_STREAM_SCHED
 #define WGRAD_STREAM_SCHED 2
 #endif
+// WGRAD_STREAM_PRIO: wavefront priority while a tile's window is staged (the MFMA pipeline runs at 0)
+#ifndef WGRAD_STREAM_PRIO
+#define WGRAD_STREAM_PRIO 0
+#endif
 #if WGRAD_STREAM_SCHED == 1
 #define WGRAD_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 #else
@@ -68,7 +72,8 @@ struct StreamParams {
 // Window staging slots (16- or 8-byte row pieces) per thread and tile.
 __host__ __device__ constexpr int stream_xslots(int wk, int gpw)
 {
-    return wk == 1 ? (gpw == 8 ? 9 : 5) : (wk == 2 ? (gpw == 8 ? 5 : 3) : 4);
+    if (gpw == 2) return wk == 4 ? 3 : 5;
+    return wk == 1 ? (gpw == 8 ? 9 : 5) : (wk == 2 ? (gpw == 8 ? 5 : 3) : (gpw == 8 ? 4 : 5));
 }
 
 // LDS offset (floats) of staged channel c_l.  In a step the four lane groups kk of an MFMA
@@ -141,39 +146,7 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams 
     const int c_first = p.tap_mode ? coltile * 16 * (NT / RS) : (coltile * NT * 16) / RS;
 
     TRACE(0);
-    int coloff[NT];                                     // byte offsets into a window buffer
-#pragma unroll
-    for (int t = 0; t < NT; ++t) {
-        int lc;
-        stream_column_of<NT>(p, coltile, t, i16, c_first, coloff[t], lc);
-        coloff[t] *= 4;
-    }
-    // ROWP != 0: one channel per lane; the taps are immediates (a padding channel reads channel 0, unused)
-    const int lane_base = (c_first + i16 < g.C ? stream_chan_off(i16, p.pp) : 0) * 4;
-    auto read_b = [&](const char *Xw, int xo, float (&b)[NT]) {
-        if (ROWP) {
-            const float *q = (const float *)(Xw + lane_base + xo);
-#pragma unroll
-            for (int j = 0; j < NT; ++j) b[j] = q[(j / 3) * ROWP + j % 3];
-        } else {
-#pragma unroll
-            for (int j = 0; j < NT; ++j) b[j] = *(const float *)(Xw + coloff[j] + xo);
-        }
-    };
-    // byte offset of staged position q inside a staged input channel; padded positions read offset 0
-    for (int q = tid; q < QT; q += kBlock) {
-        int off = 0;
-        if (q < p.q) {
-            uint32_t n_l, rem, h_l, w;
-            p.d_seg.divmod(q, n_l, rem);
-            p.d_wo.divmod(rem, h_l, w);
-            off = (n_l * p.iht * rowp + h_l * g.sh * rowp + w * g.sw) * 4;
-        }
-        xoff[q] = off;
-    }
-    // staging writes only cells that hold data: halo columns and unused channels stay zero
-    for (int e = tid; e < (2 * p.xbuf) >> 2; e += kBlock) ((float4_t *)smem)[e] = float4_t{0.f, 0.f, 0.f, 0.f};
-
+    TRACE_BLK(0);
     float4_t acc[NT];
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = float4_t{0.f, 0.f, 0.f, 0.f};
@@ -197,6 +170,7 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams 
             a_live |= 1u << gi;
         }
     }
+    TRACE(19);
     // ---- X window: this thread's staging slots (row pieces), decoded once ----
     int x_pack[XS];              // LDS float index | ih_l << 20 | valid elements << 28, -1 = unused
     uint32_t x_src[XS];          // byte offset from row 0 of the tile's first (image, channel)
@@ -272,8 +246,50 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams 
         tile_origin(wt_begin, true, dyb, xb, ih0);
 #pragma unroll
         for (int gi = 0; gi < GPW; ++gi) ring[gi].load(dyb, a_off[gi]);
+        TRACE(20);
+    }
+    // ---- LDS tables and the zero fill, while the first loads are in flight ----
+    int coloff[NT];                                     // byte offsets into a window buffer
+#pragma unroll
+    for (int t = 0; t < NT; ++t) {
+        int lc;
+        stream_column_of<NT>(p, coltile, t, i16, c_first, coloff[t], lc);
+        coloff[t] *= 4;
+    }
+    // ROWP != 0: one channel per lane; the taps are immediates (a padding channel reads channel 0, unused)
+    const int lane_base = (c_first + i16 < g.C ? stream_chan_off(i16, p.pp) : 0) * 4;
+    auto read_b = [&](const char *Xw, int xo, float (&b)[NT]) {
+        if (ROWP) {
+            const float *q = (const float *)(Xw + lane_base + xo);
+#pragma unroll
+            for (int j = 0; j < NT; ++j) b[j] = q[(j / 3) * ROWP + j % 3];
+        } else {
+#pragma unroll
+            for (int j = 0; j < NT; ++j) b[j] = *(const float *)(Xw + coloff[j] + xo);
+        }
+    };
+    TRACE(16);
+    // byte offset of staged position q inside a staged input channel; padded positions read offset 0
+    for (int q = tid; q < QT; q += kBlock) {
+        int off = 0;
+        if (q < p.q) {
+            uint32_t n_l, rem, h_l, w;
+            p.d_seg.divmod(q, n_l, rem);
+            p.d_wo.divmod(rem, h_l, w);
+            off = (n_l * p.iht * rowp + h_l * g.sh * rowp + w * g.sw) * 4;
+        }
+        xoff[q] = off;
+    }
+    TRACE(17);
+    // staging writes only cells that hold data: halo columns and unused channels stay zero
+    for (int e = tid; e < (2 * p.xbuf) >> 2; e += kBlock) ((float4_t *)smem)[e] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    TRACE(18);
+    {
         __syncthreads();                      // zero fill and tables complete
+        TRACE(21);
         commit_x(Xs0);
+        TRACE(22);
         load_x(wt_begin + 1);
     }
     TRACE(2);
@@ -285,6 +301,7 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams 
         if (wt == wt_begin) TRACE(3);
         if (wt == wt_begin + 1) TRACE(5);
         const char *Xw = (const char *)(Xs0 + par * p.xbuf);
+        if (WGRAD_STREAM_PRIO) __builtin_amdgcn_s_setprio(WGRAD_STREAM_PRIO);
         // window of the next tile: registers -> the other buffer, then request the one after it
         commit_x(Xs0 + (par ^ 1) * p.xbuf);
         if (wt == wt_begin + 1) TRACE(6);
@@ -294,6 +311,7 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams 
         int ih0;
         tile_origin(wt + 1, has_next, dyb, xb, ih0);
         if (wt == wt_begin + 1) TRACE(7);
+        if (WGRAD_STREAM_PRIO) __builtin_amdgcn_s_setprio(0);
 
 #ifdef WGRAD_TUNING
         for (int rep = 0; rep < p.repeat; ++rep)
@@ -342,35 +360,42 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams 
     }
     TRACE(8);
 
-    // ---- epilogue: every wavefront parks its accumulators in LDS in output order; then all
-    //      threads add the WQ position slices and write rows of the result, coalesced ----
+    // ---- epilogue: every wavefront parks its accumulators in LDS, column-major with the four rows a
+    //      lane holds side by side (one 16-byte write per column tile); then all threads add the WQ
+    //      position slices, four rows at a time, and write rows of the result, coalesced ----
     __syncthreads();
     TRACE(9);
     {
-        constexpr int EP = NCB + 1;                         // row pitch of the exchange buffer
-        float *red = smem;                                  // [WQ][KT][EP]
+        constexpr int KTP = KT + 4;                         // floats per parked column (16-byte multiple, odd in units of 16 bytes)
+        float *red = smem;                                  // [WQ][NCB][KTP]
 #pragma unroll
         for (int j = 0; j < NT; ++j) {
             int lo, lc;
             stream_column_of<NT>(p, coltile, j, i16, c_first, lo, lc);
             if (lc < 0) lc = p.tap_mode ? (p.tile_c0[j] + i16) * RS + p.tile_tap[j] : j * 16 + i16;   // padding column: parked, never written out
-#pragma unroll
-            for (int v = 0; v < 4; ++v) red[(wq * KT + wk * 16 + 4 * kk + v) * EP + lc] = acc[j][v];
+            *(float4_t *)(red + ((wq * NCB + lc) * KTP + wk * 16 + 4 * kk)) = acc[j];
         }
         __syncthreads();
         TRACE(14);
         const int colbase = p.tap_mode ? c_first * RS : coltile * NCB;
         float *out = p.out[prob] + (long)split * g.K * CRS;
-        for (int o = tid; o < KT * NCB; o += kBlock) {
-            const int row = o / NCB, lc = o % NCB;
-            float sum = red[row * EP + lc];
+        for (int o = tid; o < (KT / 4) * NCB; o += kBlock) {
+            const int rq = o / NCB, lc = o % NCB;
+            float4_t sum = *(const float4_t *)(red + (lc * KTP + 4 * rq));
 #pragma unroll
-            for (int w = 1; w < WQ; ++w) sum += red[(w * KT + row) * EP + lc];
-            const int k = k0 + row, col = colbase + lc;
-            if (k < g.K && col < CRS) out[(long)k * CRS + col] = sum;
+            for (int w = 1; w < WQ; ++w) sum += *(const float4_t *)(red + ((w * NCB + lc) * KTP + 4 * rq));
+            const int col = colbase + lc;
+            if (col < CRS) {
+#pragma unroll
+                for (int v = 0; v < 4; ++v) {
+                    const int k = k0 + 4 * rq + v;
+                    if (k < g.K) out[(long)k * CRS + col] = sum[v];
+                }
+            }
         }
     }
     TRACE(10);
+    TRACE_BLK(1);
 }
 
 // Per-K-tile-width launchers, each instantiated in its own translation unit.
@@ -386,10 +411,15 @@ static void stream_inst(const StreamParams &p, int gpw, int grid, size_t lds, hi
         if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)wgrad_exact_stream<NT, WK, BF16, XV, 8, ROWP>,
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return;
         WGRAD_LAUNCH((wgrad_exact_stream<NT, WK, BF16, XV, 8, ROWP>), dim3(grid), dim3(kBlock), lds, st, p);
-    } else {
+    } else if (gpw == 4) {
         if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)wgrad_exact_stream<NT, WK, BF16, XV, 4, ROWP>,
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return;
         WGRAD_LAUNCH((wgrad_exact_stream<NT, WK, BF16, XV, 4, ROWP>), dim3(grid), dim3(kBlock), lds, st, p);
+    } else {
+        // short tiles: strided layers, whose input window is four times the size of the output tile
+        if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)wgrad_exact_stream<NT, WK, BF16, XV, 2, ROWP>,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return;
+        WGRAD_LAUNCH((wgrad_exact_stream<NT, WK, BF16, XV, 2, ROWP>), dim3(grid), dim3(kBlock), lds, st, p);
     }
 }
 

@@ -13,7 +13,7 @@ void stream_launch_w1(const StreamParams &p, int nt, int xv, int gpw, int rowp, 
 #ifdef WGRAD_TUNING
 extern "C" int wgrad_debug_read_trace(long long *host_out)
 {
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace), sizeof(long long) * 64);
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace), sizeof(long long) * (64 + 2 * 4096));
 }
 #endif
 
