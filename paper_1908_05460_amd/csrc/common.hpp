@@ -80,12 +80,15 @@ struct ExactPlan {
     int h_tiles, n_groups;
     int xv;                          // elements per staging access (4, 2; 0 = element-wise staging)
     int stream, gpw, xbuf, rowp;           // streaming form: A operand from global memory, window double-buffered
+    int mm16;                        // bf16 matrix-core form of the streaming kernel
     size_t lds_bytes, ws_bytes;
     bool ok;
 };
 ExactPlan plan_exact(const Geometry &g, bool allow_stream = true);
 bool plan_exact_stream(const Geometry &g, ExactPlan &pl);
 int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st);
+bool plan_exact_bf16(const Geometry &g, ExactPlan &pl);
+int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st);
 struct CombineQueue;
 int launch_exact(const Geometry &g, const ExactPlan &pl, const Batch &b, void *ws, hipStream_t st,
                  CombineQueue *defer = nullptr);

@@ -1,0 +1,287 @@
+// Exact filter gradient for bf16 inputs on the bf16 matrix core (v_mfma_f32_16x16x32_bf16, fp32
+// accumulate): the streaming implicit GEMM of exact_stream_kernel.hpp re-cut for an instruction
+// that contracts 32 positions at once.  3x3 filters, stride 1, padding 1, C a multiple of 16 and
+// K a multiple of 64; everything else stays on the fp32 matrix-core kernels.
+//
+//   - A operand (dY): lane (i = l%16, kk = l/16) of the instruction holds row i, reduction slots
+//     8kk..8kk+7.  The order of the reduction is free, so the slots of a 32-position group are the
+//     positions themselves: the lane loads the 16 bytes dY[k][q0+8kk .. +7] straight from global
+//     memory and that register quadruple IS the operand.  A wavefront owns MT = 4 row tiles
+//     (64 output channels), so a B operand read from LDS feeds four instructions.
+//   - B operand (X): lane (c = l%16, kk) needs the eight input elements that positions
+//     q0+8kk..+7 see through tap (r,s).  The window is kept in LDS as bf16, row-major with a
+//     zero halo, and positions are handled in pairs (w, w+1), w even: for a window row the lane
+//     reads, per pair, the two aligned 32-bit words that hold columns w..w+3; the word of tap
+//     s = 0 is the first, of s = 2 the second, of s = 1 their middle (one v_alignbit).  One read
+//     per pair and row therefore serves the three taps of that row: 12 two-word reads per 36
+//     matrix instructions.
+//   - Pipeline, tiles, splits, workgroup numbering: as in the fp32 streaming kernel (window
+//     double-buffered, one barrier per tile, every load unconditional).
+#pragma once
+#include "exact_common.hpp"
+
+namespace wgrad {
+
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
+
+struct Bf16Params {
+    const void *X[kMaxBatch], *dY[kMaxBatch];
+    float *out[kMaxBatch];      // per problem: dW when splits == 1, else partials [splits][K][C*9]
+    int per_prob;               // workgroups per problem
+    Geometry g;
+    int ktiles, ctiles, splits;
+    int nti, ht, q, iht, h_tiles, n_groups;
+    int seg;                    // ht * Wo : contiguous dY elements per (image, channel) in a tile
+    int ppw;                    // 32-bit words between the planes of a channel quad (1 mod 32)
+    int buf_words;              // words per window buffer
+    int rowp;                   // elements per window row (even)
+    FastDiv d_wv, d_rows, d_iht, d_seg, d_wo, d_htiles;
+};
+
+constexpr int kBf16MT = 4;      // 16-row tiles per wavefront
+constexpr int kBf16KT = 16 * kBf16MT;
+
+// Word offset of staged channel c_l inside a window copy.  The four lane groups of an operand read
+// words 4 apart (8 positions), so with ppw = 1 (mod 32)
+//   bank(c_l, kk) = (c_l & 3) + 16 * ((c_l >> 2) & 1) + 4 * kk   (mod 32)
+// takes every value exactly twice over 16 channels x 4 groups: the minimum for 64 lanes.
+__host__ __device__ __forceinline__ int bf16_chan_off(int c_l, int ppw) { return (c_l & 3) * ppw + (c_l >> 2) * (4 * ppw + 12); }
+
+// Window staging slots (8-byte row pieces, four elements) per thread and tile.
+__host__ __device__ constexpr int bf16_xslots(int gpw) { return gpw >= 2 ? 5 : 3; }
+
+// GPW: 32-position groups per wavefront and tile (the four wavefronts split the positions of a
+// tile, 128 * GPW in all, padded with dead positions if the shape gives fewer).
+// ROWP: window row pitch in elements, compile-time so that the tap offsets are immediates.
+template <int GPW, int ROWP>
+__global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p)
+{
+    constexpr int MT = kBf16MT, KT = kBf16KT, NT = 9, NCB = NT * 16;
+    constexpr int QT = 128 * GPW;
+    constexpr int XS = bf16_xslots(GPW);
+    extern __shared__ float smem[];
+    uint32_t *Xs0 = (uint32_t *)smem;                   // [2][buf_words]
+    int *xoffp = (int *)(Xs0 + 2 * p.buf_words);        // [QT / 2] byte offsets of position pairs
+
+    const Geometry &g = p.g;
+    const int tid = threadIdx.x, lane = tid & 63, wq = tid >> 6;
+    const int i16 = lane & 15, kk = lane >> 4;
+    const int L = g.Ho * g.Wo, CRS = g.C * 9;
+
+    const int logical_all = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    const int prob = logical_all / p.per_prob;
+    const int logical = logical_all - prob * p.per_prob;
+    const char *const Xp = (const char *)p.X[prob];
+    const char *const dYp = (const char *)p.dY[prob];
+    const int coltile = logical % p.ctiles;
+    const int ktile = (logical / p.ctiles) % p.ktiles;
+    const int split = logical / (p.ctiles * p.ktiles);
+    const int k0 = ktile * KT;
+    const int c_first = coltile * 16;
+
+    float4_t acc[MT][NT];
+#pragma unroll
+    for (int m = 0; m < MT; ++m)
+#pragma unroll
+        for (int t = 0; t < NT; ++t) acc[m][t] = float4_t{0.f, 0.f, 0.f, 0.f};
+
+    const int tiles_total = p.h_tiles * p.n_groups;
+    const int wt_begin = (int)((long)split * tiles_total / p.splits);
+    const int wt_end = (int)((long)(split + 1) * tiles_total / p.splits);
+
+    // ---- A operand: byte offsets of this lane's 16-byte pieces from the tile's first element ----
+    uint32_t a_off[GPW];
+    uint32_t a_live = 0;
+#pragma unroll
+    for (int gi = 0; gi < GPW; ++gi) {
+        const int q = 32 * (wq * GPW + gi) + 8 * kk;
+        a_off[gi] = 0;
+        if (q < p.q) {
+            uint32_t n_l, rem;
+            p.d_seg.divmod(q, n_l, rem);
+            a_off[gi] = ((n_l * g.K + i16) * L + rem) * 2;
+            a_live |= 1u << gi;
+        }
+    }
+    const uint32_t row_tile_bytes = 16u * L * 2u;       // from row tile m to m + 1
+
+    // ---- X window: this thread's staging slots (row pieces of four elements), decoded once ----
+    int x_pack[XS];              // word index of column 4jv | ih_l << 20 | first piece of its row << 28 | last << 29, -1 = unused
+    uint32_t x_src[XS];          // byte offset from row 0 of the tile's first (image, channel)
+    {
+        const int x_total = 16 * p.nti * p.iht * (int)p.d_wv.d;
+#pragma unroll
+        for (int u = 0; u < XS; ++u) {
+            const int e = tid + u * kBlock;
+            x_pack[u] = -1; x_src[u] = 0;
+            if (e < x_total) {
+                uint32_t row, jv, c_l, rem, n_l, ih_l;
+                p.d_wv.divmod(e, row, jv);
+                p.d_rows.divmod(row, c_l, rem);
+                p.d_iht.divmod(rem, n_l, ih_l);
+                x_pack[u] = (int)(bf16_chan_off(c_l, p.ppw) + ((rem * ROWP + jv * 4) >> 1)) | (int)(ih_l << 20)
+                            | (jv == 0 ? 1 << 28 : 0) | (jv + 1 == p.d_wv.d ? 1 << 29 : 0);
+                x_src[u] = ((n_l * g.C + c_l) * (g.H * g.W) + jv * 4) * 2;
+            }
+        }
+    }
+
+    uint4_t ring[GPW][MT];
+    uint2 xr[XS];
+    uint32_t x_row_ok = 0;
+
+    auto tile_origin = [&](int wt, bool live, const char *&dy_base, const char *&x_base, int &ih0) {
+        const int w = live ? wt : wt_end - 1;
+        uint32_t ng, hti;
+        p.d_htiles.divmod(w, ng, hti);
+        const int n0 = ng * p.nti, h0 = hti * p.ht;
+        dy_base = dYp + (((long)n0 * g.K + k0) * g.Ho + h0) * g.Wo * 2;
+        x_base = Xp + ((long)n0 * g.C + c_first) * g.H * g.W * 2;
+        ih0 = h0 - 1;
+    };
+    auto load_x = [&](int wt) {
+        const bool live = wt < wt_end;
+        const char *dyb, *xb;
+        int ih0;
+        tile_origin(wt, live, dyb, xb, ih0);
+        x_row_ok = 0;
+#pragma unroll
+        for (int u = 0; u < XS; ++u) {
+            int ih = ih0 + ((x_pack[u] >> 20) & 0xff);
+            if (ih >= 0 && ih < g.H) x_row_ok |= 1u << u;
+            ih = ih < 0 ? 0 : (ih >= g.H ? g.H - 1 : ih);
+            xr[u] = *(const uint2 *)(xb + (live ? x_src[u] + ih * (g.W * 2) : 0u));
+        }
+    };
+    // Elements x0..x3 of a piece belong to window columns 4jv+1 .. 4jv+4 (column 0 is the halo): the
+    // aligned words of columns (4jv, 4jv+1) and (4jv+2, 4jv+3) are (x3 of the piece to the left, x0)
+    // and (x1, x2).  The left neighbour is the previous lane (pieces of a row sit in consecutive
+    // lanes, and a row never straddles a group of 16 lanes); the last piece of a row also writes
+    // (x3, halo).
+    auto commit_x = [&](uint32_t *buf) {
+#pragma unroll
+        for (int u = 0; u < XS; ++u) {
+            const bool ok = (x_row_ok >> u) & 1;
+            const uint32_t r0 = ok ? xr[u].x : 0u, r1 = ok ? xr[u].y : 0u;
+            uint32_t left = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)r1, 0x111, 0xf, 0xf, true);   // row_shr:1
+            if (x_pack[u] >= 0) {
+                if ((x_pack[u] >> 28) & 1) left = 0u;
+                uint32_t *w = buf + (x_pack[u] & 0xfffff);
+                w[0] = __builtin_amdgcn_alignbit(r0, left, 16);
+                w[1] = __builtin_amdgcn_alignbit(r1, r0, 16);
+                if ((x_pack[u] >> 29) & 1) w[2] = r1 >> 16;
+            }
+        }
+    };
+
+    // ---- prologue: first loads, then the LDS tables and the zero fill under their latency ----
+    {
+        const char *dyb, *xb;
+        int ih0;
+        load_x(wt_begin);
+        tile_origin(wt_begin, true, dyb, xb, ih0);
+#pragma unroll
+        for (int gi = 0; gi < GPW; ++gi)
+#pragma unroll
+            for (int m = 0; m < MT; ++m) ring[gi][m] = *(const uint4_t *)(dyb + m * row_tile_bytes + a_off[gi]);
+    }
+    for (int q2 = tid; q2 < QT / 2; q2 += kBlock) {
+        const int q = 2 * q2;
+        int off = 0;
+        if (q < p.q) {
+            uint32_t n_l, rem, h_l, w;
+            p.d_seg.divmod(q, n_l, rem);
+            p.d_wo.divmod(rem, h_l, w);
+            off = (n_l * p.iht * ROWP + h_l * ROWP + w) * 2;
+        }
+        xoffp[q2] = off;
+    }
+    for (int e = tid; e < (2 * p.buf_words) >> 2; e += kBlock) ((uint4_t *)Xs0)[e] = uint4_t{0u, 0u, 0u, 0u};
+    const int lane_base = (c_first + i16 < g.C ? bf16_chan_off(i16, p.ppw) : 0) * 4;
+    __syncthreads();
+    commit_x(Xs0);
+    load_x(wt_begin + 1);
+
+    int par = 0;
+    for (int wt = wt_begin; wt < wt_end; ++wt, par ^= 1) {
+        __syncthreads();   // window of tile wt is complete; everyone has left the buffer tile wt+1 goes to
+        const char *Xw = (const char *)(Xs0 + par * p.buf_words) + lane_base;
+        commit_x(Xs0 + (par ^ 1) * p.buf_words);
+        load_x(wt + 2);
+        const bool has_next = wt + 1 < wt_end;
+        const char *dyb, *xb;
+        int ih0;
+        tile_origin(wt + 1, has_next, dyb, xb, ih0);
+
+#pragma unroll
+        for (int gi = 0; gi < GPW; ++gi) {
+            // pair addresses of this lane's eight positions in both copies
+            const int4 po = *(const int4 *)(xoffp + 16 * (wq * GPW + gi) + 4 * kk);
+            const char *a0[4] = {Xw + po.x, Xw + po.y, Xw + po.z, Xw + po.w};
+            bf16x8_t a_cur[MT];
+            const bool live = (a_live >> gi) & 1u;
+#pragma unroll
+            for (int m = 0; m < MT; ++m) {
+                const uint4_t v = live ? ring[gi][m] : uint4_t{0u, 0u, 0u, 0u};
+                a_cur[m] = __builtin_bit_cast(bf16x8_t, v);
+                ring[gi][m] = *(const uint4_t *)(dyb + m * row_tile_bytes + (has_next ? a_off[gi] : 0u));   // same piece of the next tile
+            }
+#pragma unroll
+            for (int r = 0; r < 3; ++r) {
+                uint32_t lo[4], hi[4];
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const uint32_t *wp = (const uint32_t *)(a0[j] + r * ROWP * 2);
+                    lo[j] = wp[0];
+                    hi[j] = wp[1];
+                }
+#pragma unroll
+                for (int s3 = 0; s3 < 3; ++s3) {
+                    uint4_t b;
+#pragma unroll
+                    for (int j = 0; j < 4; ++j)
+                        b[j] = s3 == 0 ? lo[j] : (s3 == 2 ? hi[j] : __builtin_amdgcn_alignbit(hi[j], lo[j], 16));
+                    const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, b);
+#pragma unroll
+                    for (int m = 0; m < MT; ++m)
+                        acc[m][r * 3 + s3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_cur[m], bv, acc[m][r * 3 + s3], 0, 0, 0);
+                }
+            }
+        }
+    }
+
+    // ---- epilogue, one row tile at a time: wavefronts park their accumulators in LDS (column-major,
+    //      the four rows a lane holds side by side), then all threads add the four position slices
+    //      and write rows of the result, coalesced ----
+    {
+        constexpr int KTP = 16 + 4;
+        float *red = smem;                                  // [4][NCB][KTP]
+        float *out = p.out[prob] + (long)split * g.K * CRS;
+        const int colbase = c_first * 9;
+#pragma unroll
+        for (int m = 0; m < MT; ++m) {
+            __syncthreads();
+#pragma unroll
+            for (int t = 0; t < NT; ++t)
+                *(float4_t *)(red + ((wq * NCB + i16 * 9 + t) * KTP + 4 * kk)) = acc[m][t];
+            __syncthreads();
+            for (int o = tid; o < 4 * NCB; o += kBlock) {
+                const int rq = o / NCB, lc = o % NCB;
+                float4_t sum = *(const float4_t *)(red + (lc * KTP + 4 * rq));
+#pragma unroll
+                for (int w = 1; w < 4; ++w) sum += *(const float4_t *)(red + ((w * NCB + lc) * KTP + 4 * rq));
+                const int col = colbase + lc;
+                if (col < CRS) {
+#pragma unroll
+                    for (int v = 0; v < 4; ++v) {
+                        const int k = k0 + m * 16 + 4 * rq + v;
+                        if (k < g.K) out[(long)k * CRS + col] = sum[v];
+                    }
+                }
+            }
+        }
+    }
+}
+
+}  // namespace wgrad

@@ -448,11 +448,13 @@ int choose_splits(const ExactPlan &pl, int nprob)
     if (base > tiles) base = tiles;
     if (base < 1) base = 1;
     // (layers with a handful of input channels are bound by their loads, not by the matrix core)
-    if (!pl.stream || pl.nt != 9 || !tune_int("WGRAD_EXACT_MODEL", 1)) return (int)base;
+    if (!(pl.stream || pl.mm16) || pl.nt != 9 || !tune_int("WGRAD_EXACT_MODEL", 1)) return (int)base;
 
     int per_cu_max = (int)((size_t)160 * 1024 / (pl.lds_bytes ? pl.lds_bytes : 1));
     per_cu_max = per_cu_max > 4 ? 4 : (per_cu_max < 1 ? 1 : per_cu_max);
-    const double t_mfma = pl.nt * 4.0 * pl.gpw * 32.0 / 2400.0 / 0.86;    // us per tile and wavefront, loop efficiency included
+    if (pl.mm16 && per_cu_max > 2) per_cu_max = 2;                         // its registers allow two wavefronts per SIMD
+    // us per tile and wavefront, loop efficiency included
+    const double t_mfma = pl.mm16 ? 9.0 * 4 * pl.gpw * 16.0 / 2400.0 / 0.5 : pl.nt * 4.0 * pl.gpw * 32.0 / 2400.0 / 0.86;
     const double fixed = 9.0, skew = 0.5;                                  // skew: per resident workgroup
     auto cost = [&](long splits) {
         const long blocks = out_tiles * splits;
@@ -499,7 +501,8 @@ ExactPlan plan_exact(const Geometry &g, bool allow_stream)
         if (pl.ctch > g.C) pl.ctch = g.C;
     }
     // the streaming form (A operand straight from global memory) takes every shape it can
-    if (allow_stream && tune_int("WGRAD_EXACT_STREAM", 1) && plan_exact_stream(g, pl)) pl.ok = true;
+    if (allow_stream && tune_int("WGRAD_EXACT_BF16MM", 1) && plan_exact_bf16(g, pl)) pl.ok = true;
+    else if (allow_stream && tune_int("WGRAD_EXACT_STREAM", 1) && plan_exact_stream(g, pl)) pl.ok = true;
 
     // widest access the shape allows when staging X rows (alignment of the pointers is checked at launch)
     const int xv_shape = g.W % 4 == 0 ? 4 : (g.W % 2 == 0 ? 2 : 0);
@@ -556,7 +559,7 @@ ExactPlan plan_exact(const Geometry &g, bool allow_stream)
     pl.splits = choose_splits(pl, 1);
     pl.ws_bytes = pl.splits > 1 ? align_up((size_t)pl.splits * g.dw_elems() * 4) : 0;
     // tensors that are not 16-byte aligned fall back to the staged form at launch: size for both
-    if (pl.stream) {
+    if (pl.stream || pl.mm16) {
         const size_t alt = plan_exact(g, false).ws_bytes;
         if (alt > pl.ws_bytes) pl.ws_bytes = alt;
     }
@@ -597,11 +600,11 @@ size_t exact_ws_per_problem(const Geometry &g, const ExactPlan &pl)
     return pl.ws_bytes;
 }
 
-static bool batch_aligned(const Geometry &g, const Batch &b, int xv)
+static bool batch_aligned(const Geometry &g, const Batch &b, int xv, int dyv)
 {
     const int esz = g.bf16 ? 2 : 4;
     for (int i = 0; i < b.n; ++i)
-        if (((uintptr_t)b.dY[i] % (4 * esz)) != 0 || ((uintptr_t)b.X[i] % (xv * esz)) != 0) return false;
+        if (((uintptr_t)b.dY[i] % (dyv * esz)) != 0 || ((uintptr_t)b.X[i] % (xv * esz)) != 0) return false;
     return true;
 }
 
@@ -610,7 +613,7 @@ static int launch_exact_staged(const Geometry &g, const ExactPlan &pl, const voi
 
 int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void *ws, hipStream_t st, CombineQueue *defer)
 {
-    if (plan.stream && batch_aligned(g, b, plan.xv)) {
+    if ((plan.stream || plan.mm16) && batch_aligned(g, b, plan.xv, plan.mm16 ? 8 : 4)) {
         // one launch for the whole batch; problem i owns the i-th slice of the workspace.  The
         // workgroup target is for the whole launch: a batch splits each reduction less finely.
         ExactPlan pl = plan;
@@ -621,7 +624,7 @@ int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void 
         float *out[kMaxBatch];
         const long prob_stride = (long)pl.splits * g.dw_elems();
         for (int i = 0; i < b.n; ++i) out[i] = pl.splits > 1 ? (float *)ws + i * prob_stride : b.dW[i];
-        int rc = launch_exact_stream(g, pl, b, out, st);
+        int rc = pl.mm16 ? launch_exact_bf16(g, pl, b, out, st) : launch_exact_stream(g, pl, b, out, st);
         if (rc != WGRAD_OK) return rc;
         if (pl.splits > 1)
             return launch_combine((const float *)ws, prob_stride, pl.splits, g.dw_elems(), 1.0f, b.dW, b.n, st, defer);
@@ -629,7 +632,7 @@ int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void 
     }
     // staged form: one problem at a time (shapes or alignments the streaming form does not take),
     // each in its own slice of the workspace
-    const ExactPlan pl = plan.stream ? plan_exact(g, false) : plan;
+    const ExactPlan pl = (plan.stream || plan.mm16) ? plan_exact(g, false) : plan;
     for (int i = 0; i < b.n; ++i) {
         int rc = launch_exact_staged(g, pl, b.X[i], b.dY[i], b.dW[i], (char *)ws + (size_t)i * align_up(plan.ws_bytes), st, defer);
         if (rc != WGRAD_OK) return rc;

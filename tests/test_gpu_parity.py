@@ -30,6 +30,10 @@ SMALL = [
     (6, 80, 4, 4, 260, 3, 3, 1, 1, 1, 1),       # many output channels on tiny planes (LDS gather, ragged tiles)
     (5, 32, 8, 8, 64, 3, 3, 2, 2, 1, 1),        # stride 2 on small planes
     (40, 64, 2, 2, 512, 3, 3, 1, 1, 1, 1),      # 2x2 planes: most taps fall on padding
+    (6, 16, 32, 32, 64, 3, 3, 1, 1, 1, 1),      # K a multiple of 64: the bf16 matrix-core kernel when the dtype is bf16
+    (12, 32, 16, 16, 64, 3, 3, 1, 1, 1, 1),
+    (24, 128, 8, 8, 192, 3, 3, 1, 1, 1, 1),     # several K tiles and channel tiles, four images per tile
+    (33, 16, 4, 4, 64, 3, 3, 1, 1, 1, 1),       # 4x4 planes, a ragged last image group
 ]
 
 
