@@ -54,7 +54,11 @@ __host__ __device__ constexpr int bf16_xslots(int gpw) { return gpw >= 2 ? 5 : 3
 // GPW: 32-position groups per wavefront and tile (the four wavefronts split the positions of a
 // tile, 128 * GPW in all, padded with dead positions if the shape gives fewer).
 // ROWP: window row pitch in elements, compile-time so that the tap offsets are immediates.
-template <int GPW, int ROWP>
+// FULL: every position of a tile is a real one (q == 128 * GPW): the A registers are then used as
+// loaded; otherwise the pieces of dead positions are replaced by zeros first.
+// P4: 2x2 planes (H = W = 2).  A map is four elements, so a lane's eight positions are two images
+// (two 8-byte loads of dY), and an input plane is staged whole: one 8-byte piece per (image, channel).
+template <int GPW, int ROWP, bool FULL, bool P4>
 __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p)
 {
     constexpr int MT = kBf16MT, KT = kBf16KT, NT = 9, NCB = NT * 16;
@@ -80,6 +84,8 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
     const int k0 = ktile * KT;
     const int c_first = coltile * 16;
 
+    TRACE(0);
+    TRACE_BLK(0);
     float4_t acc[MT][NT];
 #pragma unroll
     for (int m = 0; m < MT; ++m)
@@ -105,17 +111,32 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
         }
     }
     const uint32_t row_tile_bytes = 16u * L * 2u;       // from row tile m to m + 1
+    const uint32_t image_bytes = (uint32_t)g.K * L * 2u;  // P4: from a map to the same channel's map of the next image
+    auto load_a = [&](const char *base, uint32_t off) -> uint4_t {
+        if (P4) {
+            const uint2 lo = *(const uint2 *)(base + off), hi = *(const uint2 *)(base + off + image_bytes);
+            return uint4_t{lo.x, lo.y, hi.x, hi.y};
+        }
+        return *(const uint4_t *)(base + off);
+    };
 
     // ---- X window: this thread's staging slots (row pieces of four elements), decoded once ----
     int x_pack[XS];              // word index of column 4jv | ih_l << 20 | first piece of its row << 28 | last << 29, -1 = unused
     uint32_t x_src[XS];          // byte offset from row 0 of the tile's first (image, channel)
     {
-        const int x_total = 16 * p.nti * p.iht * (int)p.d_wv.d;
+        const int x_total = P4 ? 16 * p.nti : 16 * p.nti * p.iht * (int)p.d_wv.d;
 #pragma unroll
         for (int u = 0; u < XS; ++u) {
             const int e = tid + u * kBlock;
             x_pack[u] = -1; x_src[u] = 0;
-            if (e < x_total) {
+            if (P4) {
+                // piece = the plane of (image e / 16, channel e % 16); its window is 4 rows of 4: 8 words
+                if (e < x_total) {
+                    const int n_l = e >> 4, c_l = e & 15;
+                    x_pack[u] = bf16_chan_off(c_l, p.ppw) + n_l * 8 + 2;
+                    x_src[u] = ((n_l * g.C + c_l) * 4) * 2;
+                }
+            } else if (e < x_total) {
                 uint32_t row, jv, c_l, rem, n_l, ih_l;
                 p.d_wv.divmod(e, row, jv);
                 p.d_rows.divmod(row, c_l, rem);
@@ -146,6 +167,11 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
         int ih0;
         tile_origin(wt, live, dyb, xb, ih0);
         x_row_ok = 0;
+        if (P4) {
+#pragma unroll
+            for (int u = 0; u < XS; ++u) xr[u] = *(const uint2 *)(xb + (live ? x_src[u] : 0u));
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < XS; ++u) {
             int ih = ih0 + ((x_pack[u] >> 20) & 0xff);
@@ -160,6 +186,19 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
     // lanes, and a row never straddles a group of 16 lanes); the last piece of a row also writes
     // (x3, halo).
     auto commit_x = [&](uint32_t *buf) {
+        if (P4) {
+            // rows 1 and 2 of the plane's window: (halo, x00) (x01, halo) (halo, x10) (x11, halo)
+#pragma unroll
+            for (int u = 0; u < XS; ++u)
+                if (x_pack[u] >= 0) {
+                    uint32_t *w = buf + x_pack[u];
+                    w[0] = xr[u].x << 16;
+                    w[1] = xr[u].x >> 16;
+                    w[2] = xr[u].y << 16;
+                    w[3] = xr[u].y >> 16;
+                }
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < XS; ++u) {
             const bool ok = (x_row_ok >> u) & 1;
@@ -184,7 +223,7 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
 #pragma unroll
         for (int gi = 0; gi < GPW; ++gi)
 #pragma unroll
-            for (int m = 0; m < MT; ++m) ring[gi][m] = *(const uint4_t *)(dyb + m * row_tile_bytes + a_off[gi]);
+            for (int m = 0; m < MT; ++m) ring[gi][m] = load_a(dyb + m * row_tile_bytes, a_off[gi]);
     }
     for (int q2 = tid; q2 < QT / 2; q2 += kBlock) {
         const int q = 2 * q2;
@@ -200,15 +239,26 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
     for (int e = tid; e < (2 * p.buf_words) >> 2; e += kBlock) ((uint4_t *)Xs0)[e] = uint4_t{0u, 0u, 0u, 0u};
     const int lane_base = (c_first + i16 < g.C ? bf16_chan_off(i16, p.ppw) : 0) * 4;
     __syncthreads();
+    TRACE(1);
     commit_x(Xs0);
     load_x(wt_begin + 1);
+    TRACE(2);
 
     int par = 0;
     for (int wt = wt_begin; wt < wt_end; ++wt, par ^= 1) {
+        if (wt == wt_begin + 2) TRACE(3);
         __syncthreads();   // window of tile wt is complete; everyone has left the buffer tile wt+1 goes to
+        if (wt == wt_begin + 2) TRACE(4);
+        if (wt == wt_begin + 3) TRACE(8);
         const char *Xw = (const char *)(Xs0 + par * p.buf_words) + lane_base;
         commit_x(Xs0 + (par ^ 1) * p.buf_words);
+        if (wt == wt_begin + 2) TRACE(5);
         load_x(wt + 2);
+        if (wt == wt_begin + 2) TRACE(6);
+        // keep these loads here: sunk below the matrix instructions (which would save their registers)
+        // they would be the youngest loads in flight at the next commit, which then waits a full
+        // memory round trip
+        __builtin_amdgcn_sched_barrier(0);
         const bool has_next = wt + 1 < wt_end;
         const char *dyb, *xb;
         int ih0;
@@ -220,12 +270,15 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
             const int4 po = *(const int4 *)(xoffp + 16 * (wq * GPW + gi) + 4 * kk);
             const char *a0[4] = {Xw + po.x, Xw + po.y, Xw + po.z, Xw + po.w};
             bf16x8_t a_cur[MT];
-            const bool live = (a_live >> gi) & 1u;
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
-                const uint4_t v = live ? ring[gi][m] : uint4_t{0u, 0u, 0u, 0u};
+                const uint4_t v = (FULL || ((a_live >> gi) & 1u)) ? ring[gi][m] : uint4_t{0u, 0u, 0u, 0u};
                 a_cur[m] = __builtin_bit_cast(bf16x8_t, v);
-                ring[gi][m] = *(const uint4_t *)(dyb + m * row_tile_bytes + (has_next ? a_off[gi] : 0u));   // same piece of the next tile
+            }
+            if (!FULL) {
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    ring[gi][m] = load_a(dyb + m * row_tile_bytes, has_next ? a_off[gi] : 0u);   // same piece of the next tile
             }
 #pragma unroll
             for (int r = 0; r < 3; ++r) {
@@ -248,8 +301,17 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
                         acc[m][r * 3 + s3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a_cur[m], bv, acc[m][r * 3 + s3], 0, 0, 0);
                 }
             }
+            if (FULL) {
+                // the registers are free again: same piece of the next tile
+#pragma unroll
+                for (int m = 0; m < MT; ++m)
+                    ring[gi][m] = load_a(dyb + m * row_tile_bytes, has_next ? a_off[gi] : 0u);
+            }
+            if (wt == wt_begin + 2 && gi == 0) TRACE(11);
         }
+        if (wt == wt_begin + 2) TRACE(7);
     }
+    TRACE(9);
 
     // ---- epilogue, one row tile at a time: wavefronts park their accumulators in LDS (column-major,
     //      the four rows a lane holds side by side), then all threads add the four position slices
@@ -282,6 +344,8 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
             }
         }
     }
+    TRACE(10);
+    TRACE_BLK(1);
 }
 
 }  // namespace wgrad
