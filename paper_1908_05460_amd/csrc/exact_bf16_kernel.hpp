@@ -62,6 +62,7 @@ template <int GPW, int ROWP, bool FULL, bool P4>
 __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p)
 {
     constexpr int MT = kBf16MT, KT = kBf16KT, NT = 9, NCB = NT * 16;
+    constexpr bool ROW8 = ROWP >= 12;                   // map rows of 8, 16 or 32: a lane's eight positions share a row
     constexpr int QT = 128 * GPW;
     constexpr int XS = bf16_xslots(GPW);
     extern __shared__ float smem[];
@@ -96,12 +97,18 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
     const int wt_begin = (int)((long)split * tiles_total / p.splits);
     const int wt_end = (int)((long)(split + 1) * tiles_total / p.splits);
 
+    // First of the eight positions this lane contracts in group gi.  Groups come in pairs whose lanes
+    // take adjacent runs of eight positions, so that the two 16-byte pieces a lane loads for a pair
+    // share a 128-byte line with the other three lanes of its row.
+    auto first_position = [&](int gi) {
+        return GPW % 2 == 0 ? 64 * (wq * (GPW / 2) + gi / 2) + 16 * kk + 8 * (gi & 1) : 32 * (wq * GPW + gi) + 8 * kk;
+    };
     // ---- A operand: byte offsets of this lane's 16-byte pieces from the tile's first element ----
     uint32_t a_off[GPW];
     uint32_t a_live = 0;
 #pragma unroll
     for (int gi = 0; gi < GPW; ++gi) {
-        const int q = 32 * (wq * GPW + gi) + 8 * kk;
+        const int q = first_position(gi);
         a_off[gi] = 0;
         if (q < p.q) {
             uint32_t n_l, rem;
@@ -112,9 +119,10 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
     }
     const uint32_t row_tile_bytes = 16u * L * 2u;       // from row tile m to m + 1
     const uint32_t image_bytes = (uint32_t)g.K * L * 2u;  // P4: from a map to the same channel's map of the next image
+    // uniform base + 32-bit lane offset: the address needs no vector arithmetic
     auto load_a = [&](const char *base, uint32_t off) -> uint4_t {
         if (P4) {
-            const uint2 lo = *(const uint2 *)(base + off), hi = *(const uint2 *)(base + off + image_bytes);
+            const uint2 lo = *(const uint2 *)(base + off), hi = *(const uint2 *)(base + image_bytes + off);
             return uint4_t{lo.x, lo.y, hi.x, hi.y};
         }
         return *(const uint4_t *)(base + off);
@@ -251,7 +259,12 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
         if (wt == wt_begin + 2) TRACE(4);
         if (wt == wt_begin + 3) TRACE(8);
         const char *Xw = (const char *)(Xs0 + par * p.buf_words) + lane_base;
+#ifdef WGRAD_BF16_PRIO            // timing experiments
+        __builtin_amdgcn_s_setprio(WGRAD_BF16_PRIO);
+#endif
+#ifndef WGRAD_BF16_NOCOMMIT      // timing experiments only: results are then wrong
         commit_x(Xs0 + (par ^ 1) * p.buf_words);
+#endif
         if (wt == wt_begin + 2) TRACE(5);
         load_x(wt + 2);
         if (wt == wt_begin + 2) TRACE(6);
@@ -259,15 +272,21 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
         // they would be the youngest loads in flight at the next commit, which then waits a full
         // memory round trip
         __builtin_amdgcn_sched_barrier(0);
+#ifdef WGRAD_BF16_PRIO
+        __builtin_amdgcn_s_setprio(0);
+#endif
         const bool has_next = wt + 1 < wt_end;
         const char *dyb, *xb;
         int ih0;
         tile_origin(wt + 1, has_next, dyb, xb, ih0);
 
+        uint32_t a_next[GPW];                       // offsets of the next tile's pieces (0: nothing to fetch)
+#pragma unroll
+        for (int gi = 0; gi < GPW; ++gi) a_next[gi] = has_next ? a_off[gi] : 0u;
 #pragma unroll
         for (int gi = 0; gi < GPW; ++gi) {
-            // pair addresses of this lane's eight positions in both copies
-            const int4 po = *(const int4 *)(xoffp + 16 * (wq * GPW + gi) + 4 * kk);
+            // pair addresses of this lane's eight positions
+            const int4 po = *(const int4 *)(xoffp + first_position(gi) / 2);
             const char *a0[4] = {Xw + po.x, Xw + po.y, Xw + po.z, Xw + po.w};
             bf16x8_t a_cur[MT];
 #pragma unroll
@@ -278,23 +297,36 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
             if (!FULL) {
 #pragma unroll
                 for (int m = 0; m < MT; ++m)
-                    ring[gi][m] = load_a(dyb + m * row_tile_bytes, has_next ? a_off[gi] : 0u);   // same piece of the next tile
+                    ring[gi][m] = load_a(dyb + m * row_tile_bytes, a_next[gi]);   // same piece of the next tile
             }
 #pragma unroll
             for (int r = 0; r < 3; ++r) {
-                uint32_t lo[4], hi[4];
+                // lo[j], hi[j]: the words of window columns (w, w+1) and (w+2, w+3) of pair j.  With
+                // eight positions in one row (ROW8) the pairs are neighbours, hi[j] = lo[j+1]: the
+                // five words are read as two quadruples that are the operands of taps 0 and 2 as
+                // they stand; otherwise every pair has an address of its own.
+                uint4_t lo, hi;
+                if (ROW8) {
+                    const uint32_t *wp = (const uint32_t *)(a0[0] + r * ROWP * 2);
 #pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const uint32_t *wp = (const uint32_t *)(a0[j] + r * ROWP * 2);
-                    lo[j] = wp[0];
-                    hi[j] = wp[1];
+                    for (int j = 0; j < 4; ++j) { lo[j] = wp[j]; hi[j] = wp[j + 1]; }
+                } else {
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) {
+                        const uint32_t *wp = (const uint32_t *)(a0[j] + r * ROWP * 2);
+                        lo[j] = wp[0];
+                        hi[j] = wp[1];
+                    }
                 }
 #pragma unroll
                 for (int s3 = 0; s3 < 3; ++s3) {
                     uint4_t b;
+                    if (s3 == 0) b = lo;
+                    else if (s3 == 2) b = hi;
+                    else {
 #pragma unroll
-                    for (int j = 0; j < 4; ++j)
-                        b[j] = s3 == 0 ? lo[j] : (s3 == 2 ? hi[j] : __builtin_amdgcn_alignbit(hi[j], lo[j], 16));
+                        for (int j = 0; j < 4; ++j) b[j] = __builtin_amdgcn_alignbit(hi[j], lo[j], 16);
+                    }
                     const bf16x8_t bv = __builtin_bit_cast(bf16x8_t, b);
 #pragma unroll
                     for (int m = 0; m < MT; ++m)
@@ -305,7 +337,11 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
                 // the registers are free again: same piece of the next tile
 #pragma unroll
                 for (int m = 0; m < MT; ++m)
-                    ring[gi][m] = load_a(dyb + m * row_tile_bytes, has_next ? a_off[gi] : 0u);
+#ifndef WGRAD_BF16_NOALOAD       // timing experiments only
+                    ring[gi][m] = load_a(dyb + m * row_tile_bytes, a_next[gi]);
+#else
+                    ;
+#endif
             }
             if (wt == wt_begin + 2 && gi == 0) TRACE(11);
         }
