@@ -476,11 +476,32 @@ __global__ __launch_bounds__(kBlock) void approx_fused(ApproxBatch ab, Geometry 
 #define WGRAD_GATHER_BLOCKS 256
 #endif
 
-ApproxPlan plan_approx(const Geometry &g, bool allow_lds, bool allow_fused)
+ApproxPlan plan_approx(const Geometry &g, bool allow_lds, bool allow_fused, bool allow_mm)
 {
     ApproxPlan pl{};
     const long outs = g.dw_elems();
     const int HW = g.H * g.W;
+    // bf16 inputs, shapes the bf16 matrix-core kernel takes: the approximated gradient is the exact
+    // one of the sparsified dY (Section 2.4), and contracting that on the matrix core -- the operand
+    // built in registers from each map's selected position and sum -- outruns any gather from LDS
+    // (16 K multiply-adds per instruction against 64), even though all but one of a map's slots are zero
+    // -- up to maps of 256 positions; beyond, the fused kernel below is bound by its dY stream and wins
+    if (allow_mm && g.bf16 && g.Ho * g.Wo <= 256 && tune_int("WGRAD_APPROX_MM", 1)) {
+        const ExactPlan ex = plan_exact(g);
+        if (ex.ok && ex.mm16) {
+            pl.mm = 1;
+            pl.ex = ex;
+            pl.chunks = ex.splits; pl.chunk_n = 0;
+            size_t off = 0;
+            pl.off_idx = off; off += align_up((size_t)g.N * g.K * 4);
+            pl.off_sum = off; off += align_up((size_t)g.N * g.K * 4);
+            pl.off_part = off; off += ex.splits > 1 ? align_up((size_t)ex.splits * outs * 4) : 0;
+            pl.ws_bytes = off;
+            const size_t alt = plan_approx(g, false, false, false).ws_bytes;
+            if (alt > pl.ws_bytes) pl.ws_bytes = alt;
+            return pl;
+        }
+    }
     // LDS form when every input element is used several times over by the K patches of its image
     // haloed plane: rows/cols -pad .. max(last tap the positions can reach, last row/col of X)
     const int hp = std::max((g.Ho - 1) * g.sh + 3, g.H + g.ph), wp = std::max((g.Wo - 1) * g.sw + 3, g.W + g.pw);
@@ -553,7 +574,7 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
     bool aligned = true;
     for (int i = 0; i < b.n; ++i)
         aligned = aligned && ((uintptr_t)b.X[i] % (g.bf16 ? 8 : 16)) == 0 && ((uintptr_t)b.dY[i] % (g.bf16 ? 8 : 16)) == 0;
-    ApproxPlan pl = ((plan.use_lds || plan.fused) && !aligned) ? plan_approx(g, false, false) : plan;
+    ApproxPlan pl = ((plan.use_lds || plan.fused || plan.mm) && !aligned) ? plan_approx(g, false, false, false) : plan;
     const long outs = g.dw_elems();
     if (pl.fused && b.n > 1) {
         // the workgroup target is for the whole launch: a batch chunks each problem less finely
@@ -576,6 +597,28 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
     }
     const float kscale = pl.chunks > 1 ? 1.0f : scale;
     int rc;
+    if (pl.mm) {
+        rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st);
+        if (rc != WGRAD_OK) return rc;
+        ExactPlan ex = pl.ex;
+        if (b.n > 1) {
+            const int splits = choose_splits(ex, b.n);
+            if (splits < ex.splits) ex.splits = splits;
+        }
+        SparseA sp{};
+        float *out[kMaxBatch];
+        const long prob_stride = (long)(plan.ws_bytes / 4);
+        for (int i = 0; i < b.n; ++i) {
+            sp.hw[i] = ab.hw[i]; sp.sum[i] = ab.sum[i];
+            out[i] = ex.splits > 1 ? (float *)((char *)ws + (size_t)i * plan.ws_bytes + pl.off_part) : b.dW[i];
+        }
+        sp.scale = ex.splits > 1 ? 1.0f : scale;
+        rc = launch_exact_bf16(g, ex, b, out, st, &sp);
+        if (rc != WGRAD_OK) return rc;
+        if (ex.splits > 1)
+            return launch_combine((const float *)((char *)ws + pl.off_part), prob_stride, ex.splits, outs, scale, b.dW, b.n, st, defer);
+        return WGRAD_OK;
+    }
     if (pl.fused) {
         FusedParams fp;
         fp.chunk_n = pl.chunk_n; fp.scale = kscale;

@@ -88,7 +88,15 @@ ExactPlan plan_exact(const Geometry &g, bool allow_stream = true);
 bool plan_exact_stream(const Geometry &g, ExactPlan &pl);
 int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st);
 bool plan_exact_bf16(const Geometry &g, ExactPlan &pl);
-int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st);
+// The A operand of the bf16 matrix-core kernel given as the sparsified gradient of the
+// approximation: per problem, every map's selected position (row << 16 | col) and sum.
+struct SparseA {
+    const int32_t *hw[kMaxBatch];
+    const float *sum[kMaxBatch];
+    float scale;                     // applied by the kernel when it writes dW itself (one split)
+};
+int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st,
+                      const SparseA *sparse = nullptr);
 struct CombineQueue;
 int launch_exact(const Geometry &g, const ExactPlan &pl, const Batch &b, void *ws, hipStream_t st,
                  CombineQueue *defer = nullptr);
@@ -98,9 +106,11 @@ size_t exact_ws_per_problem(const Geometry &g, const ExactPlan &pl);
 struct ApproxPlan {
     int chunks, chunk_n;             // batch chunks whose partial sums are combined afterwards
     int use_lds, fused, m, nb, pitch, wp, ctiles, ktiles;   // LDS form of the gather: tile shape
+    int mm;                          // contraction on the bf16 matrix core from the selection results
+    ExactPlan ex;                    // its plan
     size_t off_idx, off_sum, off_part, ws_bytes;
 };
-ApproxPlan plan_approx(const Geometry &g, bool allow_lds = true, bool allow_fused = true);
+ApproxPlan plan_approx(const Geometry &g, bool allow_lds = true, bool allow_fused = true, bool allow_mm = true);
 int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, hipStream_t st);
 int launch_approx(const Geometry &g, const ApproxPlan &pl, const Batch &b, float scale,
                   int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer = nullptr);

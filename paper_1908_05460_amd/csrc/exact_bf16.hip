@@ -58,31 +58,41 @@ bool plan_exact_bf16(const Geometry &g, ExactPlan &pl)
     return false;
 }
 
-template <int GPW, int ROWP, bool FULL>
+template <int GPW, int ROWP, bool FULL, bool SPARSE>
 static void bf16_inst2(const Bf16Params &p, int grid, size_t lds, hipStream_t st)
 {
     constexpr bool P4 = ROWP == 4;
     // more than 64 KB of dynamic LDS has to be granted per kernel function (the CU has 160 KB)
-    if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)wgrad_exact_bf16<GPW, ROWP, FULL, P4>,
+    if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)wgrad_exact_bf16<GPW, ROWP, FULL, P4, SPARSE>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return;
-    WGRAD_LAUNCH((wgrad_exact_bf16<GPW, ROWP, FULL, P4>), dim3(grid), dim3(kBlock), lds, st, p);
+    WGRAD_LAUNCH((wgrad_exact_bf16<GPW, ROWP, FULL, P4, SPARSE>), dim3(grid), dim3(kBlock), lds, st, p);
 }
 
 template <int GPW, int ROWP>
 static void bf16_inst(const Bf16Params &p, int grid, size_t lds, hipStream_t st)
 {
-    if (p.q == 128 * GPW) bf16_inst2<GPW, ROWP, true>(p, grid, lds, st);
-    else bf16_inst2<GPW, ROWP, false>(p, grid, lds, st);
+    const bool sparse = p.hw[0] != nullptr;
+    if (p.q == 128 * GPW) {
+        if (sparse) bf16_inst2<GPW, ROWP, true, true>(p, grid, lds, st);
+        else bf16_inst2<GPW, ROWP, true, false>(p, grid, lds, st);
+    } else {
+        if (sparse) bf16_inst2<GPW, ROWP, false, true>(p, grid, lds, st);
+        else bf16_inst2<GPW, ROWP, false, false>(p, grid, lds, st);
+    }
 }
 
 // Enqueues the kernel (not the combine); the caller has checked pointer alignment (16 bytes).
-int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st)
+int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st,
+                      const SparseA *sparse)
 {
     Bf16Params p{};
     for (int i = 0; i < kMaxBatch; ++i) {          // unused slots repeat problem 0
         const int j = i < b.n ? i : 0;
         p.X[i] = b.X[j]; p.dY[i] = b.dY[j]; p.out[i] = out[j];
+        p.hw[i] = sparse ? sparse->hw[j] : nullptr;
+        p.sum[i] = sparse ? sparse->sum[j] : nullptr;
     }
+    p.scale = sparse ? sparse->scale : 1.0f;
     p.per_prob = pl.ktiles * pl.ctiles * pl.splits;
     p.g = g;
     p.ktiles = pl.ktiles; p.ctiles = pl.ctiles; p.splits = pl.splits;

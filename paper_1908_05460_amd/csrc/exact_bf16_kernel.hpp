@@ -28,6 +28,9 @@ typedef uint32_t uint4_t __attribute__((ext_vector_type(4)));
 struct Bf16Params {
     const void *X[kMaxBatch], *dY[kMaxBatch];
     float *out[kMaxBatch];      // per problem: dW when splits == 1, else partials [splits][K][C*9]
+    const int32_t *hw[kMaxBatch];   // SPARSE: selected position of every map, (row << 16 | col), [N][K]
+    const float *sum[kMaxBatch];    // SPARSE: sum of every map, [N][K]
+    float scale;                // applied to what the kernel writes
     int per_prob;               // workgroups per problem
     Geometry g;
     int ktiles, ctiles, splits;
@@ -56,9 +59,14 @@ __host__ __device__ constexpr int bf16_xslots(int gpw) { return gpw >= 2 ? 5 : 3
 // ROWP: window row pitch in elements, compile-time so that the tap offsets are immediates.
 // FULL: every position of a tile is a real one (q == 128 * GPW): the A registers are then used as
 // loaded; otherwise the pieces of dead positions are replaced by zeros first.
+// SPARSE: the A operand is not dY but the sparsified gradient of the max-gradient approximation
+// (Section 2.4: its filter gradient is the exact one of a dY that keeps one entry per map): a map
+// is given by its selected position and its sum, and a lane builds its operand in registers -- the
+// sum, rounded to bf16, in the slot of the selected position if that is one of its eight, zeros
+// elsewhere.  Nothing of dY is read.
 // P4: 2x2 planes (H = W = 2).  A map is four elements, so a lane's eight positions are two images
 // (two 8-byte loads of dY), and an input plane is staged whole: one 8-byte piece per (image, channel).
-template <int GPW, int ROWP, bool FULL, bool P4>
+template <int GPW, int ROWP, bool FULL, bool P4, bool SPARSE>
 __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p)
 {
     constexpr int MT = kBf16MT, KT = kBf16KT, NT = 9, NCB = NT * 16;
@@ -78,7 +86,8 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
     const int prob = logical_all / p.per_prob;
     const int logical = logical_all - prob * p.per_prob;
     const char *const Xp = (const char *)p.X[prob];
-    const char *const dYp = (const char *)p.dY[prob];
+    const char *const dYp = SPARSE ? (const char *)p.hw[prob] : (const char *)p.dY[prob];
+    const char *const sump = (const char *)p.sum[prob];
     const int coltile = logical % p.ctiles;
     const int ktile = (logical / p.ctiles) % p.ktiles;
     const int split = logical / (p.ctiles * p.ktiles);
@@ -105,22 +114,31 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
     };
     // ---- A operand: byte offsets of this lane's 16-byte pieces from the tile's first element ----
     uint32_t a_off[GPW];
+    int a_pos[GPW];                                     // SPARSE: position within the tile's rows of the lane's first slot
     uint32_t a_live = 0;
 #pragma unroll
     for (int gi = 0; gi < GPW; ++gi) {
         const int q = first_position(gi);
-        a_off[gi] = 0;
+        a_off[gi] = 0; a_pos[gi] = 0;
         if (q < p.q) {
             uint32_t n_l, rem;
             p.d_seg.divmod(q, n_l, rem);
-            a_off[gi] = ((n_l * g.K + i16) * L + rem) * 2;
+            a_off[gi] = SPARSE ? (n_l * g.K + i16) * 4 : ((n_l * g.K + i16) * L + rem) * 2;
+            a_pos[gi] = rem;
             a_live |= 1u << gi;
         }
     }
-    const uint32_t row_tile_bytes = 16u * L * 2u;       // from row tile m to m + 1
-    const uint32_t image_bytes = (uint32_t)g.K * L * 2u;  // P4: from a map to the same channel's map of the next image
+    const uint32_t row_tile_bytes = SPARSE ? 64u : 16u * L * 2u;       // from row tile m to m + 1
+    const uint32_t image_bytes = SPARSE ? (uint32_t)g.K * 4u : (uint32_t)g.K * L * 2u;  // P4: to the same channel's map of the next image
     // uniform base + 32-bit lane offset: the address needs no vector arithmetic
     auto load_a = [&](const char *base, uint32_t off) -> uint4_t {
+        if (SPARSE) {
+            // (position, sum) of the lane's map, and of the next image's for 2x2 planes
+            const char *sbase = sump + (base - dYp);
+            uint4_t v{*(const uint32_t *)(base + off), *(const uint32_t *)(sbase + off), 0u, 0u};
+            if (P4) { v[2] = *(const uint32_t *)(base + image_bytes + off); v[3] = *(const uint32_t *)(sbase + image_bytes + off); }
+            return v;
+        }
         if (P4) {
             const uint2 lo = *(const uint2 *)(base + off), hi = *(const uint2 *)(base + image_bytes + off);
             return uint4_t{lo.x, lo.y, hi.x, hi.y};
@@ -165,7 +183,7 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
         uint32_t ng, hti;
         p.d_htiles.divmod(w, ng, hti);
         const int n0 = ng * p.nti, h0 = hti * p.ht;
-        dy_base = dYp + (((long)n0 * g.K + k0) * g.Ho + h0) * g.Wo * 2;
+        dy_base = SPARSE ? dYp + ((long)n0 * g.K + k0) * 4 : dYp + (((long)n0 * g.K + k0) * g.Ho + h0) * g.Wo * 2;
         x_base = Xp + ((long)n0 * g.C + c_first) * g.H * g.W * 2;
         ih0 = h0 - 1;
     };
@@ -220,6 +238,24 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
                 if ((x_pack[u] >> 29) & 1) w[2] = r1 >> 16;
             }
         }
+    };
+
+    // SPARSE: sel = (position, sum) of the lane's map [and of the next image's map]; pos0 = position in
+    // the map of the lane's first slot.  bf16 rounding of the sum is to nearest even.
+    auto sparse_operand = [&](uint4_t sel, int pos0) -> uint4_t {
+        uint4_t out{0u, 0u, 0u, 0u};
+        auto put = [&](uint32_t hwv, uint32_t sbits, int first, int word0, int nslots) {
+            const int rel = (int)((hwv >> 16) * g.Wo + (hwv & 0xffffu)) - first;
+            const uint32_t b = (sbits + 0x7fffu + ((sbits >> 16) & 1u)) >> 16;
+            const uint32_t val = (rel & 1) ? b << 16 : b;
+            const bool in = (unsigned)rel < (unsigned)nslots;
+#pragma unroll
+            for (int w = 0; w < 4; ++w)
+                if (w >= word0 && w < word0 + nslots / 2) out[w] = (in && (rel >> 1) == w - word0) ? val : 0u;
+        };
+        if (P4) { put(sel[0], sel[1], 0, 0, 4); put(sel[2], sel[3], 0, 2, 4); }
+        else put(sel[0], sel[1], pos0, 0, 8);
+        return out;
     };
 
     // ---- prologue: first loads, then the LDS tables and the zero fill under their latency ----
@@ -278,6 +314,8 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
         const bool has_next = wt + 1 < wt_end;
         const char *dyb, *xb;
         int ih0;
+        int flat0 = 0;                               // SPARSE: position in the map of the tile's first row
+        if (SPARSE) { tile_origin(wt, true, dyb, xb, ih0); flat0 = (ih0 + 1) * g.Wo; }
         tile_origin(wt + 1, has_next, dyb, xb, ih0);
 
         uint32_t a_next[GPW];                       // offsets of the next tile's pieces (0: nothing to fetch)
@@ -291,7 +329,9 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
             bf16x8_t a_cur[MT];
 #pragma unroll
             for (int m = 0; m < MT; ++m) {
-                const uint4_t v = (FULL || ((a_live >> gi) & 1u)) ? ring[gi][m] : uint4_t{0u, 0u, 0u, 0u};
+                uint4_t v = ring[gi][m];
+                if (SPARSE) v = sparse_operand(v, flat0 + a_pos[gi]);
+                if (!FULL && !((a_live >> gi) & 1u)) v = uint4_t{0u, 0u, 0u, 0u};
                 a_cur[m] = __builtin_bit_cast(bf16x8_t, v);
             }
             if (!FULL) {
@@ -374,7 +414,7 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
 #pragma unroll
                     for (int v = 0; v < 4; ++v) {
                         const int k = k0 + m * 16 + 4 * rq + v;
-                        if (k < g.K) out[(long)k * CRS + col] = sum[v];
+                        if (k < g.K) out[(long)k * CRS + col] = sum[v] * p.scale;
                     }
                 }
             }
