@@ -363,12 +363,17 @@ __global__ __launch_bounds__(kBlock) void approx_fused(ApproxBatch ab, Geometry 
     __shared__ float red[4][kFusedJ * 64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int k = blockIdx.x;
-    const char *__restrict__ X = (const char *)ab.X[blockIdx.z];
-    const char *__restrict__ dY = (const char *)ab.dY[blockIdx.z];
-    float *__restrict__ out = ab.out[blockIdx.z];
+    // The K workgroups of one (problem, batch chunk) read the same input planes: number the workgroups so
+    // that they sit on one XCD and find each other's planes in its L2.
+    const int linear = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    const int logical = xcd_contiguous_id(linear, gridDim.x * gridDim.y * gridDim.z);
+    const int k = logical % (int)gridDim.x;
+    const int by = (logical / (int)gridDim.x) % (int)gridDim.y, bz = logical / (int)(gridDim.x * gridDim.y);
+    const char *__restrict__ X = (const char *)ab.X[bz];
+    const char *__restrict__ dY = (const char *)ab.dY[bz];
+    float *__restrict__ out = ab.out[bz];
     const int L = g.Ho * g.Wo, RS = g.R * g.S, CRS = g.C * RS, HW = g.H * g.W;
-    const int n_begin = blockIdx.y * fp.chunk_n;
+    const int n_begin = by * fp.chunk_n;
     const int n_end = n_begin + fp.chunk_n < g.N ? n_begin + fp.chunk_n : g.N;
 
     // the dW entries j = lane + 64*jj of channel k that this lane accumulates
@@ -465,7 +470,7 @@ __global__ __launch_bounds__(kBlock) void approx_fused(ApproxBatch ab, Geometry 
 #pragma unroll
     for (int jj = 0; jj < kFusedJ; ++jj) red[wave][jj * 64 + lane] = acc[jj];
     __syncthreads();
-    float *o = out + ((long)blockIdx.y * g.K + k) * CRS;
+    float *o = out + ((long)by * g.K + k) * CRS;
     for (int j = tid; j < CRS; j += kBlock) o[j] = (red[0][j] + red[1][j] + red[2][j] + red[3][j]) * fp.scale;
 }
 
