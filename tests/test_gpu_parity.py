@@ -208,3 +208,38 @@ def test_schedule_run_equals_the_individual_calls():
         else: B.conv_wgrad_random(descs[i], ref, 1 / 128, 3, off)
         assert torch.equal(ref, dWs[i]), l.name
         off += ref.numel()
+
+
+def test_schedule_run_with_more_layers_than_one_table_or_group_holds():
+    """70 layers of five shapes and two dtypes, all four methods: groups of identical layers overflow
+    (more than 8 per shape and method) and so do the tables of the reduction and of the fills (more
+    than 32 tensors); every layer must still get the result of its individual call."""
+    import torch
+    from paper_1908_05460_amd import schedule as sch
+    shapes = [SMALL[0], SMALL[3], SMALL[4], SMALL[5], SMALL[18]]
+    nl = 70
+    descs, Xs, dYs, dWs, methods = [], [], [], [], []
+    for i in range(nl):
+        dtype = "bf16" if i % 7 == 3 else "fp32"
+        d = mk(shapes[i % len(shapes)], dtype)
+        X, dY = rand_inputs(d, 100 + i, dtype)
+        descs.append(d); Xs.append(to_gpu(X)); dYs.append(to_gpu(dY))
+        dWs.append(torch.full((d.K, d.C, d.R, d.S), float("nan"), device="cuda"))
+        methods.append([sch.EXACT, sch.APPROX, sch.EXACT, sch.ZERO, sch.APPROX, sch.RANDOM][i % 6])
+    methods = np.array(methods, np.uint8)
+    s = B.Schedule(descs, Xs, dYs, dWs)
+    ws = B.alloc_workspace(s.workspace_bytes(methods))
+    s.run(methods, ws, scale=0.25, sigma=1 / 128, seed=11, offset=5)
+    off = 5
+    for i in range(nl):
+        ref = torch.empty_like(dWs[i])
+        if methods[i] == sch.EXACT: B.conv_wgrad_exact(descs[i], Xs[i], dYs[i], dW=ref)
+        elif methods[i] == sch.APPROX: B.conv_wgrad_approx(descs[i], Xs[i], dYs[i], scale=0.25, dW=ref)
+        elif methods[i] == sch.ZERO: B.conv_wgrad_zero(descs[i], ref)
+        else: B.conv_wgrad_random(descs[i], ref, 1 / 128, 11, off)
+        if methods[i] in (sch.ZERO, sch.RANDOM):
+            assert torch.equal(ref, dWs[i]), i
+        else:   # the folded launch may split the reduction differently: same sum, another order
+            err = (ref - dWs[i]).abs().max().item() / max(ref.abs().max().item(), 1e-30)
+            assert err < 1e-5, (i, err)
+        off += ref.numel()
