@@ -44,10 +44,12 @@ bool plan_exact_bf16(const Geometry &g, ExactPlan &pl)
         size_t lds = ((size_t)2 * buf_words + qt / 2) * 4;
         const size_t red = (size_t)4 * 144 * 20 * 4;               // epilogue exchange buffer [4][144][20]
         if (red > lds) lds = red;
-        const long x_slots = p4 ? (long)16 * nti : (long)16 * nti * iht * (g.W / 4);
-        if (lds > 80 * 1024 || x_slots > (long)bf16_xslots(gpw) * kBlock || iht > 255) continue;   // two workgroups per CU
+        const int xv = p4 ? 4 : bf16_xv(rowp);
+        if (!p4 && g.W % xv != 0) continue;
+        const long x_slots = p4 ? (long)16 * nti : (long)16 * nti * iht * (g.W / xv);
+        if (lds > 80 * 1024 || x_slots > (long)bf16_xslots(gpw, rowp) * kBlock || iht > 255) continue;   // two workgroups per CU
         if ((long)nti * g.K * L * 2 >= (1l << 31) || (long)nti * g.C * g.H * g.W * 2 >= (1l << 31)) continue;
-        pl.mm16 = 1; pl.stream = 0; pl.gpw = gpw; pl.xv = 4;
+        pl.mm16 = 1; pl.stream = 0; pl.gpw = gpw; pl.xv = xv;
         pl.nt = 9; pl.wk = 1; pl.tap_mode = 1;
         pl.ktiles = g.K / kBf16KT; pl.ctiles = g.C / 16; pl.ctch = 16;
         pl.nti = nti; pl.ht = ht; pl.q = q; pl.qpad = qt; pl.qp = 0;
@@ -100,7 +102,7 @@ int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, fl
     p.h_tiles = pl.h_tiles; p.n_groups = pl.n_groups;
     p.seg = pl.ht * g.Wo;
     p.ppw = pl.pp; p.buf_words = pl.xbuf; p.rowp = pl.rowp;
-    p.d_wv = FastDiv(g.W >= 4 ? g.W / 4 : 1);
+    p.d_wv = FastDiv(g.W >= pl.xv ? g.W / pl.xv : 1);
     p.d_rows = FastDiv(pl.nti * pl.iht);
     p.d_iht = FastDiv(pl.iht);
     p.d_seg = FastDiv(p.seg);

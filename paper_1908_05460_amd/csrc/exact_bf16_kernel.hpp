@@ -51,8 +51,11 @@ constexpr int kBf16KT = 16 * kBf16MT;
 // takes every value exactly twice over 16 channels x 4 groups: the minimum for 64 lanes.
 __host__ __device__ __forceinline__ int bf16_chan_off(int c_l, int ppw) { return (c_l & 3) * ppw + (c_l >> 2) * (4 * ppw + 12); }
 
-// Window staging slots (8-byte row pieces, four elements) per thread and tile.
-__host__ __device__ constexpr int bf16_xslots(int gpw) { return gpw >= 2 ? 5 : 3; }
+// Elements of a window staging piece: 16-byte pieces where the input rows are a multiple of eight long
+// (the row pitches 12, 20, 36 belong to rows of 8, 16, 32), 8-byte pieces otherwise.
+__host__ __device__ constexpr int bf16_xv(int rowp) { return rowp >= 12 ? 8 : 4; }
+// Window staging slots (pieces) per thread and tile.
+__host__ __device__ constexpr int bf16_xslots(int gpw, int rowp) { return rowp >= 12 ? 3 : (gpw >= 2 ? 5 : 3); }
 
 // GPW: 32-position groups per wavefront and tile (the four wavefronts split the positions of a
 // tile, 128 * GPW in all, padded with dead positions if the shape gives fewer).
@@ -72,7 +75,7 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
     constexpr int MT = kBf16MT, KT = kBf16KT, NT = 9, NCB = NT * 16;
     constexpr bool ROW8 = ROWP >= 12;                   // map rows of 8, 16 or 32: a lane's eight positions share a row
     constexpr int QT = 128 * GPW;
-    constexpr int XS = bf16_xslots(GPW);
+    constexpr int XS = bf16_xslots(GPW, ROWP), XV = bf16_xv(ROWP);
     extern __shared__ float smem[];
     uint32_t *Xs0 = (uint32_t *)smem;                   // [2][buf_words]
     int *xoffp = (int *)(Xs0 + 2 * p.buf_words);        // [QT / 2] byte offsets of position pairs
@@ -167,15 +170,15 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
                 p.d_wv.divmod(e, row, jv);
                 p.d_rows.divmod(row, c_l, rem);
                 p.d_iht.divmod(rem, n_l, ih_l);
-                x_pack[u] = (int)(bf16_chan_off(c_l, p.ppw) + ((rem * ROWP + jv * 4) >> 1)) | (int)(ih_l << 20)
+                x_pack[u] = (int)(bf16_chan_off(c_l, p.ppw) + ((rem * ROWP + jv * XV) >> 1)) | (int)(ih_l << 20)
                             | (jv == 0 ? 1 << 28 : 0) | (jv + 1 == p.d_wv.d ? 1 << 29 : 0);
-                x_src[u] = ((n_l * g.C + c_l) * (g.H * g.W) + jv * 4) * 2;
+                x_src[u] = ((n_l * g.C + c_l) * (g.H * g.W) + jv * XV) * 2;
             }
         }
     }
 
     uint4_t ring[GPW][MT];
-    uint2 xr[XS];
+    uint32_t xr[XS][XV / 2];
     uint32_t x_row_ok = 0;
 
     auto tile_origin = [&](int wt, bool live, const char *&dy_base, const char *&x_base, int &ih0) {
@@ -195,7 +198,10 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
         x_row_ok = 0;
         if (P4) {
 #pragma unroll
-            for (int u = 0; u < XS; ++u) xr[u] = *(const uint2 *)(xb + (live ? x_src[u] : 0u));
+            for (int u = 0; u < XS; ++u) {
+                const uint2 v = *(const uint2 *)(xb + (live ? x_src[u] : 0u));
+                xr[u][0] = v.x; xr[u][1] = v.y;
+            }
             return;
         }
 #pragma unroll
@@ -203,14 +209,21 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
             int ih = ih0 + ((x_pack[u] >> 20) & 0xff);
             if (ih >= 0 && ih < g.H) x_row_ok |= 1u << u;
             ih = ih < 0 ? 0 : (ih >= g.H ? g.H - 1 : ih);
-            xr[u] = *(const uint2 *)(xb + (live ? x_src[u] + ih * (g.W * 2) : 0u));
+            const char *src = xb + (live ? x_src[u] + ih * (g.W * 2) : 0u);
+            if (XV == 8) {
+                const uint4_t v = *(const uint4_t *)src;
+                xr[u][0] = v[0]; xr[u][1] = v[1]; xr[u][2 % (XV / 2)] = v[2]; xr[u][3 % (XV / 2)] = v[3];
+            } else {
+                const uint2 v = *(const uint2 *)src;
+                xr[u][0] = v.x; xr[u][1] = v.y;
+            }
         }
     };
-    // Elements x0..x3 of a piece belong to window columns 4jv+1 .. 4jv+4 (column 0 is the halo): the
-    // aligned words of columns (4jv, 4jv+1) and (4jv+2, 4jv+3) are (x3 of the piece to the left, x0)
-    // and (x1, x2).  The left neighbour is the previous lane (pieces of a row sit in consecutive
+    // Elements x0..x{XV-1} of piece jv belong to window columns XV*jv+1 .. XV*jv+XV (column 0 is the
+    // halo): the aligned words starting at column XV*jv are (last element of the piece to the left,
+    // x0), (x1, x2), ...  The left neighbour is the previous lane (pieces of a row sit in consecutive
     // lanes, and a row never straddles a group of 16 lanes); the last piece of a row also writes
-    // (x3, halo).
+    // (x{XV-1}, halo).
     auto commit_x = [&](uint32_t *buf) {
         if (P4) {
             // rows 1 and 2 of the plane's window: (halo, x00) (x01, halo) (halo, x10) (x11, halo)
@@ -218,24 +231,27 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
             for (int u = 0; u < XS; ++u)
                 if (x_pack[u] >= 0) {
                     uint32_t *w = buf + x_pack[u];
-                    w[0] = xr[u].x << 16;
-                    w[1] = xr[u].x >> 16;
-                    w[2] = xr[u].y << 16;
-                    w[3] = xr[u].y >> 16;
+                    w[0] = xr[u][0] << 16;
+                    w[1] = xr[u][0] >> 16;
+                    w[2] = xr[u][1] << 16;
+                    w[3] = xr[u][1] >> 16;
                 }
             return;
         }
 #pragma unroll
         for (int u = 0; u < XS; ++u) {
             const bool ok = (x_row_ok >> u) & 1;
-            const uint32_t r0 = ok ? xr[u].x : 0u, r1 = ok ? xr[u].y : 0u;
-            uint32_t left = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)r1, 0x111, 0xf, 0xf, true);   // row_shr:1
+            uint32_t r[XV / 2];
+#pragma unroll
+            for (int i = 0; i < XV / 2; ++i) r[i] = ok ? xr[u][i] : 0u;
+            uint32_t left = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)r[XV / 2 - 1], 0x111, 0xf, 0xf, true);   // row_shr:1
             if (x_pack[u] >= 0) {
                 if ((x_pack[u] >> 28) & 1) left = 0u;
                 uint32_t *w = buf + (x_pack[u] & 0xfffff);
-                w[0] = __builtin_amdgcn_alignbit(r0, left, 16);
-                w[1] = __builtin_amdgcn_alignbit(r1, r0, 16);
-                if ((x_pack[u] >> 29) & 1) w[2] = r1 >> 16;
+                w[0] = __builtin_amdgcn_alignbit(r[0], left, 16);
+#pragma unroll
+                for (int i = 1; i < XV / 2; ++i) w[i] = __builtin_amdgcn_alignbit(r[i], r[i - 1], 16);
+                if ((x_pack[u] >> 29) & 1) w[XV / 2] = r[XV / 2 - 1] >> 16;
             }
         }
     };
