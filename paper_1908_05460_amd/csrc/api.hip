@@ -1,6 +1,6 @@
 // C ABI of libwgrad (declared in include/wgrad.h): argument validation and dispatch.
 // Everything here runs on the host; validation precedes the first launch.
-#include "common.hpp"
+#include "exact_stream_kernel.hpp"
 
 using namespace wgrad;
 
@@ -181,6 +181,30 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
     int group[4096];
     make_groups(layers, method, nlayers, group);
     CombineQueue queue;
+    MultiQueue multi;
+    int nexact = 0;
+    for (int i = 0; i < nlayers; ++i) nexact += method[i] == WGRAD_EXACT && group[i] == i;
+    MultiQueue *mq = nexact > 1 && tune_int("WGRAD_MULTI", 1) ? &multi : nullptr;
+    // workgroups of a multi-shape launch are shared out to the groups in proportion to their work
+    double exact_flops = 0;
+    auto group_flops = [&](int i) {
+        double f = 0;
+        for (int j = i; j < nlayers; ++j)
+            if (group[j] == i) {
+                Geometry gj;
+                make_geometry(&layers[j], gj);
+                double w = 2.0 * gj.N * gj.K * gj.Ho * gj.Wo * (double)gj.crs();
+                // layers that are not bound by the matrix core take longer than their FLOPs say: a handful of
+                // input channels (bound by the dY stream), strides (a window four times the tile)
+                if (gj.C < 16) w *= tune_int("WGRAD_MULTI_W_FLAT", 2);
+                if (gj.sh > 1 || gj.sw > 1) w *= tune_int("WGRAD_MULTI_W_STRIDE", 25) / 10.0;
+                f += w;
+            }
+        return f;
+    };
+    if (mq)
+        for (int i = 0; i < nlayers; ++i)
+            if (method[i] == WGRAD_EXACT && group[i] == i) exact_flops += group_flops(i);
     char *ws_next = (char *)ws;
     int rc = WGRAD_OK;
     for (int i = 0; i < nlayers && rc == WGRAD_OK; ++i) {
@@ -190,10 +214,16 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
         Batch b{};
         for (int j = i; j < nlayers; ++j)
             if (group[j] == i) { b.X[b.n] = X[j]; b.dY[b.n] = dY[j]; b.dW[b.n] = dW[j]; ++b.n; }
-        if (method[i] == WGRAD_EXACT) rc = launch_exact(g, plan_exact(g), b, ws_next, st, &queue);
+        if (method[i] == WGRAD_EXACT) {
+            int share = 0;
+            // 768 in all: three per CU, all resident at once, so a workgroup's fixed cost is paid once per CU slot
+            if (mq) share = (int)(tune_int("WGRAD_MULTI_TOTAL", 768) * group_flops(i) / exact_flops + 0.5);
+            rc = launch_exact(g, plan_exact(g), b, ws_next, st, &queue, mq, share < 8 ? 8 : share);
+        }
         else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue);
         ws_next += align_up(method_ws(g, method[i])) * b.n;
     }
+    if (rc == WGRAD_OK && mq) rc = multi_flush(multi, st);
     if (rc == WGRAD_OK) rc = combine_flush(queue, st);
     // fills, kTableMax tensors per launch
     for (int which = WGRAD_ZERO; which <= WGRAD_RANDOM && rc == WGRAD_OK; ++which) {

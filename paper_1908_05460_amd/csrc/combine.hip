@@ -1,6 +1,8 @@
 // Reduction of partial results: dW[o] = scale * sum_j partial[j][o], for a table of tensors in
 // one launch.  The split reductions of the exact kernel and the batch chunks of the approximated
 // one both end here.
+#include <algorithm>
+
 #include "common.hpp"
 
 namespace wgrad {
@@ -54,24 +56,27 @@ __global__ __launch_bounds__(kBlock) void combine_table(const CombineTable t)
 
 int combine_flush(CombineQueue &q, hipStream_t st)
 {
-    if (q.n == 0) return WGRAD_OK;
-    CombineTable t{};
-    t.n = q.n;
-    int blocks = 0;
-    for (int i = 0; i < q.n; ++i) {
-        const CombineItem &c = q.item[i];
-        // spread the partial index over lanes when there are few outputs and many partials
-        const int lg = (c.elems <= 16 * 1024 && c.nparts >= 64) ? 4 : ((c.elems <= 256 * 1024 && c.nparts >= 16) ? 2 : 0);
-        const int ob = kBlock >> lg;
-        t.item[i] = c;
-        t.pl_log[i] = (unsigned char)lg;
-        t.begin[i] = blocks;
-        blocks += (c.elems + ob - 1) / ob;
+    for (size_t first = 0; first < q.item.size(); first += kTableMax) {
+        const int n = (int)std::min<size_t>(kTableMax, q.item.size() - first);
+        CombineTable t{};
+        t.n = n;
+        int blocks = 0;
+        for (int i = 0; i < n; ++i) {
+            const CombineItem &c = q.item[first + i];
+            // spread the partial index over lanes when there are few outputs and many partials
+            const int lg = (c.elems <= 16 * 1024 && c.nparts >= 64) ? 4 : ((c.elems <= 256 * 1024 && c.nparts >= 16) ? 2 : 0);
+            const int ob = kBlock >> lg;
+            t.item[i] = c;
+            t.pl_log[i] = (unsigned char)lg;
+            t.begin[i] = blocks;
+            blocks += (c.elems + ob - 1) / ob;
+        }
+        t.begin[n] = blocks;
+        WGRAD_LAUNCH(combine_table, dim3((unsigned)blocks), dim3(kBlock), 0, st, t);
+        if (launch_status() != WGRAD_OK) { q.item.clear(); return WGRAD_LAUNCH_FAILED; }
     }
-    t.begin[q.n] = blocks;
-    q.n = 0;
-    WGRAD_LAUNCH(combine_table, dim3((unsigned)blocks), dim3(kBlock), 0, st, t);
-    return launch_status();
+    q.item.clear();
+    return WGRAD_OK;
 }
 
 int launch_combine(const float *partials, long prob_stride, int nparts, long elems, float scale,
@@ -80,13 +85,8 @@ int launch_combine(const float *partials, long prob_stride, int nparts, long ele
     CombineQueue local;
     CombineQueue &q = defer ? *defer : local;
     if (elems >= (1l << 31)) return WGRAD_UNSUPPORTED;        // a table entry counts its elements in an int
-    for (int i = 0; i < nprob; ++i) {
-        if (q.n == kTableMax) {
-            const int rc = combine_flush(q, st);
-            if (rc != WGRAD_OK) return rc;
-        }
-        q.item[q.n++] = CombineItem{partials + i * prob_stride, dW[i], nparts, (int)elems, scale};
-    }
+    for (int i = 0; i < nprob; ++i)
+        q.item.push_back(CombineItem{partials + i * prob_stride, dW[i], nparts, (int)elems, scale});
     return defer ? WGRAD_OK : combine_flush(local, st);
 }
 

@@ -4,6 +4,8 @@
 #include <stdint.h>
 #include <stdlib.h>
 
+#include <vector>
+
 #include "wgrad.h"
 
 namespace wgrad {
@@ -86,7 +88,9 @@ struct ExactPlan {
 };
 ExactPlan plan_exact(const Geometry &g, bool allow_stream = true);
 bool plan_exact_stream(const Geometry &g, ExactPlan &pl);
-int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st);
+struct MultiQueue;
+int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st,
+                        MultiQueue *mq = nullptr);
 bool plan_exact_bf16(const Geometry &g, ExactPlan &pl);
 // The A operand of the bf16 matrix-core kernel given as the sparsified gradient of the
 // approximation: per problem, every map's selected position (row << 16 | col) and sum.
@@ -99,8 +103,8 @@ int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, fl
                       const SparseA *sparse = nullptr);
 struct CombineQueue;
 int launch_exact(const Geometry &g, const ExactPlan &pl, const Batch &b, void *ws, hipStream_t st,
-                 CombineQueue *defer = nullptr);
-int choose_splits(const ExactPlan &pl, int nprob);
+                 CombineQueue *defer = nullptr, MultiQueue *mq = nullptr, int mq_blocks = 0);
+int choose_splits(const ExactPlan &pl, int nprob, int want_blocks = 0);
 size_t exact_ws_per_problem(const Geometry &g, const ExactPlan &pl);
 
 struct ApproxPlan {
@@ -125,14 +129,13 @@ struct CombineItem {
     int nparts, elems;
     float scale;
 };
-struct CombineQueue {
-    int n = 0;
-    CombineItem item[kTableMax];
+struct CombineQueue {              // grows as needed; nothing is launched before combine_flush
+    std::vector<CombineItem> item;
 };
 int combine_flush(CombineQueue &q, hipStream_t st);
 
 // dW[i][o] = scale * sum_j partials[i * prob_stride + j * elems + o] for the nprob problems of a batch;
-// with a queue the work is only recorded there (and the queue flushed when full)
+// with a queue the work is only recorded there
 int launch_combine(const float *partials, long prob_stride, int nparts, long elems, float scale,
                    float *const *dW, int nprob, hipStream_t st, CombineQueue *defer = nullptr);
 int launch_zero(float *dW, long elems, hipStream_t st);

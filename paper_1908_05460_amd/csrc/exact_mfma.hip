@@ -440,13 +440,19 @@ static int largest_divisor_at_most(int n, int limit)
 // other workgroups resident on the CU (as many as their LDS windows allow) plus a barrier's worth
 // of skew; it matters for short reductions, where an uneven split (some workgroups with one tile
 // more) or a second round of workgroups costs a large part of the whole.
-int choose_splits(const ExactPlan &pl, int nprob)
+int choose_splits(const ExactPlan &pl, int nprob, int want_blocks)
 {
     const long tiles = (long)pl.h_tiles * pl.n_groups;
     const long out_tiles = (long)pl.ktiles * pl.ctiles * nprob;
-    long base = (tune_int("WGRAD_EXACT_BLOCKS", WGRAD_EXACT_BLOCKS) + out_tiles - 1) / out_tiles;
+    long base = ((want_blocks ? want_blocks : tune_int("WGRAD_EXACT_BLOCKS", WGRAD_EXACT_BLOCKS)) + out_tiles - 1) / out_tiles;
     if (base > tiles) base = tiles;
     if (base < 1) base = 1;
+    if (want_blocks) {
+        // a share of a mixed launch: the largest even cut not above the target
+        long s = base;
+        while (s > 1 && tiles % s != 0 && (tiles + s - 1) / s == (tiles + s - 2) / (s - 1)) --s;
+        return (int)s;
+    }
     // (layers with a handful of input channels are bound by their loads, not by the matrix core)
     if (!(pl.stream || pl.mm16) || pl.nt != 9 || !tune_int("WGRAD_EXACT_MODEL", 1)) return (int)base;
 
@@ -611,7 +617,8 @@ static bool batch_aligned(const Geometry &g, const Batch &b, int xv, int dyv)
 static int launch_exact_staged(const Geometry &g, const ExactPlan &pl, const void *X, const void *dY, float *dW,
                                void *ws, hipStream_t st, CombineQueue *defer);
 
-int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void *ws, hipStream_t st, CombineQueue *defer)
+int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void *ws, hipStream_t st, CombineQueue *defer,
+                 MultiQueue *mq, int mq_blocks)
 {
     if ((plan.stream || plan.mm16) && batch_aligned(g, b, plan.xv, plan.mm16 ? 8 : 4)) {
         // one launch for the whole batch; problem i owns the i-th slice of the workspace.  The
@@ -621,10 +628,16 @@ int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void 
             const int splits = choose_splits(pl, b.n);
             if (splits < pl.splits) pl.splits = splits;
         }
+        if (mq && pl.stream && !g.bf16) {
+            // part of a multi-shape launch: its workgroups share the chip with the other groups', so fewer
+            // and longer ones do (a fixed cost per workgroup, less traffic in partial results)
+            const int splits = choose_splits(pl, b.n, mq_blocks > 0 ? mq_blocks : 256);
+            if (splits < pl.splits) pl.splits = splits;
+        }
         float *out[kMaxBatch];
         const long prob_stride = (long)pl.splits * g.dw_elems();
         for (int i = 0; i < b.n; ++i) out[i] = pl.splits > 1 ? (float *)ws + i * prob_stride : b.dW[i];
-        int rc = pl.mm16 ? launch_exact_bf16(g, pl, b, out, st) : launch_exact_stream(g, pl, b, out, st);
+        int rc = pl.mm16 ? launch_exact_bf16(g, pl, b, out, st) : launch_exact_stream(g, pl, b, out, st, mq);
         if (rc != WGRAD_OK) return rc;
         if (pl.splits > 1)
             return launch_combine((const float *)ws, prob_stride, pl.splits, g.dw_elems(), 1.0f, b.dW, b.n, st, defer);

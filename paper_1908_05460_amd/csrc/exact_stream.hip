@@ -64,10 +64,21 @@ bool plan_exact_stream(const Geometry &g, ExactPlan &pl)
     return false;
 }
 
-// Enqueues the streaming kernel (not the combine); the caller has checked pointer alignment.
-int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st)
+int launch_stream_now(const StreamLaunch &L, hipStream_t st)
 {
-    StreamParams p{};
+    if (L.wk == 1) stream_launch_w1(L.p, L.nt, L.xv, L.gpw, L.rowp_inst, L.grid, L.lds, st);
+    else if (L.wk == 2) stream_launch_w2(L.p, L.nt, L.xv, L.gpw, L.rowp_inst, L.grid, L.lds, st);
+    else stream_launch_w4(L.p, L.nt, L.xv, L.gpw, L.rowp_inst, L.grid, L.lds, st);
+    return launch_status();
+}
+
+// Enqueues the streaming kernel (not the combine); the caller has checked pointer alignment.  With a
+// queue, fp32 launches of a shape that a multi-shape launch can carry are only recorded there.
+int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st,
+                        MultiQueue *mq)
+{
+    StreamLaunch L{};
+    StreamParams &p = L.p;
     for (int i = 0; i < kMaxBatch; ++i) {          // unused slots repeat problem 0
         const int j = i < b.n ? i : 0;
         p.X[i] = b.X[j]; p.dY[i] = b.dY[j]; p.out[i] = out[j];
@@ -98,12 +109,19 @@ int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, 
             p.tile_toff[t] = (tap / g.S) * pl.rowp + tap % g.S;
             p.tile_tap[t] = tap;
         }
-    const int grid = pl.ktiles * pl.ctiles * pl.splits * b.n;
-    const int rowp_inst = stream_has_rowp(pl.rowp, pl.xv) && pl.nt == 9 && pl.tap_mode ? pl.rowp : 0;
-    if (pl.wk == 1) stream_launch_w1(p, pl.nt, pl.xv, pl.gpw, rowp_inst, grid, pl.lds_bytes, st);
-    else if (pl.wk == 2) stream_launch_w2(p, pl.nt, pl.xv, pl.gpw, rowp_inst, grid, pl.lds_bytes, st);
-    else stream_launch_w4(p, pl.nt, pl.xv, pl.gpw, rowp_inst, grid, pl.lds_bytes, st);
-    return launch_status();
+    L.grid = pl.ktiles * pl.ctiles * pl.splits * b.n;
+    L.rowp_inst = stream_has_rowp(pl.rowp, pl.xv) && pl.nt == 9 && pl.tap_mode ? pl.rowp : 0;
+    L.nt = pl.nt; L.wk = pl.wk; L.xv = pl.xv; L.gpw = pl.gpw; L.lds = pl.lds_bytes;
+    // up to three workgroups per CU must fit next to each other for a mixed launch to pay
+    if (mq && !g.bf16 && L.lds <= 52 * 1024 && multi_variant(L.nt, L.wk, L.xv, L.gpw, L.rowp_inst) >= 0) {
+        if (mq->n == kMultiMax) {
+            const int rc = multi_flush(*mq, st);
+            if (rc != WGRAD_OK) return rc;
+        }
+        mq->item[mq->n++] = L;
+        return WGRAD_OK;
+    }
+    return launch_stream_now(L, st);
 }
 
 }  // namespace wgrad

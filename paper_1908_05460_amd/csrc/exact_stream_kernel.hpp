@@ -112,8 +112,10 @@ __device__ __forceinline__ void stream_column_of(const StreamParams &p, int colt
 // the nine taps of a step are then one per-lane address plus nine immediate offsets, and the
 // loop has one VALU instruction per nine MFMAs instead of nine (the adds, not LDS or the matrix
 // core, bound the loop otherwise).  ROWP = 0: run-time pitch and tap offsets (any filter).
+// The body takes the workgroup's number `bid` among the `nblk` workgroups of its launch (or of its
+// share of a launch that carries several shapes) and the dynamic LDS.
 template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP>
-__global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams p)
+__device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, int bid, int nblk)
 {
     static_assert(ROWP == 0 || NT == 9, "immediate tap offsets are for 3x3 filters in tap mode");
     const int rowp = ROWP ? ROWP : p.rowp;
@@ -122,7 +124,6 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams 
     constexpr int NCB = NT * 16;
     constexpr int QT = 16 * GPW * WQ;                   // positions per tile, padded
     constexpr int XS = stream_xslots(WK, GPW);
-    extern __shared__ float smem[];
     float *Xs0 = smem;                                  // [2][xbuf]
     int *xoff = (int *)(smem + 2 * p.xbuf);             // [QT] byte offsets
 
@@ -134,7 +135,7 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams 
     const int L = g.Ho * g.Wo;
 
     // a launch may carry several problems of identical shape (layers of a schedule run)
-    const int logical_all = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    const int logical_all = xcd_contiguous_id(bid, nblk);
     const int prob = logical_all / p.per_prob;
     const int logical = logical_all - prob * p.per_prob;
     const char *const Xp = (const char *)p.X[prob];
@@ -397,6 +398,28 @@ __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams 
     TRACE(10);
     TRACE_BLK(1);
 }
+
+template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP>
+__global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams p)
+{
+    extern __shared__ float smem[];
+    stream_body<NT, WK, BF16, XV, GPW, ROWP>(p, smem, blockIdx.x, gridDim.x);
+}
+
+// A prepared launch of the streaming kernel, and a queue of them for a multi-shape launch.
+constexpr int kMultiMax = 6;        // groups per multi-shape launch (their parameters are kernel arguments)
+struct StreamLaunch {
+    StreamParams p;
+    int nt, wk, xv, gpw, rowp_inst, grid;
+    size_t lds;
+};
+struct MultiQueue {
+    int n = 0;
+    StreamLaunch item[kMultiMax];
+};
+int multi_variant(int nt, int wk, int xv, int gpw, int rowp);     // -1: not among the shapes a multi launch mixes
+int launch_stream_now(const StreamLaunch &L, hipStream_t st);
+int multi_flush(MultiQueue &q, hipStream_t st);
 
 // Per-K-tile-width launchers, each instantiated in its own translation unit.
 void stream_launch_w1(const StreamParams &p, int nt, int xv, int gpw, int rowp, int grid, size_t lds, hipStream_t st);
