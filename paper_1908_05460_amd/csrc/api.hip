@@ -205,6 +205,9 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
     if (mq)
         for (int i = 0; i < nlayers; ++i)
             if (method[i] == WGRAD_EXACT && group[i] == i) exact_flops += group_flops(i);
+    int napprox = 0;
+    for (int i = 0; i < nlayers; ++i) napprox += method[i] == WGRAD_APPROX && group[i] == i;
+    FusedQueue *fq = napprox > 1 && tune_int("WGRAD_FUSED_MULTI", 1) ? fused_queue_new() : nullptr;
     char *ws_next = (char *)ws;
     int rc = WGRAD_OK;
     for (int i = 0; i < nlayers && rc == WGRAD_OK; ++i) {
@@ -220,10 +223,14 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
             if (mq) share = (int)(tune_int("WGRAD_MULTI_TOTAL", 768) * group_flops(i) / exact_flops + 0.5);
             rc = launch_exact(g, plan_exact(g), b, ws_next, st, &queue, mq, share < 8 ? 8 : share);
         }
-        else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue);
+        else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue, fq);
         ws_next += align_up(method_ws(g, method[i])) * b.n;
     }
     if (rc == WGRAD_OK && mq) rc = multi_flush(multi, st);
+    if (fq) {
+        if (rc == WGRAD_OK) rc = fused_flush(*fq, st);
+        fused_queue_delete(fq);
+    }
     if (rc == WGRAD_OK) rc = combine_flush(queue, st);
     // fills, kTableMax tensors per launch
     for (int which = WGRAD_ZERO; which <= WGRAD_RANDOM && rc == WGRAD_OK; ++which) {

@@ -355,20 +355,20 @@ struct FusedParams {
     float *sum_out;
 };
 
+// linear: the workgroup's number among the nk * nchunks * nprob of its group
 template <bool BF16>
-__global__ __launch_bounds__(kBlock) void approx_fused(ApproxBatch ab, Geometry g, FusedParams fp)
+__device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry &g, const FusedParams &fp,
+                                           float (&red)[4][kFusedJ * 64], int linear, int nk, int nchunks, int nprob)
 {
     typedef typename Raw4<BF16>::type raw4;
     constexpr int ESZ = BF16 ? 2 : 4;
-    __shared__ float red[4][kFusedJ * 64];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // The K workgroups of one (problem, batch chunk) read the same input planes: number the workgroups so
     // that they sit on one XCD and find each other's planes in its L2.
-    const int linear = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-    const int logical = xcd_contiguous_id(linear, gridDim.x * gridDim.y * gridDim.z);
-    const int k = logical % (int)gridDim.x;
-    const int by = (logical / (int)gridDim.x) % (int)gridDim.y, bz = logical / (int)(gridDim.x * gridDim.y);
+    const int logical = xcd_contiguous_id(linear, nk * nchunks * nprob);
+    const int k = logical % nk;
+    const int by = (logical / nk) % nchunks, bz = logical / (nk * nchunks);
     const char *__restrict__ X = (const char *)ab.X[bz];
     const char *__restrict__ dY = (const char *)ab.dY[bz];
     float *__restrict__ out = ab.out[bz];
@@ -474,6 +474,70 @@ __global__ __launch_bounds__(kBlock) void approx_fused(ApproxBatch ab, Geometry 
     for (int j = tid; j < CRS; j += kBlock) o[j] = (red[0][j] + red[1][j] + red[2][j] + red[3][j]) * fp.scale;
 }
 
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void approx_fused(ApproxBatch ab, Geometry g, FusedParams fp)
+{
+    __shared__ float red[4][kFusedJ * 64];
+    const int linear = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    fused_body<BF16>(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z);
+}
+
+// Several groups of layers (each group one geometry) in one launch: a workgroup looks its group up.
+// The parameters are read through the kernel-argument segment pointer (indexing the by-value argument
+// with a run-time group number would make the compiler copy all of it into scratch memory first).
+constexpr int kFusedMultiMax = 6;
+struct FusedGroup {
+    ApproxBatch ab;
+    Geometry g;
+    FusedParams fp;
+    int nchunks, nprob;
+};
+struct FusedMulti {
+    int n;
+    int begin[kFusedMultiMax + 1];   // first workgroup of each group, multiples of 8; begin[n] = grid size
+    int count[kFusedMultiMax];
+    FusedGroup grp[kFusedMultiMax];
+};
+
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void approx_fused_multi(const FusedMulti)
+{
+    __shared__ float red[4][kFusedJ * 64];
+    const FusedMulti *mp = (const FusedMulti *)__builtin_amdgcn_kernarg_segment_ptr();
+    const int n = mp->n;
+    int gi = 0;
+    for (int i = 1; i < n; ++i) gi += (int)blockIdx.x >= mp->begin[i];
+    const int linear = (int)blockIdx.x - mp->begin[gi];
+    if (linear >= mp->count[gi]) return;
+    const FusedGroup &G = mp->grp[gi];
+    fused_body<BF16>(G.ab, G.g, G.fp, red, linear, G.g.K, G.nchunks, G.nprob);
+}
+
+struct FusedQueue {
+    int n = 0, bf16 = 0;
+    FusedGroup grp[kFusedMultiMax];
+};
+
+int fused_flush(FusedQueue &q, hipStream_t st)
+{
+    if (q.n == 0) return WGRAD_OK;
+    FusedMulti m{};
+    m.n = q.n;
+    int blocks = 0;
+    for (int i = 0; i < q.n; ++i) {
+        m.grp[i] = q.grp[i];
+        m.begin[i] = blocks;
+        m.count[i] = q.grp[i].g.K * q.grp[i].nchunks * q.grp[i].nprob;
+        blocks += (m.count[i] + 7) / 8 * 8;
+    }
+    m.begin[q.n] = blocks;
+    const bool bf16 = q.bf16;
+    q.n = 0;
+    if (bf16) WGRAD_LAUNCH((approx_fused_multi<true>), dim3((unsigned)blocks), dim3(kBlock), 0, st, m);
+    else      WGRAD_LAUNCH((approx_fused_multi<false>), dim3((unsigned)blocks), dim3(kBlock), 0, st, m);
+    return launch_status();
+}
+
 #ifndef WGRAD_APPROX_THREADS   // threads to aim for when chunking the batch (direct form)
 #define WGRAD_APPROX_THREADS (256 * 1024)
 #endif
@@ -574,7 +638,7 @@ static void launch_gather_lds(const ApproxPlan &pl, dim3 grid, size_t lds, hipSt
 }
 
 int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, float scale,
-                  int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer)
+                  int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer, FusedQueue *fq)
 {
     bool aligned = true;
     for (int i = 0; i < b.n; ++i)
@@ -629,11 +693,22 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         fp.chunk_n = pl.chunk_n; fp.scale = kscale;
         fp.d_rs = FastDiv(g.R * g.S); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
         fp.flat_out = idx_out; fp.sum_out = sum_out;
-        const dim3 grid((unsigned)g.K, (unsigned)pl.chunks, (unsigned)b.n);
-        if (g.bf16) WGRAD_LAUNCH((approx_fused<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
-        else        WGRAD_LAUNCH((approx_fused<false>), grid, dim3(kBlock), 0, st, ab, g, fp);
-        rc = launch_status();
-        if (rc != WGRAD_OK) return rc;
+        if (fq) {
+            // part of a multi-group launch (groups of one element type)
+            if (fq->n == kFusedMultiMax || (fq->n > 0 && fq->bf16 != g.bf16)) {
+                rc = fused_flush(*fq, st);
+                if (rc != WGRAD_OK) return rc;
+            }
+            FusedGroup &G = fq->grp[fq->n++];
+            fq->bf16 = g.bf16;
+            G.ab = ab; G.g = g; G.fp = fp; G.nchunks = pl.chunks; G.nprob = b.n;
+        } else {
+            const dim3 grid((unsigned)g.K, (unsigned)pl.chunks, (unsigned)b.n);
+            if (g.bf16) WGRAD_LAUNCH((approx_fused<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
+            else        WGRAD_LAUNCH((approx_fused<false>), grid, dim3(kBlock), 0, st, ab, g, fp);
+            rc = launch_status();
+            if (rc != WGRAD_OK) return rc;
+        }
         if (pl.chunks > 1)
             return launch_combine((const float *)((char *)ws + pl.off_part), (long)(plan.ws_bytes / 4), pl.chunks, outs,
                                   scale, b.dW, b.n, st, defer);
@@ -659,5 +734,8 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
                               scale, b.dW, b.n, st, defer);
     return WGRAD_OK;
 }
+
+FusedQueue *fused_queue_new() { return new FusedQueue; }
+void fused_queue_delete(FusedQueue *q) { delete q; }
 
 }  // namespace wgrad

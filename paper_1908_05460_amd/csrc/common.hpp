@@ -115,9 +115,15 @@ struct ApproxPlan {
     size_t off_idx, off_sum, off_part, ws_bytes;
 };
 ApproxPlan plan_approx(const Geometry &g, bool allow_lds = true, bool allow_fused = true, bool allow_mm = true);
+struct FusedQueue;
 int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, hipStream_t st);
 int launch_approx(const Geometry &g, const ApproxPlan &pl, const Batch &b, float scale,
-                  int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer = nullptr);
+                  int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer = nullptr,
+                  FusedQueue *fq = nullptr);
+// groups of layers that the fused approximation kernel takes, collected for one launch
+FusedQueue *fused_queue_new();
+void fused_queue_delete(FusedQueue *q);
+int fused_flush(FusedQueue &q, hipStream_t st);
 
 // Reductions of partial results that a run of several layers postpones: every producer writes
 // its partials into a workspace region of its own, and one table-driven launch at the end
