@@ -104,9 +104,9 @@ size_t conv_wgrad_workspace_bytes(const wgrad_conv_desc *desc, wgrad_method meth
  * the dW tensors must not overlap one another.  All layers are enqueued on
  * `stream` without any host synchronisation, in this order: exact and
  * approximated layers, where those that share one descriptor (up to 8) are
- * folded into a single launch; one reduction of all their partial results;
- * one launch for the zero layers and one for the random layers (32 tensors per
- * launch).  Every layer works in its own slice of `ws`, which must hold
+ * folded into one group and up to six groups into a single launch; one
+ * reduction of all their partial results; one launch for the zero layers and
+ * one for the random layers (32 tensors per launch).  Every layer works in its own slice of `ws`, which must hold
  * conv_wgrad_schedule_workspace_bytes(layers, method, nlayers): the sum over
  * the layers, not their maximum.  The results are those of the individual
  * calls.  A random layer i uses offset + (sum of K*C*R*S of the layers before
