@@ -8,7 +8,9 @@ conv_wgrad_schedule_run on torch's current stream.  Inputs are resident in HBM
 before the timed region; distinct input sets are rotated so that a step does not
 find its operands in the 256 MB last-level cache.
 
-Prints one JSON line (see the design doc for the fields).
+Prints one JSON line: metric/value (ms per step), phase_ms per method, `roofline` (exact phase against the
+matrix-core peak, with measured HBM traffic), `roofline_approx` (approximation phase against HBM bandwidth),
+`cpu_baseline` (the fp64 oracle on the host cores), `per_layer` (single-layer calls).
 """
 import argparse
 import json
