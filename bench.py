@@ -49,8 +49,9 @@ def main():
     ap.add_argument("--phases", default="exact,approx,zero,random",
                     help="phases a step enqueues; anything but the default is for counter runs that must "
                          "attribute every dispatch to one phase, and the printed line then says so")
-    ap.add_argument("--sweep-batches", type=int, default=100,
-                    help="distinct resident mini-batches of the schedule sweep (workload resnet20_schedule_sweep)")
+    ap.add_argument("--sweep-batches", type=int, default=0,
+                    help="distinct resident mini-batches of a schedule sweep (workloads *_schedule_sweep); "
+                         "0 = 100 for ResNet-20, 24 for VGG-19")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="run a plain 256 MiB device copy 10 times and exit (reference for HBM byte counters)")
     args = ap.parse_args()
@@ -78,7 +79,9 @@ def main():
     stack = stack_fn()
     e = 2 if dtype == "bf16" else 4
     nl = len(stack)
-    if args.workload == "resnet20_schedule_sweep":
+    if args.workload.endswith("_schedule_sweep"):
+        if args.sweep_batches <= 0:
+            args.sweep_batches = 100 if args.workload.startswith("resnet20") else 24
         run_sweep(args, B, inputs, sch, torch, np, cfg, stack, N, dtype)
         return
     set_bytes = sum(exact_min_bytes(l, N, e) for l in stack)

@@ -86,6 +86,7 @@ WORKLOADS = {
     "vgg19_n128_fp32": (3, vgg19_stack, 128, "fp32"),
     "vgg19_n512_bf16": (4, vgg19_stack, 512, "bf16"),
     "resnet20_schedule_sweep": (5, resnet20_stack, 128, "fp32"),
+    "vgg19_schedule_sweep": (6, vgg19_stack, 128, "fp32"),      # the same sweep on the other stack the paper trains
 }
 
 
