@@ -55,6 +55,10 @@ def lib():
         L.oracle_wgrad_approx.argtypes = [P(Shape), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int,
                                           ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p,
                                           ctypes.c_void_p]
+        L.oracle_select_topk.argtypes = [P(Shape), ctypes.c_void_p, ctypes.c_int, ctypes.c_int, ctypes.c_void_p,
+                                         ctypes.c_void_p]
+        L.oracle_wgrad_approx_topk.argtypes = [P(Shape), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.oracle_philox4x32_10.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.oracle_philox4x32_10.restype = None
         L.oracle_random_normal.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int64,
@@ -135,6 +139,31 @@ def wgrad_approx(g, X, dY, scale=1.0):
     rc = lib().oracle_wgrad_approx(ctypes.byref(g), X.ctypes.data, dY.ctypes.data, dt, float(scale),
                                    dW.ctypes.data, idx.ctypes.data, S.ctypes.data)
     assert rc == 0
+    return dW, idx, S
+
+
+def select_topk(g, dY, k):
+    """Returns (idx [N,K,k], S [N,K]): the k largest-magnitude positions of every map, in order."""
+    dY, dt = _prep(dY)
+    Ho, Wo = out_hw(g)
+    assert dY.shape == (g.N, g.K, Ho, Wo)
+    idx = np.empty((g.N, g.K, k), np.int32)
+    S = np.empty((g.N, g.K), np.float64)
+    rc = lib().oracle_select_topk(ctypes.byref(g), dY.ctypes.data, dt, int(k), idx.ctypes.data, S.ctypes.data)
+    assert rc == 0, rc
+    return idx, S
+
+
+def wgrad_approx_topk(g, X, dY, k, scale=1.0):
+    """Returns (dW, idx [N,K,k], S)."""
+    X, dY, dt = _pair(X, dY)
+    _check(g, X, dY)
+    dW = np.empty((g.K, g.C, g.R, g.S), np.float64)
+    idx = np.empty((g.N, g.K, k), np.int32)
+    S = np.empty((g.N, g.K), np.float64)
+    rc = lib().oracle_wgrad_approx_topk(ctypes.byref(g), X.ctypes.data, dY.ctypes.data, dt, int(k), float(scale),
+                                        dW.ctypes.data, idx.ctypes.data, S.ctypes.data)
+    assert rc == 0, rc
     return dW, idx, S
 
 

@@ -213,6 +213,83 @@ int oracle_wgrad_approx(const oracle_shape *g, const void *X_, const void *dY_, 
 }
 
 /* ---------------------------------------------------------------------------
+ * Top-k generalisation (Section 2.3 names it in one sentence -- keep the k
+ * largest-magnitude values of a map "with an adjustment of the scaling
+ * parameter" -- and leaves the adjustment open).  Reading used by this build:
+ * the k retained positions of a map each carry sum/k, so that k = 1 is
+ * Algorithm 1 and the total weight of a map stays its sum.  Positions are taken
+ * in order of decreasing magnitude, equal magnitudes by increasing flat index;
+ * k is clamped to the map length.
+ * idx[(n*K + k_out)*k + j] = j-th retained position, S[n*K + k_out] = map sum.
+ * ------------------------------------------------------------------------- */
+static void select_map_topk(const double *map, int len, int k, int32_t *where, double *sum)
+{
+    double s = 0.0;
+    for (int p = 0; p < len; ++p) s += map[p];
+    *sum = s;
+    /* k passes, each a first-maximum scan over the positions not taken yet */
+    for (int j = 0; j < k; ++j) {
+        double best = -1.0;
+        int at = 0;
+        for (int p = 0; p < len; ++p) {
+            int taken = 0;
+            for (int i = 0; i < j; ++i) taken |= where[i] == p;
+            if (taken) continue;
+            const double a = fabs(map[p]);
+            if (a > best) { best = a; at = p; }
+        }
+        where[j] = at;
+    }
+}
+
+int oracle_select_topk(const oracle_shape *g, const void *dY_, int dtype, int k, int32_t *idx, double *S)
+{
+    const int Ho = out_h(g), Wo = out_w(g), len = Ho * Wo;
+    if (k < 1 || k > len) return -2;
+    double *dY = to_double(dY_, dtype, (size_t)g->N * g->K * len);
+    if (!dY) return -1;
+    const long maps = (long)g->N * g->K;
+#pragma omp parallel for schedule(static)
+    for (long m = 0; m < maps; ++m) select_map_topk(dY + (size_t)m * len, len, k, idx + (size_t)m * k, &S[m]);
+    free(dY);
+    return 0;
+}
+
+int oracle_wgrad_approx_topk(const oracle_shape *g, const void *X_, const void *dY_, int dtype, int k,
+                             double scale, double *dW, int32_t *idx_out, double *S_out)
+{
+    const int Ho = out_h(g), Wo = out_w(g), len = Ho * Wo;
+    if (k < 1 || k > len || k > 64) return -2;
+    double *X = to_double(X_, dtype, (size_t)g->N * g->C * g->H * g->W);
+    double *dY = to_double(dY_, dtype, (size_t)g->N * g->K * len);
+    if (!X || !dY) { free(X); free(dY); return -1; }
+    const size_t per_k = (size_t)g->C * g->R * g->S;
+    for (size_t o = 0; o < per_k * g->K; ++o) dW[o] = 0.0;
+#pragma omp parallel for schedule(static)
+    for (int ko = 0; ko < g->K; ++ko) {
+        for (int n = 0; n < g->N; ++n) {
+            int32_t where[64]; double sum;
+            select_map_topk(dY + ((size_t)n * g->K + ko) * len, len, k, where, &sum);
+            if (S_out) S_out[(size_t)n * g->K + ko] = sum;
+            const double share = sum / k;
+            for (int j = 0; j < k; ++j) {
+                if (idx_out) idx_out[((size_t)n * g->K + ko) * k + j] = where[j];
+                const int row = where[j] / Wo, col = where[j] % Wo;
+                for (int c = 0; c < g->C; ++c)
+                    for (int r = 0; r < g->R; ++r)
+                        for (int s = 0; s < g->S; ++s)
+                            dW[ko * per_k + ((size_t)c * g->R + r) * g->S + s] +=
+                                x_at(X, g, n, c, row * g->stride_h + r - g->pad_h,
+                                     col * g->stride_w + s - g->pad_w) * share;
+            }
+        }
+        for (size_t o = 0; o < per_k; ++o) dW[ko * per_k + o] *= scale;
+    }
+    free(X); free(dY);
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------
  * Random gradient (Section 2.2): independent N(0, sigma) values, new for every
  * batch.  The paper drew them on the host with a library generator; what the
  * method fixes is the distribution only.  This build defines the stream as a
