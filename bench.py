@@ -46,6 +46,7 @@ def main():
     ap.add_argument("--layer-reps", type=int, default=20, help="back-to-back launches per layer in the per-layer pass")
     ap.add_argument("--cpu-budget-s", type=float, default=20.0, help="CPU seconds to spend on the oracle baseline (0 = skip)")
     ap.add_argument("--scale", type=float, default=1.0 / 128)
+    ap.add_argument("--topk", type=int, default=4, help="k of the top-k column of the per-layer pass (0 = skip)")
     ap.add_argument("--phases", default="exact,approx,zero,random",
                     help="phases a step enqueues; anything but the default is for counter runs that must "
                          "attribute every dispatch to one phase, and the printed line then says so")
@@ -169,6 +170,12 @@ def main():
                                                        dW=sets[r % copies]._keep[2][i], ws=ws_l))
         t_ap = time_layer(lambda r: B.conv_wgrad_approx(d, sets[r % copies]._keep[0][i], sets[r % copies]._keep[1][i],
                                                         scale=args.scale, dW=sets[r % copies]._keep[2][i], ws=ws_l))
+        topk = min(args.topk, d.Ho * d.Wo)
+        t_tk = None
+        if topk > 0:
+            ws_k = B.alloc_workspace(B.topk_workspace_bytes(d, topk))
+            t_tk = time_layer(lambda r: B.conv_wgrad_approx_topk(d, sets[r % copies]._keep[0][i], sets[r % copies]._keep[1][i],
+                                                                 topk, scale=args.scale, dW=sets[r % copies]._keep[2][i], ws=ws_k))
         fl, ab = l.flops(N), approx_algorithmic_bytes(l, N, e)
         per_layer.append({"layer": l.name, "shape": f"{l.C}->{l.K}@{l.H}s{l.stride}",
                           "exact_us": round(t_ex, 2), "approx_us": round(t_ap, 2),
@@ -176,7 +183,8 @@ def main():
                           "exact_frac_mfma": round(fl / t_ex / 1e6 / MFMA_PEAK_TFLOPS[dtype], 4),
                           "approx_gbs": round(ab / t_ap / 1e3, 1),
                           "approx_frac_hbm": round(ab / t_ap / 1e3 / HBM_PEAK_GBS, 4),
-                          "speedup": round(t_ex / t_ap, 2)})
+                          "speedup": round(t_ex / t_ap, 2),
+                          "topk": topk, "topk_us": round(t_tk, 2) if t_tk else None})
         tot["exact_us"] += t_ex; tot["approx_us"] += t_ap; tot["flops"] += fl; tot["approx_bytes"] += ab
 
     # Roofline of the dominant kernel, in the launch configuration timed above: the exact phase

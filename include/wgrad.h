@@ -81,6 +81,24 @@ int conv_wgrad_approx(const wgrad_conv_desc *desc, const void *X, const void *dY
 int conv_wgrad_select(const wgrad_conv_desc *desc, const void *dY, int32_t *idx, float *sum,
                       void *stream);
 
+/* Top-k form of the approximation (Section 2.3 names keeping more than the
+ * maximum as the natural refinement; it fixes no weighting, this library's is
+ * stated here).  Every map dY[n,k,:,:] keeps its topk positions of largest
+ * magnitude, ranked by magnitude descending and by flat index ascending among
+ * equal magnitudes; each kept position carries S/topk, S the map's signed sum:
+ *   dW[k,c,r,s] = scale * sum_n (S[n,k]/topk) * sum_{j<topk} X[n,c,h_j*stride_h + r - pad_h, w_j*stride_w + s - pad_w]
+ * topk = 1 is conv_wgrad_approx.  1 <= topk <= min(64, Ho*Wo), otherwise
+ * WGRAD_UNSUPPORTED and nothing is launched.
+ * idx_out: optional, N*K*topk elements, idx_out[(n*K + k)*topk + j] = the flat
+ * position of rank j; sum_out: optional, N*K elements.
+ * ws: at least conv_wgrad_topk_workspace_bytes(desc, topk), 256-byte aligned. */
+int conv_wgrad_approx_topk(const wgrad_conv_desc *desc, const void *X, const void *dY, float *dW,
+                           int topk, float scale, int32_t *idx_out, float *sum_out,
+                           void *ws, size_t ws_bytes, void *stream);
+
+/* Scratch bytes conv_wgrad_approx_topk needs; 0 for an invalid descriptor or topk. */
+size_t conv_wgrad_topk_workspace_bytes(const wgrad_conv_desc *desc, int topk);
+
 /* Zero gradient (Section 2.1): dW = 0. */
 int conv_wgrad_zero(const wgrad_conv_desc *desc, float *dW, void *stream);
 

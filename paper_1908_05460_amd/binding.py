@@ -18,7 +18,8 @@ OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, LAUNCH_FAILED = 0, -1, -2, -3
 
 EXPORTS = ("conv_wgrad_exact", "conv_wgrad_approx", "conv_wgrad_select", "conv_wgrad_zero",
            "conv_wgrad_random", "conv_wgrad_workspace_bytes", "conv_wgrad_schedule_run",
-           "conv_wgrad_schedule_workspace_bytes", "conv_wgrad_status_string")
+           "conv_wgrad_schedule_workspace_bytes", "conv_wgrad_status_string",
+           "conv_wgrad_approx_topk", "conv_wgrad_topk_workspace_bytes")
 
 
 class ConvDesc(ctypes.Structure):
@@ -72,6 +73,10 @@ def load():
     L.conv_wgrad_exact.argtypes = [P(ConvDesc), vp, vp, fp, vp, ctypes.c_size_t, vp]
     L.conv_wgrad_approx.argtypes = [P(ConvDesc), vp, vp, fp, ctypes.c_float, i32p, fp, vp,
                                     ctypes.c_size_t, vp]
+    L.conv_wgrad_approx_topk.argtypes = [P(ConvDesc), vp, vp, fp, ctypes.c_int, ctypes.c_float, i32p, fp, vp,
+                                         ctypes.c_size_t, vp]
+    L.conv_wgrad_topk_workspace_bytes.argtypes = [P(ConvDesc), ctypes.c_int]
+    L.conv_wgrad_topk_workspace_bytes.restype = ctypes.c_size_t
     L.conv_wgrad_select.argtypes = [P(ConvDesc), vp, i32p, fp, vp]
     L.conv_wgrad_zero.argtypes = [P(ConvDesc), fp, vp]
     L.conv_wgrad_random.argtypes = [P(ConvDesc), fp, ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64, vp]
@@ -85,7 +90,7 @@ def load():
     L.conv_wgrad_status_string.argtypes = [ctypes.c_int]
     L.conv_wgrad_status_string.restype = ctypes.c_char_p
     for f in ("conv_wgrad_exact", "conv_wgrad_approx", "conv_wgrad_select", "conv_wgrad_zero",
-              "conv_wgrad_random", "conv_wgrad_schedule_run"):
+              "conv_wgrad_random", "conv_wgrad_schedule_run", "conv_wgrad_approx_topk"):
         getattr(L, f).restype = ctypes.c_int
     _lib = L
     return L
@@ -175,6 +180,23 @@ def conv_wgrad_approx(d, X, dY, scale=1.0, dW=None, idx_out=None, sum_out=None, 
                                   _ptr(idx_out), _ptr(sum_out), p, n, _stream())
     if rc != OK:
         raise WgradError(rc, "conv_wgrad_approx")
+    return dW
+
+
+def topk_workspace_bytes(d, k):
+    return load().conv_wgrad_topk_workspace_bytes(ctypes.byref(d), int(k))
+
+
+def conv_wgrad_approx_topk(d, X, dY, k, scale=1.0, dW=None, idx_out=None, sum_out=None, ws=None):
+    _check_inputs(d, X, dY)
+    dW = _new_dW(d, X) if dW is None else dW
+    if ws is None:
+        ws = alloc_workspace(topk_workspace_bytes(d, k), X.device)
+    p, n = _ws_args(ws)
+    rc = load().conv_wgrad_approx_topk(ctypes.byref(d), _ptr(X), _ptr(dY), _ptr(dW), int(k), float(scale),
+                                       _ptr(idx_out), _ptr(sum_out), p, n, _stream())
+    if rc != OK:
+        raise WgradError(rc, "conv_wgrad_approx_topk")
     return dW
 
 

@@ -63,6 +63,26 @@ int conv_wgrad_approx(const wgrad_conv_desc *desc, const void *X, const void *dY
     return launch_approx(g, pl, b, scale, idx_out, sum_out, ws, (hipStream_t)stream);
 }
 
+int conv_wgrad_approx_topk(const wgrad_conv_desc *desc, const void *X, const void *dY, float *dW,
+                           int topk, float scale, int32_t *idx_out, float *sum_out,
+                           void *ws, size_t ws_bytes, void *stream)
+{
+    Geometry g;
+    int rc = make_geometry(desc, g);
+    if (rc != WGRAD_OK) return rc;
+    if (!X || !dY || !dW) return WGRAD_INVALID_ARG;
+    if (!topk_supported(g, topk)) return WGRAD_UNSUPPORTED;
+    if (!ws_ok(ws, ws_bytes, topk_ws_bytes(g, topk))) return WGRAD_WORKSPACE_TOO_SMALL;
+    return launch_approx_topk(g, X, dY, dW, topk, scale, idx_out, sum_out, ws, (hipStream_t)stream);
+}
+
+size_t conv_wgrad_topk_workspace_bytes(const wgrad_conv_desc *desc, int topk)
+{
+    Geometry g;
+    if (make_geometry(desc, g) != WGRAD_OK || !topk_supported(g, topk)) return 0;
+    return topk_ws_bytes(g, topk);
+}
+
 int conv_wgrad_select(const wgrad_conv_desc *desc, const void *dY, int32_t *idx, float *sum, void *stream)
 {
     Geometry g;

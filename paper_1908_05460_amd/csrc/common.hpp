@@ -125,6 +125,13 @@ FusedQueue *fused_queue_new();
 void fused_queue_delete(FusedQueue *q);
 int fused_flush(FusedQueue &q, hipStream_t st);
 
+// top-k form of the approximation (k kept positions per map, each carrying sum/k)
+constexpr int kTopKMax = 64;
+bool topk_supported(const Geometry &g, int k);
+size_t topk_ws_bytes(const Geometry &g, int k);
+int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *dW, int k, float scale,
+                       int32_t *idx_out, float *sum_out, void *ws, hipStream_t st);
+
 // Reductions of partial results that a run of several layers postpones: every producer writes
 // its partials into a workspace region of its own, and one table-driven launch at the end
 // reduces all of them (a launch per layer group costs more than the reduction itself).

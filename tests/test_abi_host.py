@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert set(names) == set(B.EXPORTS) and len(names) == 9
+    assert set(names) == set(B.EXPORTS) and len(names) == 11
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -70,6 +70,23 @@ def test_workspace_is_checked(lib):
         assert call(None, need) == B.WORKSPACE_TOO_SMALL
         assert call(ctypes.c_void_p(0x1010), need) == B.WORKSPACE_TOO_SMALL      # misaligned
     assert B.workspace_bytes(d, B.ZERO) == 0 and B.workspace_bytes(d, B.RANDOM) == 0
+
+
+def test_topk_limits_and_workspace_are_checked_on_the_host(lib):
+    d = B.desc(16, 16, 32, 32, 16)
+    f = lib.conv_wgrad_approx_topk
+    for k in (0, -3, 65, 32 * 32 + 1):
+        assert B.topk_workspace_bytes(d, k) == 0
+        assert f(ctypes.byref(d), FAKE, FAKE, FAKE, k, 1.0, None, None, FAKE, 1 << 30, None) == B.UNSUPPORTED
+    tiny = B.desc(4, 8, 2, 2, 8)
+    assert B.topk_workspace_bytes(tiny, 4) > 0 and B.topk_workspace_bytes(tiny, 5) == 0
+    need = B.topk_workspace_bytes(d, 8)
+    assert need >= 16 * 16 * 8 * 4 and need % 256 == 0
+    assert f(ctypes.byref(d), FAKE, FAKE, FAKE, 8, 1.0, None, None, FAKE, need - 1, None) == B.WORKSPACE_TOO_SMALL
+    assert f(ctypes.byref(d), FAKE, FAKE, FAKE, 8, 1.0, None, None, None, need, None) == B.WORKSPACE_TOO_SMALL
+    assert f(ctypes.byref(d), None, FAKE, FAKE, 8, 1.0, None, None, FAKE, need, None) == B.INVALID_ARG
+    bad = B.desc(16, 16, 32, 32, 0)
+    assert f(ctypes.byref(bad), FAKE, FAKE, FAKE, 1, 1.0, None, None, FAKE, need, None) == B.INVALID_ARG
 
 
 def test_schedule_validates_all_layers_first(lib):
