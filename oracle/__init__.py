@@ -59,6 +59,10 @@ def lib():
                                          ctypes.c_void_p]
         L.oracle_wgrad_approx_topk.argtypes = [P(Shape), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
                                                ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
+        L.oracle_wgrad_exact_nhwc.argtypes = [P(Shape), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
+                                              ctypes.c_void_p]
+        L.oracle_wgrad_approx_nhwc.argtypes = [P(Shape), ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_double, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.oracle_philox4x32_10.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p]
         L.oracle_philox4x32_10.restype = None
         L.oracle_random_normal.argtypes = [ctypes.c_uint64, ctypes.c_uint64, ctypes.c_int64,
@@ -165,6 +169,61 @@ def wgrad_approx_topk(g, X, dY, k, scale=1.0):
                                         dW.ctypes.data, idx.ctypes.data, S.ctypes.data)
     assert rc == 0, rc
     return dW, idx, S
+
+
+# ---- the layouts of the paper's own kernel (Section 2.4): X channel-last, dY unchanged, dW as OHWI or HWIO ----
+OIHW, OHWI, HWIO = 0, 1, 2
+
+
+def dw_shape(g, layout):
+    return {OIHW: (g.K, g.C, g.R, g.S), OHWI: (g.K, g.R, g.S, g.C), HWIO: (g.R, g.S, g.C, g.K)}[layout]
+
+
+def _check_nhwc(g, X, dY):
+    Ho, Wo = out_hw(g)
+    assert X.shape == (g.N, g.H, g.W, g.C), (X.shape, (g.N, g.H, g.W, g.C))
+    assert dY.shape == (g.N, g.K, Ho, Wo), (dY.shape, (g.N, g.K, Ho, Wo))
+
+
+def wgrad_exact_nhwc(g, X, dY, dw_layout=OHWI):
+    """Exact filter gradient from X[n,h,w,c] and dY[n,k,h,w], in the given dW layout."""
+    X, dY, dt = _pair(X, dY)
+    _check_nhwc(g, X, dY)
+    dW = np.empty(dw_shape(g, dw_layout), np.float64)
+    rc = lib().oracle_wgrad_exact_nhwc(ctypes.byref(g), X.ctypes.data, dY.ctypes.data, dt, int(dw_layout),
+                                       dW.ctypes.data)
+    assert rc == 0, rc
+    return dW
+
+
+def wgrad_approx_nhwc(g, X, dY, scale=1.0, dw_layout=OHWI):
+    """Algorithm 1 from X[n,h,w,c] and dY[n,k,h,w]; returns (dW in the given layout, idx, S)."""
+    X, dY, dt = _pair(X, dY)
+    _check_nhwc(g, X, dY)
+    dW = np.empty(dw_shape(g, dw_layout), np.float64)
+    idx = np.empty((g.N, g.K), np.int32)
+    S = np.empty((g.N, g.K), np.float64)
+    rc = lib().oracle_wgrad_approx_nhwc(ctypes.byref(g), X.ctypes.data, dY.ctypes.data, dt, int(dw_layout),
+                                        float(scale), dW.ctypes.data, idx.ctypes.data, S.ctypes.data)
+    assert rc == 0, rc
+    return dW, idx, S
+
+
+def x_to_nhwc(X):
+    """X[n,c,h,w] -> X[n,h,w,c]: the paper's input transpose (Section 2.4)."""
+    return np.ascontiguousarray(np.asarray(X).transpose(0, 2, 3, 1))
+
+
+def x_to_nchw(X):
+    """X[n,h,w,c] -> X[n,c,h,w]."""
+    return np.ascontiguousarray(np.asarray(X).transpose(0, 3, 1, 2))
+
+
+def dw_permute(dW, src, dst):
+    """Filter gradient from layout src to layout dst (the paper's second transpose is OHWI -> HWIO)."""
+    to_oihw = {OIHW: (0, 1, 2, 3), OHWI: (0, 3, 1, 2), HWIO: (3, 2, 0, 1)}[src]
+    from_oihw = {OIHW: (0, 1, 2, 3), OHWI: (0, 2, 3, 1), HWIO: (2, 3, 1, 0)}[dst]
+    return np.ascontiguousarray(np.asarray(dW).transpose(to_oihw).transpose(from_oihw))
 
 
 def philox4x32_10(counter, key):

@@ -290,6 +290,92 @@ int oracle_wgrad_approx_topk(const oracle_shape *g, const void *X_, const void *
 }
 
 /* ---------------------------------------------------------------------------
+ * The layouts of the paper's own kernel (Section 2.4, last paragraphs):
+ * input activations channel-last, X[n,h,w,c]; output gradient unchanged,
+ * dY[n,k,h,w]; filter gradient produced as [C_o,K,K,C_i] = dW[k,r,s,c]
+ * ("OHWI"), and afterwards transposed to the [K,K,C_i,C_o] = dW[r,s,c,k]
+ * ("HWIO") form in which Section 2.4 writes the filter tensor.  The values are
+ * those of the definitions above; only where an element lives changes.  These
+ * functions index the channel-last tensors directly, they do not go through
+ * the NCHW functions (the tests compare the two routes).
+ * ------------------------------------------------------------------------- */
+enum { ORACLE_DW_OIHW = 0, ORACLE_DW_OHWI = 1, ORACLE_DW_HWIO = 2 };
+
+static double x_at_nhwc(const double *X, const oracle_shape *g, int n, int ih, int iw, int c)
+{
+    if (ih < 0 || ih >= g->H || iw < 0 || iw >= g->W) return 0.0;
+    return X[(((size_t)n * g->H + ih) * g->W + iw) * g->C + c];
+}
+
+/* where dW(k,c,r,s) lives in a filter-gradient tensor of the given layout */
+static size_t dw_offset(const oracle_shape *g, int layout, int k, int c, int r, int s)
+{
+    if (layout == ORACLE_DW_OHWI) return (((size_t)k * g->R + r) * g->S + s) * g->C + c;
+    if (layout == ORACLE_DW_HWIO) return (((size_t)r * g->S + s) * g->C + c) * g->K + k;
+    return (((size_t)k * g->C + c) * g->R + r) * g->S + s;
+}
+
+int oracle_wgrad_exact_nhwc(const oracle_shape *g, const void *X_, const void *dY_, int dtype,
+                            int dw_layout, double *dW)
+{
+    const int Ho = out_h(g), Wo = out_w(g);
+    double *X = to_double(X_, dtype, (size_t)g->N * g->C * g->H * g->W);
+    double *dY = to_double(dY_, dtype, (size_t)g->N * g->K * Ho * Wo);
+    if (!X || !dY) { free(X); free(dY); return -1; }
+#pragma omp parallel for schedule(static) collapse(2)
+    for (int k = 0; k < g->K; ++k)
+        for (int c = 0; c < g->C; ++c)
+            for (int r = 0; r < g->R; ++r)
+                for (int s = 0; s < g->S; ++s) {
+                    double acc = 0.0;
+                    for (int n = 0; n < g->N; ++n)
+                        for (int h = 0; h < Ho; ++h)
+                            for (int w = 0; w < Wo; ++w)
+                                acc += dY[(((size_t)n * g->K + k) * Ho + h) * Wo + w] *
+                                       x_at_nhwc(X, g, n, h * g->stride_h + r - g->pad_h,
+                                                 w * g->stride_w + s - g->pad_w, c);
+                    dW[dw_offset(g, dw_layout, k, c, r, s)] = acc;
+                }
+    free(X); free(dY);
+    return 0;
+}
+
+/* Algorithm 1 on the channel-last input: the patch of map (n,k) is the R x S x C
+ * block of X[n] whose corner is the selected position (its C values per tap are
+ * contiguous, which is why the paper's kernel wants this layout). */
+int oracle_wgrad_approx_nhwc(const oracle_shape *g, const void *X_, const void *dY_, int dtype,
+                             int dw_layout, double scale, double *dW, int32_t *idx_out, double *S_out)
+{
+    const int Ho = out_h(g), Wo = out_w(g), len = Ho * Wo;
+    double *X = to_double(X_, dtype, (size_t)g->N * g->C * g->H * g->W);
+    double *dY = to_double(dY_, dtype, (size_t)g->N * g->K * len);
+    if (!X || !dY) { free(X); free(dY); return -1; }
+    const size_t total = (size_t)g->K * g->C * g->R * g->S;
+    for (size_t o = 0; o < total; ++o) dW[o] = 0.0;
+#pragma omp parallel for schedule(static)
+    for (int k = 0; k < g->K; ++k) {
+        for (int n = 0; n < g->N; ++n) {
+            int32_t where; double sum;
+            select_map(dY + ((size_t)n * g->K + k) * len, len, &where, &sum);
+            if (idx_out) idx_out[(size_t)n * g->K + k] = where;
+            if (S_out) S_out[(size_t)n * g->K + k] = sum;
+            const int row = where / Wo, col = where % Wo;
+            for (int r = 0; r < g->R; ++r)
+                for (int s = 0; s < g->S; ++s)
+                    for (int c = 0; c < g->C; ++c)
+                        dW[dw_offset(g, dw_layout, k, c, r, s)] +=
+                            x_at_nhwc(X, g, n, row * g->stride_h + r - g->pad_h,
+                                      col * g->stride_w + s - g->pad_w, c) * sum;
+        }
+        for (int r = 0; r < g->R; ++r)
+            for (int s = 0; s < g->S; ++s)
+                for (int c = 0; c < g->C; ++c) dW[dw_offset(g, dw_layout, k, c, r, s)] *= scale;
+    }
+    free(X); free(dY);
+    return 0;
+}
+
+/* ---------------------------------------------------------------------------
  * Random gradient (Section 2.2): independent N(0, sigma) values, new for every
  * batch.  The paper drew them on the host with a library generator; what the
  * method fixes is the distribution only.  This build defines the stream as a
