@@ -47,6 +47,8 @@ def main():
     ap.add_argument("--cpu-budget-s", type=float, default=20.0, help="CPU seconds to spend on the oracle baseline (0 = skip)")
     ap.add_argument("--scale", type=float, default=1.0 / 128)
     ap.add_argument("--topk", type=int, default=4, help="k of the top-k column of the per-layer pass (0 = skip)")
+    ap.add_argument("--no-layouts", action="store_true",
+                    help="skip the channel-last columns of the per-layer pass (the paper's kernel layout and its two transposes)")
     ap.add_argument("--phases", default="exact,approx,zero,random",
                     help="phases a step enqueues; anything but the default is for counter runs that must "
                          "attribute every dispatch to one phase, and the printed line then says so")
@@ -176,6 +178,20 @@ def main():
             ws_k = B.alloc_workspace(B.topk_workspace_bytes(d, topk))
             t_tk = time_layer(lambda r: B.conv_wgrad_approx_topk(d, sets[r % copies]._keep[0][i], sets[r % copies]._keep[1][i],
                                                                  topk, scale=args.scale, dW=sets[r % copies]._keep[2][i], ws=ws_k))
+        lay = {}
+        if not args.no_layouts:
+            # the paper's route inside an NCHW framework: transpose X, channel-last kernel (OHWI result), transpose dW
+            Xn = [B.conv_wgrad_transpose_x(d, sets[c]._keep[0][i], True) for c in range(min(copies, 2))]
+            ws_n = B.alloc_workspace(B.nhwc_workspace_bytes(d, B.APPROX))
+            ohwi = torch.empty(B.dw_shape(d, B.DW_OHWI), dtype=torch.float32, device="cuda")
+            hwio = torch.empty(B.dw_shape(d, B.DW_HWIO), dtype=torch.float32, device="cuda")
+            t_k = time_layer(lambda r: B.conv_wgrad_approx_nhwc(d, Xn[r % len(Xn)], sets[r % copies]._keep[1][i], B.DW_OHWI,
+                                                               scale=args.scale, dW=ohwi, ws=ws_n))
+            t_x = time_layer(lambda r: B.conv_wgrad_transpose_x(d, sets[r % copies]._keep[0][i], True, out=Xn[r % len(Xn)]))
+            t_w = time_layer(lambda r: B.conv_wgrad_permute_dw(d, ohwi, B.DW_OHWI, B.DW_HWIO, out=hwio))
+            lay = {"nhwc_kernel_us": round(t_k, 2), "transpose_x_us": round(t_x, 2), "transpose_dw_us": round(t_w, 2),
+                   "nhwc_total_us": round(t_k + t_x + t_w, 2)}
+            del Xn, ws_n
         fl, ab = l.flops(N), approx_algorithmic_bytes(l, N, e)
         per_layer.append({"layer": l.name, "shape": f"{l.C}->{l.K}@{l.H}s{l.stride}",
                           "exact_us": round(t_ex, 2), "approx_us": round(t_ap, 2),
@@ -184,7 +200,7 @@ def main():
                           "approx_gbs": round(ab / t_ap / 1e3, 1),
                           "approx_frac_hbm": round(ab / t_ap / 1e3 / HBM_PEAK_GBS, 4),
                           "speedup": round(t_ex / t_ap, 2),
-                          "topk": topk, "topk_us": round(t_tk, 2) if t_tk else None})
+                          "topk": topk, "topk_us": round(t_tk, 2) if t_tk else None, **lay})
         tot["exact_us"] += t_ex; tot["approx_us"] += t_ap; tot["flops"] += fl; tot["approx_bytes"] += ab
 
     # Roofline of the dominant kernel, in the launch configuration timed above: the exact phase

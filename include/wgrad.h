@@ -99,6 +99,45 @@ int conv_wgrad_approx_topk(const wgrad_conv_desc *desc, const void *X, const voi
 /* Scratch bytes conv_wgrad_approx_topk needs; 0 for an invalid descriptor or topk. */
 size_t conv_wgrad_topk_workspace_bytes(const wgrad_conv_desc *desc, int topk);
 
+/* ---- The layouts of the paper's own kernel (Section 2.4, its last paragraphs) ----
+ * The paper's kernel reads the input activations channel-last, X[n,h,w,c] (the patch
+ * of a selected position is then R rows of S*C contiguous values, and neighbouring
+ * threads read neighbouring channels), takes dY as [n,k,h,w] unchanged, and produces
+ * the filter gradient as [C_o,K,K,C_i] = dW[k,r,s,c] (OHWI).  Its framework holds
+ * activations as NCHW and filters as [K,K,C_i,C_o] = dW[r,s,c,k] (HWIO), so it pays
+ * one transpose of X and one of dW around the kernel.  The calls below take X
+ * channel-last and write dW in any of the three layouts; the two transposes are
+ * also callable on their own so that their cost can be measured. */
+typedef enum { WGRAD_DW_OIHW = 0, WGRAD_DW_OHWI = 1, WGRAD_DW_HWIO = 2 } wgrad_dw_layout;
+
+/* conv_wgrad_approx with X given as [N,H,W,C] (element type desc->dtype); dY, idx_out,
+ * sum_out as there.  dW (K*C*R*S floats) is written in dw_layout.  Same values as
+ * conv_wgrad_approx on the NCHW copy of X, up to the order of the fp32 sums.
+ * ws: at least conv_wgrad_nhwc_workspace_bytes(desc, WGRAD_APPROX). */
+int conv_wgrad_approx_nhwc(const wgrad_conv_desc *desc, const void *X_nhwc, const void *dY, float *dW,
+                           wgrad_dw_layout dw_layout, float scale, int32_t *idx_out, float *sum_out,
+                           void *ws, size_t ws_bytes, void *stream);
+
+/* conv_wgrad_exact with X given as [N,H,W,C]: X is transposed to NCHW inside the
+ * workspace, the NCHW kernels run, and the result is permuted into dw_layout.
+ * ws: at least conv_wgrad_nhwc_workspace_bytes(desc, WGRAD_EXACT). */
+int conv_wgrad_exact_nhwc(const wgrad_conv_desc *desc, const void *X_nhwc, const void *dY, float *dW,
+                          wgrad_dw_layout dw_layout, void *ws, size_t ws_bytes, void *stream);
+
+/* Scratch bytes of the two calls above; 0 for an invalid descriptor or method. */
+size_t conv_wgrad_nhwc_workspace_bytes(const wgrad_conv_desc *desc, wgrad_method method);
+
+/* The paper's input transpose: dst = X as [N,H,W,C] from src = X as [N,C,H,W]
+ * (to_nhwc != 0), or the reverse (to_nhwc == 0).  N*C*H*W elements of desc->dtype
+ * each; src and dst must not overlap. */
+int conv_wgrad_transpose_x(const wgrad_conv_desc *desc, int to_nhwc, const void *src, void *dst, void *stream);
+
+/* The paper's filter-gradient transpose (OHWI -> HWIO) and every other permutation
+ * between the three layouts: dst (layout `to`) = src (layout `from`), K*C*R*S floats
+ * each; src and dst must not overlap. */
+int conv_wgrad_permute_dw(const wgrad_conv_desc *desc, wgrad_dw_layout from, wgrad_dw_layout to,
+                          const float *src, float *dst, void *stream);
+
 /* Zero gradient (Section 2.1): dW = 0. */
 int conv_wgrad_zero(const wgrad_conv_desc *desc, float *dW, void *stream);
 

@@ -19,7 +19,10 @@ OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, LAUNCH_FAILED = 0, -1, -2, -3
 EXPORTS = ("conv_wgrad_exact", "conv_wgrad_approx", "conv_wgrad_select", "conv_wgrad_zero",
            "conv_wgrad_random", "conv_wgrad_workspace_bytes", "conv_wgrad_schedule_run",
            "conv_wgrad_schedule_workspace_bytes", "conv_wgrad_status_string",
-           "conv_wgrad_approx_topk", "conv_wgrad_topk_workspace_bytes")
+           "conv_wgrad_approx_topk", "conv_wgrad_topk_workspace_bytes",
+           "conv_wgrad_approx_nhwc", "conv_wgrad_exact_nhwc", "conv_wgrad_nhwc_workspace_bytes",
+           "conv_wgrad_transpose_x", "conv_wgrad_permute_dw")
+DW_OIHW, DW_OHWI, DW_HWIO = 0, 1, 2
 
 
 class ConvDesc(ctypes.Structure):
@@ -77,6 +80,13 @@ def load():
                                          ctypes.c_size_t, vp]
     L.conv_wgrad_topk_workspace_bytes.argtypes = [P(ConvDesc), ctypes.c_int]
     L.conv_wgrad_topk_workspace_bytes.restype = ctypes.c_size_t
+    L.conv_wgrad_approx_nhwc.argtypes = [P(ConvDesc), vp, vp, fp, ctypes.c_int, ctypes.c_float, i32p, fp, vp,
+                                         ctypes.c_size_t, vp]
+    L.conv_wgrad_exact_nhwc.argtypes = [P(ConvDesc), vp, vp, fp, ctypes.c_int, vp, ctypes.c_size_t, vp]
+    L.conv_wgrad_nhwc_workspace_bytes.argtypes = [P(ConvDesc), ctypes.c_int]
+    L.conv_wgrad_nhwc_workspace_bytes.restype = ctypes.c_size_t
+    L.conv_wgrad_transpose_x.argtypes = [P(ConvDesc), ctypes.c_int, vp, vp, vp]
+    L.conv_wgrad_permute_dw.argtypes = [P(ConvDesc), ctypes.c_int, ctypes.c_int, fp, fp, vp]
     L.conv_wgrad_select.argtypes = [P(ConvDesc), vp, i32p, fp, vp]
     L.conv_wgrad_zero.argtypes = [P(ConvDesc), fp, vp]
     L.conv_wgrad_random.argtypes = [P(ConvDesc), fp, ctypes.c_float, ctypes.c_uint64, ctypes.c_uint64, vp]
@@ -90,7 +100,8 @@ def load():
     L.conv_wgrad_status_string.argtypes = [ctypes.c_int]
     L.conv_wgrad_status_string.restype = ctypes.c_char_p
     for f in ("conv_wgrad_exact", "conv_wgrad_approx", "conv_wgrad_select", "conv_wgrad_zero",
-              "conv_wgrad_random", "conv_wgrad_schedule_run", "conv_wgrad_approx_topk"):
+              "conv_wgrad_random", "conv_wgrad_schedule_run", "conv_wgrad_approx_topk",
+              "conv_wgrad_approx_nhwc", "conv_wgrad_exact_nhwc", "conv_wgrad_transpose_x", "conv_wgrad_permute_dw"):
         getattr(L, f).restype = ctypes.c_int
     _lib = L
     return L
@@ -198,6 +209,76 @@ def conv_wgrad_approx_topk(d, X, dY, k, scale=1.0, dW=None, idx_out=None, sum_ou
     if rc != OK:
         raise WgradError(rc, "conv_wgrad_approx_topk")
     return dW
+
+
+# ---- channel-last input, other filter-gradient layouts ----
+
+def dw_shape(d, layout):
+    return {DW_OIHW: (d.K, d.C, d.R, d.S), DW_OHWI: (d.K, d.R, d.S, d.C), DW_HWIO: (d.R, d.S, d.C, d.K)}[layout]
+
+
+def _check_nhwc(d, X, dY):
+    torch = _torch()
+    want = torch.bfloat16 if d.dtype == BF16 else torch.float32
+    if not X.is_cuda or not X.is_contiguous() or X.dtype != want or tuple(X.shape) != (d.N, d.H, d.W, d.C):
+        raise ValueError(f"X: need a contiguous {want} GPU tensor of shape {(d.N, d.H, d.W, d.C)}, "
+                         f"got {X.dtype} {tuple(X.shape)}")
+    _check_inputs(d, None, dY)
+
+
+def nhwc_workspace_bytes(d, method):
+    return load().conv_wgrad_nhwc_workspace_bytes(ctypes.byref(d), int(method))
+
+
+def conv_wgrad_approx_nhwc(d, X, dY, dw_layout=DW_OHWI, scale=1.0, dW=None, idx_out=None, sum_out=None, ws=None):
+    torch = _torch()
+    _check_nhwc(d, X, dY)
+    dW = torch.empty(dw_shape(d, dw_layout), dtype=torch.float32, device=X.device) if dW is None else dW
+    if ws is None:
+        ws = alloc_workspace(nhwc_workspace_bytes(d, APPROX), X.device)
+    p, n = _ws_args(ws)
+    rc = load().conv_wgrad_approx_nhwc(ctypes.byref(d), _ptr(X), _ptr(dY), _ptr(dW), int(dw_layout), float(scale),
+                                       _ptr(idx_out), _ptr(sum_out), p, n, _stream())
+    if rc != OK:
+        raise WgradError(rc, "conv_wgrad_approx_nhwc")
+    return dW
+
+
+def conv_wgrad_exact_nhwc(d, X, dY, dw_layout=DW_OHWI, dW=None, ws=None):
+    torch = _torch()
+    _check_nhwc(d, X, dY)
+    dW = torch.empty(dw_shape(d, dw_layout), dtype=torch.float32, device=X.device) if dW is None else dW
+    if ws is None:
+        ws = alloc_workspace(nhwc_workspace_bytes(d, EXACT), X.device)
+    p, n = _ws_args(ws)
+    rc = load().conv_wgrad_exact_nhwc(ctypes.byref(d), _ptr(X), _ptr(dY), _ptr(dW), int(dw_layout), p, n, _stream())
+    if rc != OK:
+        raise WgradError(rc, "conv_wgrad_exact_nhwc")
+    return dW
+
+
+def conv_wgrad_transpose_x(d, X, to_nhwc, out=None):
+    torch = _torch()
+    shp = (d.N, d.H, d.W, d.C) if to_nhwc else (d.N, d.C, d.H, d.W)
+    out = torch.empty(shp, dtype=X.dtype, device=X.device) if out is None else out
+    if X.numel() != d.N * d.C * d.H * d.W or not X.is_contiguous() or not out.is_contiguous() or out.dtype != X.dtype \
+            or X.dtype != (torch.bfloat16 if d.dtype == BF16 else torch.float32):
+        raise ValueError("transpose_x: contiguous tensors of the descriptor's size and element type are needed")
+    rc = load().conv_wgrad_transpose_x(ctypes.byref(d), int(bool(to_nhwc)), _ptr(X), _ptr(out), _stream())
+    if rc != OK:
+        raise WgradError(rc, "conv_wgrad_transpose_x")
+    return out
+
+
+def conv_wgrad_permute_dw(d, dW, src_layout, dst_layout, out=None):
+    torch = _torch()
+    out = torch.empty(dw_shape(d, dst_layout), dtype=torch.float32, device=dW.device) if out is None else out
+    if tuple(dW.shape) != dw_shape(d, src_layout) or dW.dtype != torch.float32 or not dW.is_contiguous():
+        raise ValueError(f"permute_dw: need a contiguous float32 tensor of shape {dw_shape(d, src_layout)}")
+    rc = load().conv_wgrad_permute_dw(ctypes.byref(d), int(src_layout), int(dst_layout), _ptr(dW), _ptr(out), _stream())
+    if rc != OK:
+        raise WgradError(rc, "conv_wgrad_permute_dw")
+    return out
 
 
 def conv_wgrad_select(d, dY, idx=None, sums=None):

@@ -83,6 +83,59 @@ size_t conv_wgrad_topk_workspace_bytes(const wgrad_conv_desc *desc, int topk)
     return topk_ws_bytes(g, topk);
 }
 
+int conv_wgrad_approx_nhwc(const wgrad_conv_desc *desc, const void *X, const void *dY, float *dW,
+                           wgrad_dw_layout dw_layout, float scale, int32_t *idx_out, float *sum_out,
+                           void *ws, size_t ws_bytes, void *stream)
+{
+    Geometry g;
+    int rc = make_geometry(desc, g);
+    if (rc != WGRAD_OK) return rc;
+    if (!X || !dY || !dW || !dw_layout_ok(dw_layout)) return WGRAD_INVALID_ARG;
+    if (!ws_ok(ws, ws_bytes, approx_nhwc_ws_bytes(g))) return WGRAD_WORKSPACE_TOO_SMALL;
+    return launch_approx_nhwc(g, X, dY, dW, dw_layout, scale, idx_out, sum_out, ws, (hipStream_t)stream);
+}
+
+int conv_wgrad_exact_nhwc(const wgrad_conv_desc *desc, const void *X, const void *dY, float *dW,
+                          wgrad_dw_layout dw_layout, void *ws, size_t ws_bytes, void *stream)
+{
+    Geometry g;
+    int rc = make_geometry(desc, g);
+    if (rc != WGRAD_OK) return rc;
+    if (!X || !dY || !dW || !dw_layout_ok(dw_layout)) return WGRAD_INVALID_ARG;
+    const ExactPlan pl = plan_exact(g);
+    if (!pl.ok) return WGRAD_UNSUPPORTED;
+    if (!ws_ok(ws, ws_bytes, exact_nhwc_ws_bytes(g, pl))) return WGRAD_WORKSPACE_TOO_SMALL;
+    return launch_exact_nhwc(g, pl, X, dY, dW, dw_layout, ws, (hipStream_t)stream);
+}
+
+size_t conv_wgrad_nhwc_workspace_bytes(const wgrad_conv_desc *desc, wgrad_method method)
+{
+    Geometry g;
+    if (make_geometry(desc, g) != WGRAD_OK) return 0;
+    if (method == WGRAD_EXACT) { const ExactPlan pl = plan_exact(g); return pl.ok ? exact_nhwc_ws_bytes(g, pl) : 0; }
+    if (method == WGRAD_APPROX) return approx_nhwc_ws_bytes(g);
+    return 0;
+}
+
+int conv_wgrad_transpose_x(const wgrad_conv_desc *desc, int to_nhwc, const void *src, void *dst, void *stream)
+{
+    Geometry g;
+    int rc = make_geometry(desc, g);
+    if (rc != WGRAD_OK) return rc;
+    if (!src || !dst || src == dst) return WGRAD_INVALID_ARG;
+    return launch_transpose_x(g, to_nhwc != 0, src, dst, (hipStream_t)stream);
+}
+
+int conv_wgrad_permute_dw(const wgrad_conv_desc *desc, wgrad_dw_layout from, wgrad_dw_layout to,
+                          const float *src, float *dst, void *stream)
+{
+    Geometry g;
+    int rc = make_geometry(desc, g);
+    if (rc != WGRAD_OK) return rc;
+    if (!src || !dst || src == dst || !dw_layout_ok(from) || !dw_layout_ok(to)) return WGRAD_INVALID_ARG;
+    return launch_permute_dw(g, from, to, src, dst, (hipStream_t)stream);
+}
+
 int conv_wgrad_select(const wgrad_conv_desc *desc, const void *dY, int32_t *idx, float *sum, void *stream)
 {
     Geometry g;

@@ -353,10 +353,15 @@ struct FusedParams {
     FastDiv d_rs, d_s, d_wo;
     int32_t *flat_out;           // optional user outputs (single-problem launches only)
     float *sum_out;
+    int dw_layout;               // channel-last form only: where the result goes (WGRAD_DW_*)
 };
 
 // linear: the workgroup's number among the nk * nchunks * nprob of its group
-template <bool BF16>
+//
+// NHWC = true is the layout of the paper's own kernel (Section 2.4): X[n,h,w,c], so that a patch is R
+// rows of S*C contiguous values and consecutive lanes read consecutive channels; the entries of one
+// output channel are then numbered (r, s, c) and fp.d_rs divides by C.
+template <bool BF16, bool NHWC = false>
 __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry &g, const FusedParams &fp,
                                            float (&red)[4][kFusedJ * 64], int linear, int nk, int nchunks, int nprob)
 {
@@ -383,9 +388,10 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
     for (int jj = 0; jj < kFusedJ; ++jj) {
         const int j = lane + 64 * jj;
         uint32_t c, tap, r, s2;
-        fp.d_rs.divmod(j, c, tap);
+        if (NHWC) fp.d_rs.divmod(j, tap, c);
+        else      fp.d_rs.divmod(j, c, tap);
         fp.d_s.divmod(tap, r, s2);
-        xo[jj] = (int)(c * HW + r * g.W + s2);
+        xo[jj] = NHWC ? (int)((r * g.W + s2) * g.C + c) : (int)(c * HW + r * g.W + s2);
         rs[jj] = j < CRS ? (int)(r << 16 | s2) : -1;
         acc[jj] = 0.f;
     }
@@ -453,7 +459,9 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
         uint32_t h, w;
         fp.d_wo.divmod(pos, h, w);
         const int ihb = (int)h * g.sh - g.ph, iwb = (int)w * g.sw - g.pw;
-        const char *Xn = X + ((long)n * g.C * HW + (long)ihb * g.W + iwb) * ESZ;   // may lie before X: only taps inside X are read
+        // may lie before X: only taps inside X are read
+        const char *Xn = NHWC ? X + ((long)n * HW + (long)ihb * g.W + iwb) * g.C * ESZ
+                              : X + ((long)n * g.C * HW + (long)ihb * g.W + iwb) * ESZ;
 #pragma unroll
         for (int jj = 0; jj < kFusedJ; ++jj) {
             const int ih = ihb + (rs[jj] >> 16), iw = iwb + (rs[jj] & 0xffff);
@@ -471,7 +479,17 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
     for (int jj = 0; jj < kFusedJ; ++jj) red[wave][jj * 64 + lane] = acc[jj];
     __syncthreads();
     float *o = out + ((long)by * g.K + k) * CRS;
-    for (int j = tid; j < CRS; j += kBlock) o[j] = (red[0][j] + red[1][j] + red[2][j] + red[3][j]) * fp.scale;
+    for (int j = tid; j < CRS; j += kBlock) {
+        const float v = (red[0][j] + red[1][j] + red[2][j] + red[3][j]) * fp.scale;
+        if (!NHWC || fp.dw_layout == WGRAD_DW_OHWI) {
+            o[j] = v;
+        } else {
+            uint32_t tap, c;
+            fp.d_rs.divmod(j, tap, c);
+            if (fp.dw_layout == WGRAD_DW_HWIO) out[(long)by * g.K * CRS + (long)j * g.K + k] = v;
+            else                               o[c * RS + tap] = v;
+        }
+    }
 }
 
 template <bool BF16>
@@ -480,6 +498,64 @@ __global__ __launch_bounds__(kBlock) void approx_fused(ApproxBatch ab, Geometry 
     __shared__ float red[4][kFusedJ * 64];
     const int linear = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
     fused_body<BF16>(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void approx_fused_nhwc(ApproxBatch ab, Geometry g, FusedParams fp)
+{
+    __shared__ float red[4][kFusedJ * 64];
+    const int linear = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    fused_body<BF16, true>(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z);
+}
+
+// Channel-last gather for the shapes the fused form does not take: one thread per VEC consecutive
+// channels of one filter-gradient entry (k, r, s, c..) and batch chunk.  Consecutive lanes read
+// consecutive channels of the same input pixel, the access pattern the paper's kernel is built on.
+template <bool BF16, int VEC>
+__global__ __launch_bounds__(kBlock) void nhwc_gather(const void *__restrict__ X, const int32_t *__restrict__ hw,
+                                                      const float *__restrict__ sum, float *__restrict__ out,
+                                                      Geometry g, int chunk_n, float scale, int dw_layout)
+{
+    const long o = ((long)blockIdx.x * kBlock + threadIdx.x) * VEC;     // (k, r, s, c) with c fastest
+    const int RS = g.R * g.S, CRS = g.C * RS;
+    if (o >= (long)g.K * CRS) return;
+    const int k = (int)(o / CRS), j = (int)(o % CRS);
+    const int tap = j / g.C, c = j % g.C, r = tap / g.S, s = tap % g.S;
+    const int n_begin = blockIdx.y * chunk_n;
+    const int n_end = n_begin + chunk_n < g.N ? n_begin + chunk_n : g.N;
+    float acc[VEC];
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) acc[v] = 0.f;
+#pragma unroll 4
+    for (int n = n_begin; n < n_end; ++n) {
+        const int p = hw[(long)n * g.K + k];
+        const float sv = sum[(long)n * g.K + k];
+        const int ih = (p >> 16) * g.sh + r - g.ph, iw = (p & 0xffff) * g.sw + s - g.pw;
+        if (ih >= 0 && ih < g.H && iw >= 0 && iw < g.W) {
+            const long xi = (((long)n * g.H + ih) * g.W + iw) * g.C + c;
+            float xv[VEC];
+            if (VEC == 1) {
+                xv[0] = BF16 ? bf16_bits_to_float(((const uint16_t *)X)[xi]) : ((const float *)X)[xi];
+            } else if (BF16) {
+                const uint2 raw = *(const uint2 *)((const uint16_t *)X + xi);
+                xv[0] = __uint_as_float(raw.x << 16); xv[1] = __uint_as_float(raw.x & 0xffff0000u);
+                xv[2] = __uint_as_float(raw.y << 16); xv[3] = __uint_as_float(raw.y & 0xffff0000u);
+            } else {
+                const float4 raw = *(const float4 *)((const float *)X + xi);
+                xv[0] = raw.x; xv[1] = raw.y; xv[2] = raw.z; xv[3] = raw.w;
+            }
+#pragma unroll
+            for (int v = 0; v < VEC; ++v) acc[v] = fmaf(sv, xv[v], acc[v]);
+        }
+    }
+    float *dst = out + (long)blockIdx.y * g.K * CRS;
+#pragma unroll
+    for (int v = 0; v < VEC; ++v) {
+        long at = o + v;
+        if (dw_layout == WGRAD_DW_HWIO) at = (long)(j + v) * g.K + k;
+        else if (dw_layout == WGRAD_DW_OIHW) at = ((long)k * g.C + c + v) * RS + tap;
+        dst[at] = acc[v] * scale;
+    }
 }
 
 // Several groups of layers (each group one geometry) in one launch: a workgroup looks its group up.
@@ -692,7 +768,7 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         FusedParams fp;
         fp.chunk_n = pl.chunk_n; fp.scale = kscale;
         fp.d_rs = FastDiv(g.R * g.S); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
-        fp.flat_out = idx_out; fp.sum_out = sum_out;
+        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW;
         if (fq) {
             // part of a multi-group launch (groups of one element type)
             if (fq->n == kFusedMultiMax || (fq->n > 0 && fq->bf16 != g.bf16)) {
@@ -737,5 +813,54 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
 
 FusedQueue *fused_queue_new() { return new FusedQueue; }
 void fused_queue_delete(FusedQueue *q) { delete q; }
+
+// ---- channel-last input (Section 2.4: the layouts of the paper's kernel) ----
+static ApproxPlan plan_approx_nhwc(const Geometry &g)
+{
+    return plan_approx(g, /*allow_lds=*/false, /*allow_fused=*/true, /*allow_mm=*/false);
+}
+
+size_t approx_nhwc_ws_bytes(const Geometry &g) { return plan_approx_nhwc(g).ws_bytes; }
+
+int launch_approx_nhwc(const Geometry &g, const void *X, const void *dY, float *dW, int dw_layout, float scale,
+                       int32_t *idx_out, float *sum_out, void *ws, hipStream_t st)
+{
+    ApproxPlan pl = plan_approx_nhwc(g);
+    if (pl.fused && ((uintptr_t)dY % (g.bf16 ? 8 : 16)) != 0) pl = plan_approx(g, false, false, false);
+    const long outs = g.dw_elems();
+    ApproxBatch ab{};
+    for (int i = 0; i < kMaxBatch; ++i) {
+        ab.X[i] = X; ab.dY[i] = dY;
+        ab.hw[i] = (int32_t *)((char *)ws + pl.off_idx);
+        ab.sum[i] = (float *)((char *)ws + pl.off_sum);
+        ab.out[i] = pl.chunks > 1 ? (float *)((char *)ws + pl.off_part) : dW;
+    }
+    const float kscale = pl.chunks > 1 ? 1.0f : scale;
+    int rc;
+    if (pl.fused) {
+        FusedParams fp;
+        fp.chunk_n = pl.chunk_n; fp.scale = kscale;
+        fp.d_rs = FastDiv(g.C); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
+        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = dw_layout;
+        const dim3 grid(g.K, pl.chunks, 1);
+        if (g.bf16) WGRAD_LAUNCH((approx_fused_nhwc<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
+        else        WGRAD_LAUNCH((approx_fused_nhwc<false>), grid, dim3(kBlock), 0, st, ab, g, fp);
+        rc = launch_status();
+    } else {
+        rc = launch_select_impl(g, ab, 1, idx_out, sum_out, st);
+        if (rc != WGRAD_OK) return rc;
+        const bool vec = g.C % 4 == 0 && ((uintptr_t)X % (g.bf16 ? 8 : 16)) == 0;
+        const long threads = vec ? outs / 4 : outs;
+        const dim3 grid((unsigned)((threads + kBlock - 1) / kBlock), pl.chunks);
+#define NG_ARGS grid, dim3(kBlock), 0, st, X, ab.hw[0], ab.sum[0], ab.out[0], g, pl.chunk_n, kscale, dw_layout
+        if (g.bf16) { if (vec) WGRAD_LAUNCH((nhwc_gather<true, 4>), NG_ARGS); else WGRAD_LAUNCH((nhwc_gather<true, 1>), NG_ARGS); }
+        else        { if (vec) WGRAD_LAUNCH((nhwc_gather<false, 4>), NG_ARGS); else WGRAD_LAUNCH((nhwc_gather<false, 1>), NG_ARGS); }
+#undef NG_ARGS
+        rc = launch_status();
+    }
+    if (rc != WGRAD_OK || pl.chunks == 1) return rc;
+    float *dst[1] = {dW};
+    return launch_combine((const float *)((char *)ws + pl.off_part), 0, pl.chunks, outs, scale, dst, 1, st, nullptr);
+}
 
 }  // namespace wgrad

@@ -132,6 +132,17 @@ size_t topk_ws_bytes(const Geometry &g, int k);
 int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *dW, int k, float scale,
                        int32_t *idx_out, float *sum_out, void *ws, hipStream_t st);
 
+// channel-last input and the other filter-gradient layouts (Section 2.4)
+bool dw_layout_ok(int layout);
+size_t approx_nhwc_ws_bytes(const Geometry &g);
+int launch_approx_nhwc(const Geometry &g, const void *X, const void *dY, float *dW, int dw_layout, float scale,
+                       int32_t *idx_out, float *sum_out, void *ws, hipStream_t st);
+size_t exact_nhwc_ws_bytes(const Geometry &g, const ExactPlan &pl);
+int launch_exact_nhwc(const Geometry &g, const ExactPlan &pl, const void *X, const void *dY, float *dW,
+                      int dw_layout, void *ws, hipStream_t st);
+int launch_transpose_x(const Geometry &g, bool to_nhwc, const void *src, void *dst, hipStream_t st);
+int launch_permute_dw(const Geometry &g, int from, int to, const float *src, float *dst, hipStream_t st);
+
 // Reductions of partial results that a run of several layers postpones: every producer writes
 // its partials into a workspace region of its own, and one table-driven launch at the end
 // reduces all of them (a launch per layer group costs more than the reduction itself).

@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert set(names) == set(B.EXPORTS) and len(names) == 11
+    assert set(names) == set(B.EXPORTS) and len(names) == 16
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -87,6 +87,33 @@ def test_topk_limits_and_workspace_are_checked_on_the_host(lib):
     assert f(ctypes.byref(d), None, FAKE, FAKE, 8, 1.0, None, None, FAKE, need, None) == B.INVALID_ARG
     bad = B.desc(16, 16, 32, 32, 0)
     assert f(ctypes.byref(bad), FAKE, FAKE, FAKE, 1, 1.0, None, None, FAKE, need, None) == B.INVALID_ARG
+
+
+def test_layout_calls_validate_on_the_host(lib):
+    d = B.desc(16, 16, 32, 32, 16)
+    for method in (B.EXACT, B.APPROX):
+        need = B.nhwc_workspace_bytes(d, method)
+        assert need > 0 and need % 256 == 0
+    assert B.nhwc_workspace_bytes(d, B.EXACT) >= 16 * 16 * 32 * 32 * 4 + B.workspace_bytes(d, B.EXACT)
+    assert B.nhwc_workspace_bytes(d, B.ZERO) == 0
+    ap, ex = lib.conv_wgrad_approx_nhwc, lib.conv_wgrad_exact_nhwc
+    need = B.nhwc_workspace_bytes(d, B.APPROX)
+    assert ap(ctypes.byref(d), FAKE, FAKE, FAKE, 3, 1.0, None, None, FAKE, need, None) == B.INVALID_ARG     # layout
+    assert ap(ctypes.byref(d), FAKE, FAKE, FAKE, -1, 1.0, None, None, FAKE, need, None) == B.INVALID_ARG
+    assert ap(ctypes.byref(d), None, FAKE, FAKE, 1, 1.0, None, None, FAKE, need, None) == B.INVALID_ARG
+    assert ap(ctypes.byref(d), FAKE, FAKE, FAKE, 1, 1.0, None, None, FAKE, need - 1, None) == B.WORKSPACE_TOO_SMALL
+    need = B.nhwc_workspace_bytes(d, B.EXACT)
+    assert ex(ctypes.byref(d), FAKE, FAKE, FAKE, 7, FAKE, need, None) == B.INVALID_ARG
+    assert ex(ctypes.byref(d), FAKE, FAKE, FAKE, 2, FAKE, need - 1, None) == B.WORKSPACE_TOO_SMALL
+    assert ex(ctypes.byref(d), FAKE, FAKE, FAKE, 2, None, need, None) == B.WORKSPACE_TOO_SMALL
+    tx, pm = lib.conv_wgrad_transpose_x, lib.conv_wgrad_permute_dw
+    assert tx(ctypes.byref(d), 1, None, FAKE, None) == B.INVALID_ARG
+    assert tx(ctypes.byref(d), 1, FAKE, FAKE, None) == B.INVALID_ARG           # in place
+    assert pm(ctypes.byref(d), 0, 3, FAKE, ctypes.c_void_p(0x2000), None) == B.INVALID_ARG
+    assert pm(ctypes.byref(d), 0, 1, FAKE, FAKE, None) == B.INVALID_ARG        # in place
+    bad = B.desc(16, 16, 32, 32, 0)
+    assert tx(ctypes.byref(bad), 1, FAKE, ctypes.c_void_p(0x2000), None) == B.INVALID_ARG
+    assert B.nhwc_workspace_bytes(bad, B.APPROX) == 0
 
 
 def test_schedule_validates_all_layers_first(lib):
