@@ -198,9 +198,13 @@ struct GatherParams {
     int wp, pitch;                   // haloed row pitch, LDS pitch of a haloed plane (odd)
     FastDiv d_hw4, d_w;
     float scale;
+    int tk;                          // top-k form: kept positions per map (hw holds tk entries per map) ...
+    float inv_k;                     // ... each weighted by sum / tk
 };
 
-template <bool BF16, int M>
+// TOPK: every map contributes tk patches (its kept positions, hw[(n*K + k)*tk + t]) with weight sum/tk
+// instead of one with weight sum; a group is then limited to nb*M*tk <= 64 (position, weight) pairs.
+template <bool BF16, int M, bool TOPK = false>
 __global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch ab, Geometry g, GatherParams gp)
 {
     const void *__restrict__ X = ab.X[blockIdx.z];
@@ -242,10 +246,19 @@ __global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch
     auto prefetch = [&](int n0) {
         // lane l of every wavefront: map (image n0 + l / M, channel k_base + l % M).  Issued before
         // the plane loads: memory returns in order, so once the planes have arrived these have too.
-        const int n = n0 + lane / M, k = k_base + lane % M;
-        const bool ok = lane < nb * M && n < n_end && k < g.K;
-        hw_next = ok ? hw[(long)n * g.K + k] : 0;
-        sv_next = ok ? sum[(long)n * g.K + k] : 0.f;
+        if (TOPK) {
+            const int per_img = M * gp.tk;
+            const int n = n0 + lane / per_img, q = lane % per_img;
+            const int k = k_base + q / gp.tk, t = q % gp.tk;
+            const bool ok = lane < nb * per_img && n < n_end && k < g.K;
+            hw_next = ok ? hw[((long)n * g.K + k) * gp.tk + t] : 0;
+            sv_next = ok ? sum[(long)n * g.K + k] * gp.inv_k : 0.f;
+        } else {
+            const int n = n0 + lane / M, k = k_base + lane % M;
+            const bool ok = lane < nb * M && n < n_end && k < g.K;
+            hw_next = ok ? hw[(long)n * g.K + k] : 0;
+            sv_next = ok ? sum[(long)n * g.K + k] : 0.f;
+        }
         const int nb_cur = n_end - n0 < nb ? n_end - n0 : nb;
         const int total = nb_cur * run4;
 #pragma unroll
@@ -309,14 +322,18 @@ __global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch
             for (int n_l = 0; n_l < nb_cur; ++n_l, plane += kGatherCT * pitch) {
 #pragma unroll
                 for (int j = 0; j < M; ++j) {
-                    const int p = __builtin_amdgcn_readlane(hw_cur, n_l * M + j);
-                    const float sv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sv_cur), n_l * M + j));
-                    const float *win = plane + (p >> 16) * g.sh * WP + (p & 0xffff) * g.sw;   // window origin
+                    const int tk = TOPK ? gp.tk : 1;
+                    for (int t = 0; t < tk; ++t) {
+                        const int slot = TOPK ? (n_l * M + j) * tk + t : n_l * M + j;
+                        const int p = __builtin_amdgcn_readlane(hw_cur, slot);
+                        const float sv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sv_cur), slot));
+                        const float *win = plane + (p >> 16) * g.sh * WP + (p & 0xffff) * g.sw;   // window origin
 #pragma unroll
-                    for (int r = 0; r < 3; ++r) {
-                        const float *row = win + r * WP;
+                        for (int r = 0; r < 3; ++r) {
+                            const float *row = win + r * WP;
 #pragma unroll
-                        for (int s = 0; s < 3; ++s) acc[j][r * 3 + s] = fmaf(sv, row[s], acc[j][r * 3 + s]);
+                            for (int s = 0; s < 3; ++s) acc[j][r * 3 + s] = fmaf(sv, row[s], acc[j][r * 3 + s]);
+                        }
                     }
                 }
             }
@@ -354,6 +371,8 @@ struct FusedParams {
     int32_t *flat_out;           // optional user outputs (single-problem launches only)
     float *sum_out;
     int dw_layout;               // channel-last form only: where the result goes (WGRAD_DW_*)
+    int tk;                      // top-k form only: kept positions per map, each weighted by sum * inv_k
+    float inv_k;
 };
 
 // linear: the workgroup's number among the nk * nchunks * nprob of its group
@@ -361,7 +380,10 @@ struct FusedParams {
 // NHWC = true is the layout of the paper's own kernel (Section 2.4): X[n,h,w,c], so that a patch is R
 // rows of S*C contiguous values and consecutive lanes read consecutive channels; the entries of one
 // output channel are then numbered (r, s, c) and fp.d_rs divides by C.
-template <bool BF16, bool NHWC = false>
+// TOPK = true keeps fp.tk positions per map: the scan is repeated with "largest rank key below the last one
+// found" (keys (|v| bits << 32) | ~position are unique within a map), every kept position's patch enters
+// the same one-step-delayed accumulation with weight sum / tk.
+template <bool BF16, bool NHWC = false, bool TOPK = false>
 __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry &g, const FusedParams &fp,
                                            float (&red)[4][kFusedJ * 64], int linear, int nk, int nchunks, int nprob)
 {
@@ -408,12 +430,79 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
             if (e < L) m[v] = *(const raw4 *)(base + (long)e * ESZ);
         }
     };
+    // the patch requested one step ago has had a whole scan to arrive: accumulate it
+    auto accumulate_pending = [&]() {
+#pragma unroll
+        for (int jj = 0; jj < kFusedJ; ++jj) acc[jj] = fmaf(S_pend, x_pend[jj], acc[jj]);
+    };
+    // request the patch of position pos of image n; it is accumulated one step later
+    auto request_patch = [&](int n, int pos) {
+        uint32_t h, w;
+        fp.d_wo.divmod(pos, h, w);
+        const int ihb = (int)h * g.sh - g.ph, iwb = (int)w * g.sw - g.pw;
+        // may lie before X: only taps inside X are read
+        const char *Xn = NHWC ? X + ((long)n * HW + (long)ihb * g.W + iwb) * g.C * ESZ
+                              : X + ((long)n * g.C * HW + (long)ihb * g.W + iwb) * ESZ;
+#pragma unroll
+        for (int jj = 0; jj < kFusedJ; ++jj) {
+            const int ih = ihb + (rs[jj] >> 16), iw = iwb + (rs[jj] & 0xffff);
+            x_pend[jj] = 0.f;
+            if (rs[jj] >= 0 && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
+                x_pend[jj] = BF16 ? bf16_bits_to_float(*(const uint16_t *)(Xn + (long)xo[jj] * ESZ))
+                                  : *(const float *)(Xn + (long)xo[jj] * ESZ);
+        }
+    };
     if (n_begin + wave < n_end) load_map(n_begin + wave, nxt);
     for (int n = n_begin + wave; n < n_end; n += 4) {
 #pragma unroll
         for (int v = 0; v < kFusedV; ++v) cur[v] = nxt[v];
         if (n + 4 < n_end) load_map(n + 4, nxt);
 
+        if (TOPK) {
+            float sum = 0.f, S = 0.f;
+            unsigned long long below = ~0ull;
+            for (int t = 0; t < fp.tk; ++t) {
+                unsigned long long best = 0ull;          // lanes that hold nothing lose every comparison
+#pragma unroll
+                for (int v = 0; v < kFusedV; ++v) {
+                    const int e = (lane + 64 * v) * 4;
+                    if (e < L) {
+                        uint32_t bits[4];
+                        if (BF16) {
+                            const uint2 r2 = *(const uint2 *)&cur[v];
+                            bits[0] = r2.x << 16; bits[1] = r2.x & 0xffff0000u; bits[2] = r2.y << 16; bits[3] = r2.y & 0xffff0000u;
+                        } else {
+                            const uint4 r4 = *(const uint4 *)&cur[v];
+                            bits[0] = r4.x; bits[1] = r4.y; bits[2] = r4.z; bits[3] = r4.w;
+                        }
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            unsigned long long pk = ((unsigned long long)mag_key<BF16>(bits[i]) << 32) | (uint32_t)~(uint32_t)(e + i);
+                            pk = pk < below ? pk : 0ull;
+                            best = pk > best ? pk : best;
+                            if (t == 0) sum += __uint_as_float(bits[i]);
+                        }
+                    }
+                }
+#pragma unroll
+                for (int d = 32; d > 0; d >>= 1) {
+                    const unsigned long long other = __shfl_xor(best, d, 64);
+                    best = other > best ? other : best;
+                    if (t == 0) sum += __shfl_xor(sum, d, 64);
+                }
+                if (t == 0) S = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sum)));
+                const int pos = __builtin_amdgcn_readfirstlane((int)~(uint32_t)best);
+                below = best;
+                if (lane == 0) {
+                    if (fp.flat_out) fp.flat_out[((long)n * g.K + k) * fp.tk + t] = pos;
+                    if (fp.sum_out && t == 0) fp.sum_out[(long)n * g.K + k] = S;
+                }
+                accumulate_pending();
+                request_patch(n, pos);
+                S_pend = S * fp.inv_k;
+            }
+            continue;
+        }
         // ---- select: per-lane scan in ascending position, then a butterfly over the wavefront ----
         uint32_t best_key = 0, best_pos = 0;
         bool have = false;
@@ -452,24 +541,8 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
             if (fp.flat_out) fp.flat_out[(long)n * g.K + k] = pos;
             if (fp.sum_out) fp.sum_out[(long)n * g.K + k] = S;
         }
-        // ---- the patch of the previous image has had this image's scan to arrive: accumulate it ----
-#pragma unroll
-        for (int jj = 0; jj < kFusedJ; ++jj) acc[jj] = fmaf(S_pend, x_pend[jj], acc[jj]);
-        // ---- request the patch of the selected position; it is accumulated one image later ----
-        uint32_t h, w;
-        fp.d_wo.divmod(pos, h, w);
-        const int ihb = (int)h * g.sh - g.ph, iwb = (int)w * g.sw - g.pw;
-        // may lie before X: only taps inside X are read
-        const char *Xn = NHWC ? X + ((long)n * HW + (long)ihb * g.W + iwb) * g.C * ESZ
-                              : X + ((long)n * g.C * HW + (long)ihb * g.W + iwb) * ESZ;
-#pragma unroll
-        for (int jj = 0; jj < kFusedJ; ++jj) {
-            const int ih = ihb + (rs[jj] >> 16), iw = iwb + (rs[jj] & 0xffff);
-            x_pend[jj] = 0.f;
-            if (rs[jj] >= 0 && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
-                x_pend[jj] = BF16 ? bf16_bits_to_float(*(const uint16_t *)(Xn + (long)xo[jj] * ESZ))
-                                  : *(const float *)(Xn + (long)xo[jj] * ESZ);
-        }
+        accumulate_pending();
+        request_patch(n, pos);
         S_pend = S;
     }
 #pragma unroll
@@ -506,6 +579,14 @@ __global__ __launch_bounds__(kBlock) void approx_fused_nhwc(ApproxBatch ab, Geom
     __shared__ float red[4][kFusedJ * 64];
     const int linear = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
     fused_body<BF16, true>(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z);
+}
+
+template <bool BF16>
+__global__ __launch_bounds__(kBlock) void approx_fused_topk(ApproxBatch ab, Geometry g, FusedParams fp)
+{
+    __shared__ float red[4][kFusedJ * 64];
+    const int linear = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    fused_body<BF16, false, true>(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z);
 }
 
 // Channel-last gather for the shapes the fused form does not take: one thread per VEC consecutive
@@ -707,10 +788,86 @@ static void launch_gather_lds(const ApproxPlan &pl, dim3 grid, size_t lds, hipSt
     gp.d_hw4 = FastDiv(g.H * g.W / 4);        // dividends stay below 64 * H*W, far under the 2^32 bound
     gp.d_w = FastDiv(g.W);
     gp.scale = scale;
+    gp.tk = 1; gp.inv_k = 1.0f;
 #define GL_ARGS grid, dim3(kGatherBlock), lds, st, ab, g, gp
     if (pl.m == 2) WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 2>), GL_ARGS);
     else WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 1>), GL_ARGS);
 #undef GL_ARGS
+}
+
+// Batch-chunk partials (bytes) that the top-k forms borrowed from this file may need.
+size_t topk_borrowed_partial_bytes(const Geometry &g)
+{
+    size_t need = 0;
+    const ApproxPlan a = plan_approx(g, true, false, false), b = plan_approx(g, false, true, false);
+    if (a.use_lds && a.chunks > 1) need = (size_t)a.chunks * g.dw_elems() * 4;
+    if (b.fused && b.chunks > 1 && (size_t)b.chunks * g.dw_elems() * 4 > need) need = (size_t)b.chunks * g.dw_elems() * 4;
+    return need;
+}
+
+// Top-k through the fused kernel (selection and gather in one launch, positions never leave registers).
+// False if the shape is not one the fused form takes.
+bool topk_fused(const Geometry &g, const void *X, const void *dY, int k, float scale, float *dW,
+                int32_t *idx_out, float *sum_out, float *partials, hipStream_t st, int *rc)
+{
+    const ApproxPlan pl = plan_approx(g, /*allow_lds=*/false, /*allow_fused=*/true, /*allow_mm=*/false);
+    if (!pl.fused || ((uintptr_t)dY % (g.bf16 ? 8 : 16)) != 0) return false;
+    const long outs = g.dw_elems();
+    ApproxBatch ab{};
+    for (int i = 0; i < kMaxBatch; ++i) {
+        ab.X[i] = X; ab.dY[i] = dY;
+        ab.out[i] = pl.chunks > 1 ? partials : dW;
+    }
+    FusedParams fp;
+    fp.chunk_n = pl.chunk_n; fp.scale = pl.chunks > 1 ? 1.0f : scale;
+    fp.d_rs = FastDiv(g.R * g.S); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
+    fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = k; fp.inv_k = 1.0f / k;
+    const dim3 grid(g.K, pl.chunks, 1);
+    if (g.bf16) WGRAD_LAUNCH((approx_fused_topk<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
+    else        WGRAD_LAUNCH((approx_fused_topk<false>), grid, dim3(kBlock), 0, st, ab, g, fp);
+    *rc = launch_status();
+    if (*rc == WGRAD_OK && pl.chunks > 1) {
+        float *dst[1] = {dW};
+        *rc = launch_combine(partials, 0, pl.chunks, outs, scale, dst, 1, st, nullptr);
+    }
+    return true;
+}
+
+// The LDS gather over the kept positions of the top-k form.  False if the shape is not one the LDS
+// form takes (the caller then uses its general gather); rc receives the launch status otherwise.
+bool topk_gather_lds(const Geometry &g, const void *X, const int32_t *hw, const float *sum, int k, float scale,
+                     float *dW, float *partials, size_t partial_cap_bytes, hipStream_t st, int *rc)
+{
+    ApproxPlan pl = plan_approx(g, /*allow_lds=*/true, /*allow_fused=*/false, /*allow_mm=*/false);
+    if (!pl.use_lds || pl.m * k > 64 || ((uintptr_t)X % (g.bf16 ? 8 : 16)) != 0) return false;
+    if (pl.nb > 64 / (pl.m * k)) pl.nb = 64 / (pl.m * k);
+    const long outs = g.dw_elems();
+    if (pl.chunks > 1 && (size_t)pl.chunks * outs * 4 > partial_cap_bytes) return false;
+    ApproxBatch ab{};
+    for (int i = 0; i < kMaxBatch; ++i) {
+        ab.X[i] = X; ab.hw[i] = const_cast<int32_t *>(hw); ab.sum[i] = const_cast<float *>(sum);
+        ab.out[i] = pl.chunks > 1 ? partials : dW;
+    }
+    GatherParams gp;
+    gp.ctiles = pl.ctiles; gp.nb = pl.nb; gp.chunk_n = pl.chunk_n; gp.wp = pl.wp; gp.pitch = pl.pitch;
+    gp.d_hw4 = FastDiv(g.H * g.W / 4);
+    gp.d_w = FastDiv(g.W);
+    gp.scale = pl.chunks > 1 ? 1.0f : scale;
+    gp.tk = k; gp.inv_k = 1.0f / k;
+    const dim3 grid(pl.ctiles * pl.ktiles, pl.chunks, 1);
+    const size_t lds = (size_t)2 * pl.nb * kGatherCT * pl.pitch * 4;
+#define GL_ARGS grid, dim3(kGatherBlock), lds, st, ab, g, gp
+    if (g.bf16) { if (pl.m == 2) WGRAD_LAUNCH((approx_gather_lds3x3<true, 2, true>), GL_ARGS);
+                  else           WGRAD_LAUNCH((approx_gather_lds3x3<true, 1, true>), GL_ARGS); }
+    else        { if (pl.m == 2) WGRAD_LAUNCH((approx_gather_lds3x3<false, 2, true>), GL_ARGS);
+                  else           WGRAD_LAUNCH((approx_gather_lds3x3<false, 1, true>), GL_ARGS); }
+#undef GL_ARGS
+    *rc = launch_status();
+    if (*rc == WGRAD_OK && pl.chunks > 1) {
+        float *dst[1] = {dW};
+        *rc = launch_combine(partials, 0, pl.chunks, outs, scale, dst, 1, st, nullptr);
+    }
+    return true;
 }
 
 int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, float scale,
@@ -768,7 +925,7 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         FusedParams fp;
         fp.chunk_n = pl.chunk_n; fp.scale = kscale;
         fp.d_rs = FastDiv(g.R * g.S); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
-        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW;
+        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = 1; fp.inv_k = 1.0f;
         if (fq) {
             // part of a multi-group launch (groups of one element type)
             if (fq->n == kFusedMultiMax || (fq->n > 0 && fq->bf16 != g.bf16)) {
@@ -841,7 +998,7 @@ int launch_approx_nhwc(const Geometry &g, const void *X, const void *dY, float *
         FusedParams fp;
         fp.chunk_n = pl.chunk_n; fp.scale = kscale;
         fp.d_rs = FastDiv(g.C); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
-        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = dw_layout;
+        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = dw_layout; fp.tk = 1; fp.inv_k = 1.0f;
         const dim3 grid(g.K, pl.chunks, 1);
         if (g.bf16) WGRAD_LAUNCH((approx_fused_nhwc<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
         else        WGRAD_LAUNCH((approx_fused_nhwc<false>), grid, dim3(kBlock), 0, st, ab, g, fp);

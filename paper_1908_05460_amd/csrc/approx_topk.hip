@@ -150,12 +150,19 @@ bool topk_supported(const Geometry &g, int k)
     return k >= 1 && k <= kTopKMax && (long)k <= (long)g.Ho * g.Wo && g.Ho < 32768 && g.Wo < 65536;
 }
 
+// batch-chunk partials of whichever form runs: the general gather here, the fused kernel or the LDS gather
+static size_t topk_partial_bytes(const Geometry &g)
+{
+    const int chunks = topk_chunks(g);
+    size_t general = chunks > 1 ? (size_t)chunks * g.dw_elems() * sizeof(float) : 0;
+    const size_t borrowed = topk_borrowed_partial_bytes(g);
+    return align_up(general > borrowed ? general : borrowed);
+}
+
 size_t topk_ws_bytes(const Geometry &g, int k)
 {
     const size_t maps = (size_t)g.N * g.K;
-    const int chunks = topk_chunks(g);
-    return align_up(maps * k * sizeof(int32_t)) + align_up(maps * sizeof(float)) +
-           (chunks > 1 ? align_up((size_t)chunks * g.dw_elems() * sizeof(float)) : 0);
+    return align_up(maps * k * sizeof(int32_t)) + align_up(maps * sizeof(float)) + topk_partial_bytes(g);
 }
 
 int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *dW, int k, float scale,
@@ -168,6 +175,10 @@ int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *
     float *sum = (float *)w;     w += align_up((size_t)maps * sizeof(float));
     float *partials = (float *)w;
 
+    int rc;
+    // maps of up to 1024 positions and C*R*S <= 576: selection and gather in one launch
+    if (topk_fused(g, X, dY, k, scale, dW, idx_out, sum_out, partials, st, &rc)) return rc;
+
     const long grid = (maps + kBlock / 64 - 1) / (kBlock / 64);
     if (grid >= (1l << 31)) return WGRAD_UNSUPPORTED;
 #define SEL_ARGS dim3((unsigned)grid), dim3(kBlock), 0, st, dY, maps, len, g.Wo, k, hw, idx_out, sum, sum_out
@@ -179,8 +190,11 @@ int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *
     if (g.bf16) { SEL_PICK(true); } else { SEL_PICK(false); }
 #undef SEL_PICK
 #undef SEL_ARGS
-    int rc = launch_status();
+    rc = launch_status();
     if (rc != WGRAD_OK) return rc;
+
+    // small planes and many output channels: the LDS-staged gather of the k = 1 path, over k positions per map
+    if (topk_gather_lds(g, X, hw, sum, k, scale, dW, partials, topk_partial_bytes(g), st, &rc)) return rc;
 
     const int chunks = topk_chunks(g);
     const int chunk_n = (g.N + chunks - 1) / chunks;

@@ -129,6 +129,11 @@ int fused_flush(FusedQueue &q, hipStream_t st);
 constexpr int kTopKMax = 64;
 bool topk_supported(const Geometry &g, int k);
 size_t topk_ws_bytes(const Geometry &g, int k);
+size_t topk_borrowed_partial_bytes(const Geometry &g);
+bool topk_fused(const Geometry &g, const void *X, const void *dY, int k, float scale, float *dW,
+                int32_t *idx_out, float *sum_out, float *partials, hipStream_t st, int *rc);
+bool topk_gather_lds(const Geometry &g, const void *X, const int32_t *hw, const float *sum, int k, float scale,
+                     float *dW, float *partials, size_t partial_cap_bytes, hipStream_t st, int *rc);
 int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *dW, int k, float scale,
                        int32_t *idx_out, float *sum_out, void *ws, hipStream_t st);
 
