@@ -11,6 +11,13 @@
 
 namespace wgrad {
 
+#ifdef WGRAD_TUNING
+static __device__ long long g_trace_fused[4 * 8192];
+#define FTRACE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace_fused[4 * blockIdx.x + (i)] = wall_clock64(); } while (0)
+#else
+#define FTRACE(i) do { } while (0)
+#endif
+
 // ------------------------------------------------------------------------------------
 // select: a group of G lanes (power of two, <= 64) owns one map; each lane walks the
 // map in 16-byte pieces G pieces apart, keeps its own best (|v| bits, position) and
@@ -383,7 +390,9 @@ struct FusedParams {
 // TOPK = true keeps fp.tk positions per map: the scan is repeated with "largest rank key below the last one
 // found" (keys (|v| bits << 32) | ~position are unique within a map), every kept position's patch enters
 // the same one-step-delayed accumulation with weight sum / tk.
-template <bool BF16, bool NHWC = false, bool TOPK = false>
+// V, FULLMAP: a map is V 16-byte pieces per lane; FULLMAP says that every lane holds all V of them (maps of
+// exactly 256*V positions), which leaves the image loop free of conditional loads and of branches.
+template <bool BF16, bool NHWC, bool TOPK, int V, bool FULLMAP>
 __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry &g, const FusedParams &fp,
                                            float (&red)[4][kFusedJ * 64], int linear, int nk, int nchunks, int nprob)
 {
@@ -404,7 +413,9 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
     const int n_end = n_begin + fp.chunk_n < g.N ? n_begin + fp.chunk_n : g.N;
 
     // the dW entries j = lane + 64*jj of channel k that this lane accumulates
-    int xo[kFusedJ], rs[kFusedJ];
+    // xo: element offset of the entry's tap from the patch origin (bits 0-23), its tap row (24-27) and
+    // column (28-30); negative for an entry beyond C*R*S
+    int xo[kFusedJ];
     float acc[kFusedJ];
 #pragma unroll
     for (int jj = 0; jj < kFusedJ; ++jj) {
@@ -413,60 +424,97 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
         if (NHWC) fp.d_rs.divmod(j, tap, c);
         else      fp.d_rs.divmod(j, c, tap);
         fp.d_s.divmod(tap, r, s2);
-        xo[jj] = NHWC ? (int)((r * g.W + s2) * g.C + c) : (int)(c * HW + r * g.W + s2);
-        rs[jj] = j < CRS ? (int)(r << 16 | s2) : -1;
+        const uint32_t off = NHWC ? (r * g.W + s2) * g.C + c : c * HW + r * g.W + s2;
+        xo[jj] = j < CRS ? (int)(off | r << 24 | s2 << 28) : (int)0x80000000u;   // beyond C*R*S: offset 0, sign bit set
         acc[jj] = 0.f;
     }
 
     float x_pend[kFusedJ], S_pend = 0.f;       // patch and sum of the previous image, not yet accumulated
 #pragma unroll
     for (int jj = 0; jj < kFusedJ; ++jj) x_pend[jj] = 0.f;
-    raw4 cur[kFusedV], nxt[kFusedV];
-    auto load_map = [&](int n, raw4 (&m)[kFusedV]) {
+    // one map buffer: the next image's map is requested as soon as the scan has consumed this one's, and
+    // arrives under the butterfly, the accumulation and the patch request
+    raw4 cur[V];
+    auto load_map = [&](int n, raw4 (&m)[V]) {
         const char *base = dY + ((long)n * g.K + k) * L * ESZ;
 #pragma unroll
-        for (int v = 0; v < kFusedV; ++v) {
+        for (int v = 0; v < V; ++v) {
             const int e = (lane + 64 * v) * 4;
-            if (e < L) m[v] = *(const raw4 *)(base + (long)e * ESZ);
+            if (FULLMAP || e < L) m[v] = *(const raw4 *)(base + (long)e * ESZ);
         }
     };
-    // the patch requested one step ago has had a whole scan to arrive: accumulate it
+    // the patch requested one step ago has had a whole scan to arrive: accumulate it (the loaded values are
+    // touched only here, so the wait for them sits here and not behind the request)
+    uint32_t pend_inside = 0;                  // bit jj: entry jj of the pending patch lies inside X
+    bool pend_whole = true;                    // wavefront-uniform: the pending patch lies inside X entirely
     auto accumulate_pending = [&]() {
+        if (pend_whole) {
 #pragma unroll
-        for (int jj = 0; jj < kFusedJ; ++jj) acc[jj] = fmaf(S_pend, x_pend[jj], acc[jj]);
+            for (int jj = 0; jj < kFusedJ; ++jj)
+                acc[jj] = fmaf(S_pend, BF16 ? __uint_as_float(__float_as_uint(x_pend[jj]) << 16) : x_pend[jj], acc[jj]);
+        } else {
+#pragma unroll
+            for (int jj = 0; jj < kFusedJ; ++jj)
+                acc[jj] = fmaf(S_pend, (pend_inside >> jj & 1) ? (BF16 ? __uint_as_float(__float_as_uint(x_pend[jj]) << 16) : x_pend[jj]) : 0.f,
+                               acc[jj]);
+        }
     };
-    // request the patch of position pos of image n; it is accumulated one step later
+    // request the patch of position pos of image n; it is accumulated one step later.  The kernel is bound
+    // by the number of vector instructions per image, so the common case -- a patch that lies inside X
+    // entirely, a wavefront-uniform test -- is one add and one load per entry; only patches that reach
+    // into the padding pay for per-tap bounds.  Every lane loads unconditionally in both cases (a tap
+    // outside X, or an entry beyond C*R*S, reads a valid element that is not used), so there are no
+    // branches around the loads and all nine are in flight together.  Offsets are relative to the image
+    // start, a scalar base.
     auto request_patch = [&](int n, int pos) {
         uint32_t h, w;
         fp.d_wo.divmod(pos, h, w);
         const int ihb = (int)h * g.sh - g.ph, iwb = (int)w * g.sw - g.pw;
-        // may lie before X: only taps inside X are read
-        const char *Xn = NHWC ? X + ((long)n * HW + (long)ihb * g.W + iwb) * g.C * ESZ
-                              : X + ((long)n * g.C * HW + (long)ihb * g.W + iwb) * ESZ;
+        const char *Ximg = X + (long)n * g.C * HW * ESZ;
+        const int origin = (ihb * g.W + iwb) * (NHWC ? g.C : 1);      // may be negative; a tap inside X is not
+        pend_whole = ihb >= 0 && ihb + g.R <= g.H && iwb >= 0 && iwb + g.S <= g.W;
+        if (pend_whole) {
 #pragma unroll
-        for (int jj = 0; jj < kFusedJ; ++jj) {
-            const int ih = ihb + (rs[jj] >> 16), iw = iwb + (rs[jj] & 0xffff);
-            x_pend[jj] = 0.f;
-            if (rs[jj] >= 0 && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W)
-                x_pend[jj] = BF16 ? bf16_bits_to_float(*(const uint16_t *)(Xn + (long)xo[jj] * ESZ))
-                                  : *(const float *)(Xn + (long)xo[jj] * ESZ);
+            for (int jj = 0; jj < kFusedJ; ++jj) {
+                const uint32_t off = (uint32_t)(origin + (xo[jj] & 0xffffff)) * ESZ;
+                if (BF16) x_pend[jj] = __uint_as_float((uint32_t)*(const uint16_t *)(Ximg + off));   // widened when used
+                else      x_pend[jj] = *(const float *)(Ximg + off);
+            }
+        } else {
+            pend_inside = 0;
+#pragma unroll
+            for (int jj = 0; jj < kFusedJ; ++jj) {
+                const int ih = ihb + ((xo[jj] >> 24) & 15), iw = iwb + ((xo[jj] >> 28) & 7);
+                const bool inside = xo[jj] >= 0 && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
+                const uint32_t off = inside ? (uint32_t)(origin + (xo[jj] & 0xffffff)) * ESZ : 0u;
+                pend_inside |= (uint32_t)inside << jj;
+                if (BF16) x_pend[jj] = __uint_as_float((uint32_t)*(const uint16_t *)(Ximg + off));
+                else      x_pend[jj] = *(const float *)(Ximg + off);
+            }
         }
     };
-    if (n_begin + wave < n_end) load_map(n_begin + wave, nxt);
-    for (int n = n_begin + wave; n < n_end; n += 4) {
+    FTRACE(1);
+    if (n_begin + wave < n_end) load_map(n_begin + wave, cur);
+    // Pass the first map through opaque moves: the wait for it then sits here, and the loop is entered with
+    // no load pending on these registers.  Otherwise the wait the compiler places before the scan must
+    // cover this first load on the entry path, and (the memory counter being in-order) it would then also
+    // drain the previous image's patch loads in every iteration.
 #pragma unroll
-        for (int v = 0; v < kFusedV; ++v) cur[v] = nxt[v];
-        if (n + 4 < n_end) load_map(n + 4, nxt);
-
+    for (int v = 0; v < V; ++v) {
+        uint32_t *w = (uint32_t *)&cur[v];
+#pragma unroll
+        for (int i = 0; i < (int)(sizeof(raw4) / 4); ++i) asm volatile("v_mov_b32 %0, %1" : "=v"(w[i]) : "v"(w[i]));
+    }
+    for (int n = n_begin + wave; n < n_end; n += 4) {
         if (TOPK) {
             float sum = 0.f, S = 0.f;
             unsigned long long below = ~0ull;
             for (int t = 0; t < fp.tk; ++t) {
                 unsigned long long best = 0ull;          // lanes that hold nothing lose every comparison
 #pragma unroll
-                for (int v = 0; v < kFusedV; ++v) {
+                for (int v = 0; v < V; ++v) {
                     const int e = (lane + 64 * v) * 4;
-                    if (e < L) {
+                    if (FULLMAP || e < L) {
                         uint32_t bits[4];
                         if (BF16) {
                             const uint2 r2 = *(const uint2 *)&cur[v];
@@ -501,6 +549,7 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
                 request_patch(n, pos);
                 S_pend = S * fp.inv_k;
             }
+            if (n + 4 < n_end) load_map(n + 4, cur);
             continue;
         }
         // ---- select: per-lane scan in ascending position, then a butterfly over the wavefront ----
@@ -508,9 +557,9 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
         bool have = false;
         float sum = 0.f;
 #pragma unroll
-        for (int v = 0; v < kFusedV; ++v) {
+        for (int v = 0; v < V; ++v) {
             const int e = (lane + 64 * v) * 4;
-            if (e < L) {
+            if (FULLMAP || e < L) {
                 uint32_t bits[4];
                 if (BF16) {
                     const uint2 r2 = *(const uint2 *)&cur[v];
@@ -527,6 +576,7 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
                 }
             }
         }
+        if (n + 4 < n_end) load_map(n + 4, cur);
         unsigned long long packed = have ? ((unsigned long long)best_key << 32) | (uint32_t)~best_pos : 0ull;
 #pragma unroll
         for (int d = 32; d > 0; d >>= 1) {
@@ -545,8 +595,8 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
         request_patch(n, pos);
         S_pend = S;
     }
-#pragma unroll
-    for (int jj = 0; jj < kFusedJ; ++jj) acc[jj] = fmaf(S_pend, x_pend[jj], acc[jj]);
+    accumulate_pending();
+    FTRACE(2);
     // ---- add the four wavefronts' sums and write this chunk's row of the result ----
 #pragma unroll
     for (int jj = 0; jj < kFusedJ; ++jj) red[wave][jj * 64 + lane] = acc[jj];
@@ -565,12 +615,24 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
     }
 }
 
+// Picks the body for the map size: maps of exactly 1024 or 256 positions get the branch-free forms.
+template <bool BF16, bool NHWC, bool TOPK>
+__device__ __forceinline__ void fused_dispatch(const ApproxBatch &ab, const Geometry &g, const FusedParams &fp,
+                                               float (&red)[4][kFusedJ * 64], int linear, int nk, int nchunks, int nprob)
+{
+    const int L = g.Ho * g.Wo;
+    if (L == 1024)     fused_body<BF16, NHWC, TOPK, 4, true>(ab, g, fp, red, linear, nk, nchunks, nprob);
+    else if (L == 256) fused_body<BF16, NHWC, TOPK, 1, true>(ab, g, fp, red, linear, nk, nchunks, nprob);
+    else if (L < 256)  fused_body<BF16, NHWC, TOPK, 1, false>(ab, g, fp, red, linear, nk, nchunks, nprob);
+    else               fused_body<BF16, NHWC, TOPK, kFusedV, false>(ab, g, fp, red, linear, nk, nchunks, nprob);
+}
+
 template <bool BF16>
 __global__ __launch_bounds__(kBlock) void approx_fused(ApproxBatch ab, Geometry g, FusedParams fp)
 {
     __shared__ float red[4][kFusedJ * 64];
     const int linear = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-    fused_body<BF16>(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z);
+    fused_dispatch<BF16, false, false>(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z);
 }
 
 template <bool BF16>
@@ -578,7 +640,7 @@ __global__ __launch_bounds__(kBlock) void approx_fused_nhwc(ApproxBatch ab, Geom
 {
     __shared__ float red[4][kFusedJ * 64];
     const int linear = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-    fused_body<BF16, true>(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z);
+    fused_dispatch<BF16, true, false>(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z);
 }
 
 template <bool BF16>
@@ -586,7 +648,7 @@ __global__ __launch_bounds__(kBlock) void approx_fused_topk(ApproxBatch ab, Geom
 {
     __shared__ float red[4][kFusedJ * 64];
     const int linear = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
-    fused_body<BF16, false, true>(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z);
+    fused_dispatch<BF16, false, true>(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z);
 }
 
 // Channel-last gather for the shapes the fused form does not take: one thread per VEC consecutive
@@ -666,9 +728,18 @@ __global__ __launch_bounds__(kBlock) void approx_fused_multi(const FusedMulti)
     for (int i = 1; i < n; ++i) gi += (int)blockIdx.x >= mp->begin[i];
     const int linear = (int)blockIdx.x - mp->begin[gi];
     if (linear >= mp->count[gi]) return;
+    FTRACE(0);
     const FusedGroup &G = mp->grp[gi];
-    fused_body<BF16>(G.ab, G.g, G.fp, red, linear, G.g.K, G.nchunks, G.nprob);
+    fused_dispatch<BF16, false, false>(G.ab, G.g, G.fp, red, linear, G.g.K, G.nchunks, G.nprob);
+    FTRACE(3);
 }
+
+#ifdef WGRAD_TUNING
+extern "C" int wgrad_debug_read_trace_fused(long long *host_out)
+{
+    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace_fused), sizeof(long long) * 4 * 8192);
+}
+#endif
 
 struct FusedQueue {
     int n = 0, bf16 = 0;
@@ -878,11 +949,20 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         aligned = aligned && ((uintptr_t)b.X[i] % (g.bf16 ? 8 : 16)) == 0 && ((uintptr_t)b.dY[i] % (g.bf16 ? 8 : 16)) == 0;
     ApproxPlan pl = ((plan.use_lds || plan.fused || plan.mm) && !aligned) ? plan_approx(g, false, false, false) : plan;
     const long outs = g.dw_elems();
-    if (pl.fused && b.n > 1) {
-        // the workgroup target is for the whole launch: a batch chunks each problem less finely
-        long chunks = (tune_int("WGRAD_FUSED_BLOCKS", 768) + (long)g.K * b.n - 1) / ((long)g.K * b.n);
+    if (pl.fused && (b.n > 1 || fq)) {
+        long chunks;
+        if (fq) {
+            // part of a launch of many groups, which fills the chip anyway: chunk for the images a wavefront
+            // walks -- eight: fewer (more, shorter workgroups) loses to the per-workgroup set-up and to the
+            // larger partial sums, more leaves too few workgroups to balance the tail
+            const int per_wave = tune_int("WGRAD_FUSED_IPW", 8);
+            chunks = (g.N + 4 * per_wave - 1) / (4 * per_wave);
+        } else {
+            // the workgroup target is for the whole launch: a batch chunks each problem less finely
+            chunks = (tune_int("WGRAD_FUSED_BLOCKS", 768) + (long)g.K * b.n - 1) / ((long)g.K * b.n);
+        }
         if (chunks < 1) chunks = 1;
-        if (chunks < pl.chunks) {
+        if (chunks < pl.chunks) {       // never more than planned: the workspace holds pl.chunks partials
             pl.chunk_n = (int)((g.N + chunks - 1) / chunks);
             pl.chunks = (g.N + pl.chunk_n - 1) / pl.chunk_n;
         }
