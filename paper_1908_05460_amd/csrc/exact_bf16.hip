@@ -41,7 +41,7 @@ bool plan_exact_bf16(const Geometry &g, ExactPlan &pl)
         int ppw = (nti * iht * rowp + 1) / 2;
         while (ppw % 32 != 1) ++ppw;
         const int buf_words = 4 * (4 * ppw + 12);
-        size_t lds = ((size_t)2 * buf_words + qt / 2) * 4;
+        size_t lds = ((size_t)2 * buf_words + qt / 2 + 8) * 4;      // two windows, the pair-offset table, 8 dump words
         const size_t red = (size_t)4 * 144 * 20 * 4;               // epilogue exchange buffer [4][144][20]
         if (red > lds) lds = red;
         const int xv = p4 ? 4 : bf16_xv(rowp);
@@ -118,7 +118,7 @@ int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, fl
     return launch_status();
 }
 
-#ifdef WGRAD_TUNING
+#if defined(WGRAD_TUNING) && !defined(WGRAD_NO_TRACE)
 extern "C" int wgrad_debug_read_trace_bf16(long long *host_out)
 {
     return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace), sizeof(long long) * (64 + 2 * 4096));

@@ -224,18 +224,22 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
     // x0), (x1, x2), ...  The left neighbour is the previous lane (pieces of a row sit in consecutive
     // lanes, and a row never straddles a group of 16 lanes); the last piece of a row also writes
     // (x{XV-1}, halo).
+    // Every lane writes unconditionally (a slot without a piece, and the halo word of a piece that is not the
+    // last of its row, go to a few dump words behind the tables): a conditional write masks lanes, and an
+    // instruction that changes the lane mask fences the instruction scheduler, which must be free to spread
+    // this work under the matrix instructions.
+    uint32_t *const dump = Xs0 + 2 * p.buf_words + QT / 2;          // 8 words
     auto commit_x = [&](uint32_t *buf) {
         if (P4) {
             // rows 1 and 2 of the plane's window: (halo, x00) (x01, halo) (halo, x10) (x11, halo)
 #pragma unroll
-            for (int u = 0; u < XS; ++u)
-                if (x_pack[u] >= 0) {
-                    uint32_t *w = buf + x_pack[u];
-                    w[0] = xr[u][0] << 16;
-                    w[1] = xr[u][0] >> 16;
-                    w[2] = xr[u][1] << 16;
-                    w[3] = xr[u][1] >> 16;
-                }
+            for (int u = 0; u < XS; ++u) {
+                uint32_t *w = x_pack[u] >= 0 ? buf + x_pack[u] : dump;
+                w[0] = xr[u][0] << 16;
+                w[1] = xr[u][0] >> 16;
+                w[2] = xr[u][1] << 16;
+                w[3] = xr[u][1] >> 16;
+            }
             return;
         }
 #pragma unroll
@@ -245,14 +249,13 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
 #pragma unroll
             for (int i = 0; i < XV / 2; ++i) r[i] = ok ? xr[u][i] : 0u;
             uint32_t left = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)r[XV / 2 - 1], 0x111, 0xf, 0xf, true);   // row_shr:1
-            if (x_pack[u] >= 0) {
-                if ((x_pack[u] >> 28) & 1) left = 0u;
-                uint32_t *w = buf + (x_pack[u] & 0xfffff);
-                w[0] = __builtin_amdgcn_alignbit(r[0], left, 16);
+            if ((x_pack[u] >> 28) & 1) left = 0u;
+            uint32_t *w = x_pack[u] >= 0 ? buf + (x_pack[u] & 0xfffff) : dump;
+            w[0] = __builtin_amdgcn_alignbit(r[0], left, 16);
 #pragma unroll
-                for (int i = 1; i < XV / 2; ++i) w[i] = __builtin_amdgcn_alignbit(r[i], r[i - 1], 16);
-                if ((x_pack[u] >> 29) & 1) w[XV / 2] = r[XV / 2 - 1] >> 16;
-            }
+            for (int i = 1; i < XV / 2; ++i) w[i] = __builtin_amdgcn_alignbit(r[i], r[i - 1], 16);
+            uint32_t *wl = (x_pack[u] >= 0 && ((x_pack[u] >> 29) & 1)) ? w + XV / 2 : dump + XV / 2;
+            *wl = r[XV / 2 - 1] >> 16;
         }
     };
 
@@ -311,22 +314,19 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
         if (wt == wt_begin + 2) TRACE(4);
         if (wt == wt_begin + 3) TRACE(8);
         const char *Xw = (const char *)(Xs0 + par * p.buf_words) + lane_base;
-#ifdef WGRAD_BF16_PRIO            // timing experiments
-        __builtin_amdgcn_s_setprio(WGRAD_BF16_PRIO);
-#endif
+        // The window of tile wt+1 is committed and the loads of tile wt+2 are requested after the first
+        // group's operand reads, in one scheduling region with the matrix instructions of both groups (no
+        // fence, no lane-mask changes inside), so that the scheduler spreads this vector and scalar work
+        // under them; ahead of the matrix instructions it was a phase of its own in which the wavefront
+        // issued none.
+        auto stage_next = [&]() {
 #ifndef WGRAD_BF16_NOCOMMIT      // timing experiments only: results are then wrong
-        commit_x(Xs0 + (par ^ 1) * p.buf_words);
+            commit_x(Xs0 + (par ^ 1) * p.buf_words);
 #endif
-        if (wt == wt_begin + 2) TRACE(5);
-        load_x(wt + 2);
-        if (wt == wt_begin + 2) TRACE(6);
-        // keep these loads here: sunk below the matrix instructions (which would save their registers)
-        // they would be the youngest loads in flight at the next commit, which then waits a full
-        // memory round trip
-        __builtin_amdgcn_sched_barrier(0);
-#ifdef WGRAD_BF16_PRIO
-        __builtin_amdgcn_s_setprio(0);
-#endif
+            if (wt == wt_begin + 2) TRACE(5);
+            load_x(wt + 2);
+            if (wt == wt_begin + 2) TRACE(6);
+        };
         const bool has_next = wt + 1 < wt_end;
         const char *dyb, *xb;
         int ih0;
@@ -400,6 +400,7 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
 #endif
             }
             if (wt == wt_begin + 2 && gi == 0) TRACE(11);
+            if (gi == 0) stage_next();
         }
         if (wt == wt_begin + 2) TRACE(7);
     }
