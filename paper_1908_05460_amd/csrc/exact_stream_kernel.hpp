@@ -292,6 +292,17 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
         commit_x(Xs0);
         TRACE(22);
         load_x(wt_begin + 1);
+#ifndef WGRAD_STREAM_NOSETTLE
+        // Enter the loop with no load pending.  The memory counter is in-order and the compiler merges what is
+        // pending on the entry path with what is pending around the loop: in the loop the window pieces are
+        // older than the operand pieces requested after them and the commit may leave those in flight; on the
+        // entry path they are the youngest loads.  Merged, every tile would begin by waiting for everything,
+        // the operand pieces requested late in the tile before included.
+#pragma unroll
+        for (int u = 0; u < XS; ++u) xr[u].settle();
+#pragma unroll
+        for (int gi = 0; gi < GPW; ++gi) ring[gi].settle();
+#endif
     }
     TRACE(2);
 
