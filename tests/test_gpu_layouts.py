@@ -117,3 +117,26 @@ def test_workload_layers_at_full_size():
         got = B.conv_wgrad_approx_nhwc(d, to_gpu(Xl), to_gpu(dY), B.DW_OHWI, scale=1 / 128).cpu().numpy()
         want, _, _ = oracle.wgrad_approx_nhwc(oracle_shape(d), Xl, dY, 1 / 128, oracle.OHWI)
         assert normwise_err(got, want) <= TOL["fp32"], layer.name
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("t", [SMALL[0], SMALL[5], SMALL[9], SMALL[20]])
+def test_tensors_that_are_only_element_aligned(t, dtype):
+    """X and dY start one element into their allocations: no 16-byte access may be used on them."""
+    d = mk(t, dtype)
+    X, dY = rand_inputs(d, 78, dtype)
+    Xl = oracle.x_to_nhwc(X)
+
+    def shifted(a):
+        flat = to_gpu(np.concatenate([a.ravel()[:1], a.ravel()]))
+        return flat[1:].view(a.shape)
+    Xg, dYg = shifted(Xl), shifted(dY)
+    assert Xg.data_ptr() % 16 != 0 and dYg.data_ptr() % 16 != 0
+    g = oracle_shape(d)
+    got = B.conv_wgrad_approx_nhwc(d, Xg, dYg, B.DW_HWIO).cpu().numpy()
+    assert normwise_err(got, oracle.wgrad_approx_nhwc(g, Xl, dY, 1.0, oracle.HWIO)[0]) <= TOL[dtype]
+    got = B.conv_wgrad_exact_nhwc(d, Xg, dYg, B.DW_OHWI).cpu().numpy()
+    assert normwise_err(got, oracle.wgrad_exact_nhwc(g, Xl, dY, oracle.OHWI)) <= TOL[dtype]
+    back = B.conv_wgrad_transpose_x(d, Xg, False)
+    assert np.array_equal(back.view(dtype=__import__("torch").int16).cpu().numpy().view(np.uint16) if dtype == "bf16"
+                          else back.cpu().numpy(), X)

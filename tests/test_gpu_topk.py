@@ -124,3 +124,24 @@ def test_topk_on_a_workload_layer_at_full_size():
     d = B.desc_for(layer, 128)
     X, dY = rand_inputs(d, 31)
     check(d, X, dY, 4, "fp32", scale=1 / 128)
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("t", [SMALL[0], SMALL[5], SMALL[9], SMALL[20]])
+def test_tensors_that_are_only_element_aligned(t, dtype):
+    """X and dY start one element into their allocations: the fused and LDS forms must step aside or cope."""
+    import torch
+    d = mk(t, dtype)
+    X, dY = rand_inputs(d, 79, dtype)
+
+    def shifted(a):
+        flat = to_gpu(np.concatenate([a.ravel()[:1], a.ravel()]))
+        return flat[1:].view(a.shape)
+    Xg, dYg = shifted(X), shifted(dY)
+    assert Xg.data_ptr() % 16 != 0 and dYg.data_ptr() % 16 != 0
+    k = min(3, d.Ho * d.Wo)
+    idx = torch.empty((d.N, d.K, k), dtype=torch.int32, device="cuda")
+    got = B.conv_wgrad_approx_topk(d, Xg, dYg, k, idx_out=idx).cpu().numpy()
+    want, want_idx, _ = oracle.wgrad_approx_topk(oracle_shape(d), X, dY, k)
+    assert np.array_equal(idx.cpu().numpy(), want_idx)
+    assert normwise_err(got, want) <= TOL[dtype]
