@@ -136,3 +136,44 @@ def test_schedule_validates_all_layers_first(lib):
 def test_status_strings(lib):
     seen = {B.status_string(s) for s in (0, -1, -2, -3, -4, -99)}
     assert len(seen) == 6 and B.status_string(0) == "ok"
+
+
+C_CALLER = r"""
+#include <stdio.h>
+#include "wgrad.h"
+int main(void)
+{
+    wgrad_conv_desc d = {128, 16, 32, 32, 16, 3, 3, 1, 1, 1, 1, WGRAD_F32};
+    printf("%zu %zu %zu %zu\n", conv_wgrad_workspace_bytes(&d, WGRAD_EXACT), conv_wgrad_workspace_bytes(&d, WGRAD_APPROX),
+           conv_wgrad_topk_workspace_bytes(&d, 4), conv_wgrad_nhwc_workspace_bytes(&d, WGRAD_APPROX));
+    printf("%d %s\n", conv_wgrad_exact(&d, 0, 0, 0, 0, 0, 0), conv_wgrad_status_string(WGRAD_INVALID_ARG));
+    return 0;
+}
+"""
+
+
+def test_header_is_plain_c_and_a_c_program_can_call_the_library(lib, tmp_path):
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if not gcc:
+        pytest.skip("no gcc")
+    inc = os.path.join(ROOT, "include")
+    src = tmp_path / "caller.c"
+    src.write_text(C_CALLER)
+    # the header alone: strict C99 and C++
+    subprocess.run([gcc, "-std=c99", "-pedantic", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    subprocess.run([gcc, "-x", "c++", "-std=c++11", "-Wall", "-Werror", "-fsyntax-only", "-I", inc, str(src)], check=True)
+    hip = "/opt/rocm/lib/libamdhip64.so"
+    if not os.path.exists(hip):
+        pytest.skip("no HIP runtime to link a C program against")
+    exe = tmp_path / "caller"
+    pkg = os.path.dirname(B.LIB_PATH)
+    subprocess.run([gcc, "-std=c99", "-I", inc, str(src), "-o", str(exe), "-L", pkg, "-l:libwgrad.so", hip,
+                    "-Wl,-rpath," + pkg, "-Wl,-rpath,/opt/rocm/lib"], check=True)
+    out = subprocess.run([str(exe)], check=True, capture_output=True, text=True, timeout=120).stdout.split("\n")
+    d = B.desc(128, 16, 32, 32, 16)
+    want = [B.workspace_bytes(d, B.EXACT), B.workspace_bytes(d, B.APPROX), B.topk_workspace_bytes(d, 4),
+            B.nhwc_workspace_bytes(d, B.APPROX)]
+    assert [int(x) for x in out[0].split()] == want
+    assert out[1].split()[0] == str(B.INVALID_ARG) and out[1].split(None, 1)[1] == B.status_string(B.INVALID_ARG)
