@@ -57,11 +57,13 @@ def test_layer_at_benchmark_size(workload, index):
     assert normwise_err(got_a, want_a) <= TOL[dtype]
 
 
-def test_whole_resnet_stack_through_schedule_run_matches_per_layer_oracle_samples():
-    """The launch path bench.py uses: one conv_wgrad_schedule_run per method over the stack."""
+@pytest.mark.parametrize("workload", ["resnet20_n128_fp32", "vgg19_n128_fp32", "vgg19_n512_bf16"])
+def test_whole_stack_through_schedule_run_matches_per_layer_oracle_samples(workload):
+    """The launch path bench.py uses: one conv_wgrad_schedule_run per method over the stack; then a mask that
+    mixes the methods (every other layer approximated), as the schedule sweep runs it."""
     import torch
     from paper_1908_05460_amd import schedule as sch
-    cfg, stack_fn, N, dtype = inputs.WORKLOADS["resnet20_n128_fp32"]
+    cfg, stack_fn, N, dtype = inputs.WORKLOADS[workload]
     stack = stack_fn()
     descs = [B.desc_for(l, N, dtype) for l in stack]
     data = [inputs.make_layer_inputs(l, N, cfg, 0, i, dtype) for i, l in enumerate(stack)]
@@ -70,15 +72,24 @@ def test_whole_resnet_stack_through_schedule_run_matches_per_layer_oracle_sample
     s = B.Schedule(descs, Xs, dYs, dWs)
     exact = np.full(len(stack), sch.EXACT, np.uint8)
     approx = np.full(len(stack), sch.APPROX, np.uint8)
-    ws = B.alloc_workspace(max(s.workspace_bytes(exact), s.workspace_bytes(approx)))
+    mixed = exact.copy(); mixed[1::2] = sch.APPROX
+    ws = B.alloc_workspace(max(s.workspace_bytes(m) for m in (exact, approx, mixed)))
     s.run(exact, ws)
     ex = [t.cpu().numpy().ravel().copy() for t in dWs]
     s.run(approx, ws, scale=1.0)
     ap = [t.cpu().numpy().copy() for t in dWs]
+    s.run(mixed, ws, scale=1.0)
+    mx = [t.cpu().numpy().copy() for t in dWs]
     rng = np.random.default_rng(5)
     for i, l in enumerate(stack):
         g = oracle_shape(descs[i])
         pick = rng.integers(0, ex[i].size, 24)
         want = oracle.wgrad_exact_at(g, data[i][0], data[i][1], pick)
-        assert np.abs(ex[i][pick] - want).max() <= TOL[dtype] * max(np.abs(want).max(), np.abs(ex[i]).max()), l.name
-        assert normwise_err(ap[i], oracle.wgrad_approx(g, data[i][0], data[i][1])[0]) <= TOL[dtype], l.name
+        bound = TOL[dtype] * max(np.abs(want).max(), np.abs(ex[i]).max())
+        assert np.abs(ex[i][pick] - want).max() <= bound, l.name
+        want_a = oracle.wgrad_approx(g, data[i][0], data[i][1])[0]
+        assert normwise_err(ap[i], want_a) <= TOL[dtype], l.name
+        if mixed[i] == sch.APPROX:
+            assert normwise_err(mx[i], want_a) <= TOL[dtype], l.name
+        else:
+            assert np.abs(mx[i].ravel()[pick] - want).max() <= bound, l.name
