@@ -379,11 +379,15 @@ int oracle_wgrad_approx_nhwc(const oracle_shape *g, const void *X_, const void *
  * Random gradient (Section 2.2): independent N(0, sigma) values, new for every
  * batch.  The paper drew them on the host with a library generator; what the
  * method fixes is the distribution only.  This build defines the stream as a
- * pure function of (seed, offset + i) so the GPU can be checked value by value:
- *   (w0,w1,w2,w3) = Philox4x32-10(counter = (lo32(g), hi32(g), 0, 0),
- *                                 key = (lo32(seed), hi32(seed))),  g = offset + i
- *   u1 = ((w0 >> 8) + 0.5) / 2^24,  u2 = ((w1 >> 8) + 0.5) / 2^24   (both in (0,1))
- *   value = sigma * sqrt(-2 ln u1) * cos(2 pi u2)                    (Box-Muller)
+ * pure function of (seed, offset + i) so the GPU can be checked value by value.
+ * One Philox call gives four 32-bit words, i.e. two Box-Muller pairs, i.e. four
+ * independent normals (the cosine and the sine of one pair are independent), so
+ * four consecutive stream positions share a call:
+ *   g = offset + i,  c = g / 4,  j = g mod 4
+ *   (w0,w1,w2,w3) = Philox4x32-10(counter = (lo32(c), hi32(c), 0, 0),
+ *                                 key = (lo32(seed), hi32(seed)))
+ *   pair p = j / 2:  u1 = ((w[2p] >> 8) + 0.5) / 2^24,  u2 = ((w[2p+1] >> 8) + 0.5) / 2^24   (both in (0,1))
+ *   value = sigma * sqrt(-2 ln u1) * (j even ? cos(2 pi u2) : sin(2 pi u2))                    (Box-Muller)
  * Philox4x32-10 is the counter-based generator of Salmon, Moraes, Dror and
  * Shaw, "Parallel random numbers: as easy as 1, 2, 3" (SC'11).
  * ------------------------------------------------------------------------- */
@@ -411,12 +415,16 @@ void oracle_random_normal(uint64_t seed, uint64_t offset, int64_t count, double 
     const uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
     for (int64_t i = 0; i < count; ++i) {
         uint64_t gidx = offset + (uint64_t)i;
-        uint32_t ctr[4] = { (uint32_t)gidx, (uint32_t)(gidx >> 32), 0u, 0u };
+        uint64_t c = gidx >> 2;
+        int j = (int)(gidx & 3u);
+        uint32_t ctr[4] = { (uint32_t)c, (uint32_t)(c >> 32), 0u, 0u };
         uint32_t w[4];
         oracle_philox4x32_10(ctr, key, w);
-        double u1 = ((double)(w[0] >> 8) + 0.5) / 16777216.0;
-        double u2 = ((double)(w[1] >> 8) + 0.5) / 16777216.0;
-        out[i] = sigma * sqrt(-2.0 * log(u1)) * cos(two_pi * u2);
+        int p = j >> 1;
+        double u1 = ((double)(w[2 * p] >> 8) + 0.5) / 16777216.0;
+        double u2 = ((double)(w[2 * p + 1] >> 8) + 0.5) / 16777216.0;
+        double radius = sqrt(-2.0 * log(u1));
+        out[i] = sigma * radius * ((j & 1) ? sin(two_pi * u2) : cos(two_pi * u2));
     }
 }
 
