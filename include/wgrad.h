@@ -142,11 +142,13 @@ int conv_wgrad_permute_dw(const wgrad_conv_desc *desc, wgrad_dw_layout from, wgr
 int conv_wgrad_zero(const wgrad_conv_desc *desc, float *dW, void *stream);
 
 /* Random gradient (Section 2.2): independent N(0, sigma) values (paper: 1/128).
- * dW[i] is a pure function of (seed, offset + i): Philox4x32-10 with counter
- * (lo32, hi32, 0, 0) of offset + i and key (lo32, hi32) of seed, then Box-Muller
- * on the first two output words, u = ((word >> 8) + 0.5) / 2^24.  The caller
- * advances offset by K*C*R*S per layer and batch so that every batch draws new
- * numbers, as the method requires. */
+ * dW[i] is a pure function of (seed, offset + i).  With g = offset + i, c = g / 4,
+ * j = g mod 4: Philox4x32-10 with counter (lo32, hi32, 0, 0) of c and key
+ * (lo32, hi32) of seed gives four words; words (0,1) serve j = 0,1 and words (2,3)
+ * serve j = 2,3 as Box-Muller pairs, u = ((word >> 8) + 0.5) / 2^24:
+ *   dW[i] = sigma * sqrt(-2 ln u1) * (j even ? cos(2 pi u2) : sin(2 pi u2)).
+ * The caller advances offset by K*C*R*S per layer and batch so that every batch
+ * draws new numbers, as the method requires. */
 int conv_wgrad_random(const wgrad_conv_desc *desc, float *dW, float sigma,
                       uint64_t seed, uint64_t offset, void *stream);
 

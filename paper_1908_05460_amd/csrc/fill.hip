@@ -68,7 +68,7 @@ int launch_zero_table(float *const *dW, const long *elems, int n, hipStream_t st
 // Philox4x32-10 (Salmon, Moraes, Dror, Shaw, SC'11): ten rounds of two 32x32->64
 // multiplications with the key bumped by the Weyl constants after each round.
 __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                              uint32_t k0, uint32_t k1, uint32_t &o0, uint32_t &o1)
+                                              uint32_t k0, uint32_t k1, uint32_t (&o)[4])
 {
 #pragma unroll
     for (int round = 0; round < 10; ++round) {
@@ -81,36 +81,68 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
         k0 += 0x9E3779B9u;
         k1 += 0xBB67AE85u;
     }
-    o0 = c0;
-    o1 = c1;
+    o[0] = c0; o[1] = c1; o[2] = c2; o[3] = c3;
 }
 
-// dW[i] = sigma * sqrt(-2 ln u1) * cos(2 pi u2), with (u1, u2) from the first two
-// Philox words of counter (offset + i) under key seed; u = ((word >> 8) + 0.5) / 2^24
-// lies strictly inside (0,1) and is exact in fp32.
-__device__ __forceinline__ float normal_at(uint64_t gidx, float sigma, uint64_t seed)
+// The four values of generator call c: stream positions 4c .. 4c+3.  Words (0,1) and (2,3) are two
+// Box-Muller pairs, u = ((word >> 8) + 0.5) / 2^24 (strictly inside (0,1), exact in fp32); a pair gives
+// sigma * sqrt(-2 ln u1) * cos(2 pi u2) for the even position and the sine for the odd one.
+__device__ __forceinline__ void normal4_at(uint64_t c, float sigma, uint64_t seed, float (&z)[4])
 {
-    uint32_t w0, w1;
-    philox4x32_10((uint32_t)gidx, (uint32_t)(gidx >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), w0, w1);
-    const float u1 = ((float)(w0 >> 8) + 0.5f) * (1.0f / 16777216.0f);
-    const float u2 = ((float)(w1 >> 8) + 0.5f) * (1.0f / 16777216.0f);
-    return sigma * sqrtf(-2.0f * logf(u1)) * cospif(2.0f * u2);
+    uint32_t w[4];
+    philox4x32_10((uint32_t)c, (uint32_t)(c >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), w);
+#pragma unroll
+    for (int p = 0; p < 2; ++p) {
+        const float u1 = ((float)(w[2 * p] >> 8) + 0.5f) * (1.0f / 16777216.0f);
+        const float u2 = ((float)(w[2 * p + 1] >> 8) + 0.5f) * (1.0f / 16777216.0f);
+        const float radius = sigma * sqrtf(-2.0f * logf(u1));
+        float sn, cs;
+        sincospif(2.0f * u2, &sn, &cs);
+        z[2 * p] = radius * cs;
+        z[2 * p + 1] = radius * sn;
+    }
+}
+
+// One thread per generator call: positions 4c..4c+3 of the stream, those of them that lie in
+// [offset, offset + elems) written to dW[position - offset] (the first and the last call of a tensor may
+// reach outside it).
+__device__ __forceinline__ void fill_normal_call(float *__restrict__ dW, long elems, uint64_t offset, long call,
+                                                 float sigma, uint64_t seed)
+{
+    const uint64_t c = (offset >> 2) + (uint64_t)call;
+    const long first = (long)(4 * c - offset);            // index in dW of position 4c (negative for the first call of an unaligned offset)
+    if (first >= elems) return;
+    float z[4];
+    normal4_at(c, sigma, seed, z);
+    if (first >= 0 && first + 3 < elems && ((uintptr_t)(dW + first) % 16) == 0) {
+        *(float4 *)(dW + first) = make_float4(z[0], z[1], z[2], z[3]);
+    } else {
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            if (first + j >= 0 && first + j < elems) dW[first + j] = z[j];
+    }
+}
+
+// generator calls that cover positions offset .. offset + elems - 1
+__host__ __device__ inline long normal_calls(long elems, uint64_t offset)
+{
+    return elems > 0 ? (long)(((offset + (uint64_t)elems - 1) >> 2) - (offset >> 2) + 1) : 0;
 }
 
 __global__ __launch_bounds__(kBlock) void fill_normal(float *__restrict__ dW, long elems, float sigma,
                                                       uint64_t seed, uint64_t offset)
 {
-    const long i = (long)blockIdx.x * kBlock + threadIdx.x;
-    if (i >= elems) return;
-    dW[i] = normal_at(offset + (uint64_t)i, sigma, seed);
+    const long call = (long)blockIdx.x * kBlock + threadIdx.x;
+    if (call >= normal_calls(elems, offset)) return;
+    fill_normal_call(dW, elems, offset, call, sigma, seed);
 }
 
 __global__ __launch_bounds__(kBlock) void fill_normal_table(const FillTable t, float sigma, uint64_t seed)
 {
     const int it = table_entry(t);
-    const long i = (long)((int)blockIdx.x - t.begin[it]) * kBlock + threadIdx.x;
-    if (i >= t.elems[it]) return;
-    t.dst[it][i] = normal_at(t.offset[it] + (uint64_t)i, sigma, seed);
+    const long call = (long)((int)blockIdx.x - t.begin[it]) * kBlock + threadIdx.x;
+    if (call >= normal_calls(t.elems[it], t.offset[it])) return;
+    fill_normal_call(t.dst[it], t.elems[it], t.offset[it], call, sigma, seed);
 }
 
 int launch_random_table(float *const *dW, const long *elems, const uint64_t *offset, int n, float sigma,
@@ -121,7 +153,7 @@ int launch_random_table(float *const *dW, const long *elems, const uint64_t *off
     long blocks = 0;
     for (int i = 0; i < n; ++i) {
         t.dst[i] = dW[i]; t.elems[i] = elems[i]; t.offset[i] = offset[i]; t.begin[i] = (int)blocks;
-        blocks += (elems[i] + kBlock - 1) / kBlock;
+        blocks += (normal_calls(elems[i], offset[i]) + kBlock - 1) / kBlock;
     }
     if (blocks >= (1l << 31)) return WGRAD_UNSUPPORTED;
     t.begin[n] = (int)blocks;
@@ -131,7 +163,7 @@ int launch_random_table(float *const *dW, const long *elems, const uint64_t *off
 
 int launch_random(float *dW, long elems, float sigma, uint64_t seed, uint64_t offset, hipStream_t st)
 {
-    WGRAD_LAUNCH(fill_normal, dim3((unsigned)((elems + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
+    WGRAD_LAUNCH(fill_normal, dim3((unsigned)((normal_calls(elems, offset) + kBlock - 1) / kBlock)), dim3(kBlock), 0, st,
                        dW, elems, sigma, seed, offset);
     return launch_status();
 }

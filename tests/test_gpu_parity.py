@@ -173,12 +173,22 @@ def test_random_gradient_matches_oracle_stream_value_by_value():
     d = B.desc(1, 64, 8, 8, 129)                      # 74304 values
     n = d.K * d.C * 9
     sigma, seed = 1 / 128, 190805460
-    for offset in (0, 12345, (1 << 32) - 1000):
+    # four stream positions share a generator call: offsets in every residue mod 4, and across the 2^32 counter boundary
+    for offset in (0, 12345, 2, 7, (1 << 32) - 1000, (1 << 34) - 1001):
         dW = torch.empty((d.K, d.C, 3, 3), device="cuda")
         B.conv_wgrad_random(d, dW, sigma, seed, offset)
         want = oracle.random_normal(seed, offset, n, sigma)
         got = dW.cpu().numpy().ravel().astype(np.float64)
-        assert np.abs(got - want).max() <= 2e-5 * sigma          # fp32 log/sqrt/cos vs fp64
+        assert np.abs(got - want).max() <= 2e-5 * sigma          # fp32 log/sqrt/sin/cos vs fp64
+    # tensors smaller than a call, and a tensor that is only element-aligned, with a guard element on either side
+    for (K, C), offset in (((1, 1), 3), ((1, 1), 0), ((2, 1), 1), ((7, 3), 6)):
+        t = B.desc(1, C, 8, 8, K)
+        m = K * C * 9
+        buf = torch.full((m + 2,), 7.0, device="cuda")
+        B.conv_wgrad_random(t, buf[1:m + 1].view(K, C, 3, 3), sigma, seed, offset)
+        got = buf.cpu().numpy().astype(np.float64)
+        assert got[0] == 7.0 and got[-1] == 7.0
+        assert np.abs(got[1:-1] - oracle.random_normal(seed, offset, m, sigma)).max() <= 2e-5 * sigma
     a = torch.empty((d.K, d.C, 3, 3), device="cuda"); b = torch.empty_like(a)
     B.conv_wgrad_random(d, a, sigma, seed, 0); B.conv_wgrad_random(d, b, sigma, seed, n)
     assert not torch.equal(a, b)                      # a new batch (advanced offset) draws new numbers
