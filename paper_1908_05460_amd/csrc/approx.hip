@@ -249,6 +249,29 @@ __global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch
     int hw_next = 0;
     float sv_next = 0.f;
 
+    // This thread's staging slots, decoded once: slot u is the 16-byte piece e = tid + u * kGatherBlock of a group
+    // (image e / run4 of the group, then channel, then four consecutive elements of the plane).
+    //   slot_src: element offset of the piece from the first image of a group
+    //   slot_dst: float index of its first element in a window buffer | image within the group << 20; -1 = none
+    // The four elements go to dst + {0,1,2,3} when a plane row holds a multiple of four (rowmode 0), to
+    // dst + {0,1,WP,WP+1} for rows of two (rowmode 1); any other width takes the divisions per element (rowmode 2).
+    const int rowmode = g.W % 4 == 0 ? 0 : (g.W == 2 ? 1 : 2);
+    uint32_t slot_src[kGatherSlots];
+    int slot_dst[kGatherSlots];
+#pragma unroll
+    for (int u = 0; u < kGatherSlots; ++u) {
+        const int e = tid + u * kGatherBlock;
+        slot_src[u] = 0; slot_dst[u] = -1;
+        if (e < nb * run4) {
+            uint32_t n_l, rem, c_l, q4, ih, iw;
+            d_run4.divmod(e, n_l, rem);
+            gp.d_hw4.divmod(rem, c_l, q4);
+            gp.d_w.divmod(q4 * 4, ih, iw);
+            slot_src[u] = n_l * (uint32_t)(g.C * HW) + rem * 4;
+            slot_dst[u] = (int)((n_l * kGatherCT + c_l) * pitch + (g.ph + ih) * WP + g.pw + iw) | (int)(n_l << 20);
+        }
+    }
+
     // issue the loads of the group starting at image n0 (registers only)
     auto prefetch = [&](int n0) {
         // lane l of every wavefront: map (image n0 + l / M, channel k_base + l % M).  Issued before
@@ -267,17 +290,13 @@ __global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch
             sv_next = ok ? sum[(long)n * g.K + k] : 0.f;
         }
         const int nb_cur = n_end - n0 < nb ? n_end - n0 : nb;
-        const int total = nb_cur * run4;
+        const long base = ((long)n0 * g.C + c0) * HW;
 #pragma unroll
-        for (int u = 0; u < kGatherSlots; ++u) {
-            const int e = tid + u * kGatherBlock;
-            if (e < total) {
-                uint32_t n_l, rem;
-                d_run4.divmod(e, n_l, rem);
-                const long src = ((long)(n0 + n_l) * g.C + c0) * HW + (long)rem * 4;
+        for (int u = 0; u < kGatherSlots; ++u)
+            if (slot_dst[u] >= 0 && (slot_dst[u] >> 20) < nb_cur) {
+                const long src = base + slot_src[u];
                 xr[u] = BF16 ? *(const raw4 *)((const uint16_t *)X + src) : *(const raw4 *)((const float *)X + src);
             }
-        }
     };
 
     prefetch(n_begin);
@@ -287,14 +306,9 @@ __global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch
         float *buf = xs + parity * buf_floats;
         if (n0 == n_begin) __syncthreads();               // the zero fill is complete
         {   // registers -> LDS (interior of the haloed planes)
-            const int total = nb_cur * run4;
 #pragma unroll
-            for (int u = 0; u < kGatherSlots; ++u) {
-                const int e = tid + u * kGatherBlock;
-                if (e < total) {
-                    uint32_t n_l, rem, c_l, q4;
-                    d_run4.divmod(e, n_l, rem);
-                    gp.d_hw4.divmod(rem, c_l, q4);
+            for (int u = 0; u < kGatherSlots; ++u)
+                if (slot_dst[u] >= 0 && (slot_dst[u] >> 20) < nb_cur) {
                     float v[4];
                     if (BF16) {
                         const uint2 r = *(const uint2 *)&xr[u];
@@ -304,15 +318,23 @@ __global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch
                         const float4 r = *(const float4 *)&xr[u];
                         v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
                     }
-                    float *dst = buf + (n_l * kGatherCT + c_l) * pitch + g.ph * WP + g.pw;
+                    float *dst = buf + (slot_dst[u] & 0xfffff);
+                    if (rowmode == 0) {
+                        dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
+                    } else if (rowmode == 1) {
+                        dst[0] = v[0]; dst[1] = v[1]; dst[WP] = v[2]; dst[WP + 1] = v[3];
+                    } else {
+                        // dst is the cell of the piece's first element: walk on from its column
+                        const int cell0 = (slot_dst[u] & 0xfffff) % pitch;          // offset inside the haloed plane
+                        int iw = (cell0 % WP) - g.pw;
+                        float *q = dst;
 #pragma unroll
-                    for (int i = 0; i < 4; ++i) {
-                        uint32_t ih, iw;
-                        gp.d_w.divmod(q4 * 4 + i, ih, iw);
-                        dst[ih * WP + iw] = v[i];
+                        for (int i = 0; i < 4; ++i) {
+                            *q = v[i];
+                            if (++iw == g.W) { iw = 0; q += WP - g.W + 1; } else ++q;
+                        }
                     }
                 }
-            }
         }
         // Copy through an opaque move: it makes the wait for these two loads happen here, where
         // they have long arrived, instead of at their first use below, after the next group's
@@ -770,7 +792,7 @@ int fused_flush(FusedQueue &q, hipStream_t st)
 #define WGRAD_APPROX_THREADS (256 * 1024)
 #endif
 #ifndef WGRAD_GATHER_BLOCKS    // workgroups to aim for (LDS form)
-#define WGRAD_GATHER_BLOCKS 256
+#define WGRAD_GATHER_BLOCKS 512
 #endif
 
 ApproxPlan plan_approx(const Geometry &g, bool allow_lds, bool allow_fused, bool allow_mm)
@@ -949,6 +971,16 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         aligned = aligned && ((uintptr_t)b.X[i] % (g.bf16 ? 8 : 16)) == 0 && ((uintptr_t)b.dY[i] % (g.bf16 ? 8 : 16)) == 0;
     ApproxPlan pl = ((plan.use_lds || plan.fused || plan.mm) && !aligned) ? plan_approx(g, false, false, false) : plan;
     const long outs = g.dw_elems();
+    if (pl.use_lds && b.n > 1) {
+        // the workgroup target is for the whole launch: a batch of layers chunks each layer's images less finely
+        const long tiles = (long)pl.ctiles * pl.ktiles * b.n;
+        const int want_blocks = tune_int("WGRAD_GATHER_BLOCKS", WGRAD_GATHER_BLOCKS);
+        long chunks = tiles >= want_blocks ? 1 : (want_blocks + tiles - 1) / tiles;
+        if (chunks < pl.chunks) {       // never more than planned: the workspace holds pl.chunks partials
+            pl.chunk_n = (int)((g.N + chunks - 1) / chunks);
+            pl.chunks = (g.N + pl.chunk_n - 1) / pl.chunk_n;
+        }
+    }
     if (pl.fused && (b.n > 1 || fq)) {
         long chunks;
         if (fq) {

@@ -34,6 +34,8 @@ SMALL = [
     (12, 32, 16, 16, 64, 3, 3, 1, 1, 1, 1),
     (24, 128, 8, 8, 192, 3, 3, 1, 1, 1, 1),     # several K tiles and channel tiles, four images per tile
     (33, 16, 4, 4, 64, 3, 3, 1, 1, 1, 1),       # 4x4 planes, a ragged last image group
+    (5, 32, 6, 6, 144, 3, 3, 1, 1, 1, 1),       # 6x6 planes: a 16-byte piece of a plane wraps over rows (LDS gather)
+    (9, 70, 2, 6, 130, 3, 3, 1, 1, 1, 1),       # 2x6 planes, ragged channel tile
 ]
 
 
