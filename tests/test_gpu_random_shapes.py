@@ -1,0 +1,62 @@
+"""Seeded random convolution shapes (filters 1..5, strides 1..3, paddings, odd sizes, both element types)
+through every entry point, against the oracle: selected positions bit-exact, gradients within tolerance."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1908_05460_amd import binding as B
+from tests.gpu_util import TOL, check_select, normwise_err, oracle_shape, rand_inputs, to_gpu
+
+pytestmark = pytest.mark.gpu
+
+
+def random_cases(seed, count):
+    rng = np.random.default_rng(seed)
+    out = []
+    while len(out) < count:
+        R = int(rng.choice([1, 2, 3, 3, 3, 5])); S = int(rng.choice([1, 2, 3, 3, 3, 4]))
+        sh = int(rng.choice([1, 1, 1, 2, 3])); sw = int(rng.choice([1, 1, 1, 2]))
+        ph = int(rng.integers(0, R)); pw = int(rng.integers(0, S))
+        H = int(rng.integers(max(1, R - 2 * ph), 20)); W = int(rng.integers(max(1, S - 2 * pw), 20))
+        if rng.random() < 0.3:
+            H = W = int(rng.choice([2, 4, 6, 8, 16]))
+        C = int(rng.choice([1, 3, 5, 16, 24, 32, 48, 64, 80, 128]))
+        K = int(rng.choice([1, 7, 16, 32, 64, 96, 128, 144, 256]))
+        N = int(rng.integers(1, 40))
+        dtype = "bf16" if rng.random() < 0.4 else "fp32"
+        k = int(rng.integers(1, 6)); layout = int(rng.integers(0, 3))
+        if H + 2 * ph < R or W + 2 * pw < S:
+            continue
+        Ho, Wo = (H + 2 * ph - R) // sh + 1, (W + 2 * pw - S) // sw + 1
+        if N * K * Ho * Wo * C * R * S > 2e8:
+            continue
+        out.append(pytest.param((N, C, H, W, K, R, S, sh, sw, ph, pw), dtype, min(k, Ho * Wo), layout,
+                                id=f"N{N}C{C}H{H}W{W}K{K}R{R}S{S}s{sh}{sw}p{ph}{pw}-{dtype}"))
+    return out
+
+
+@pytest.mark.parametrize("t,dtype,k,layout", random_cases(20190805, 48))
+def test_every_entry_point_on_a_random_shape(t, dtype, k, layout):
+    import torch
+    N, C, H, W, K, R, S, sh, sw, ph, pw = t
+    d = B.desc(N, C, H, W, K, R=R, S=S, stride=sh, pad=ph, stride_w=sw, pad_w=pw, dtype=B.BF16 if dtype == "bf16" else B.F32)
+    X, dY = rand_inputs(d, N * 1000 + K, dtype)
+    g = oracle_shape(d)
+    Xg, dYg = to_gpu(X), to_gpu(dY)
+    assert normwise_err(B.conv_wgrad_exact(d, Xg, dYg).cpu().numpy(), oracle.wgrad_exact(g, X, dY)) <= TOL[dtype]
+    idx = torch.empty((d.N, d.K), dtype=torch.int32, device="cuda")
+    sums = torch.empty((d.N, d.K), dtype=torch.float32, device="cuda")
+    got = B.conv_wgrad_approx(d, Xg, dYg, scale=0.5, idx_out=idx, sum_out=sums).cpu().numpy()
+    check_select(d, dY, idx.cpu().numpy(), sums.cpu().numpy())
+    assert normwise_err(got, oracle.wgrad_approx(g, X, dY, scale=0.5)[0]) <= TOL[dtype]
+    idk = torch.empty((d.N, d.K, k), dtype=torch.int32, device="cuda")
+    got = B.conv_wgrad_approx_topk(d, Xg, dYg, k, idx_out=idk).cpu().numpy()
+    want, want_idx, _ = oracle.wgrad_approx_topk(g, X, dY, k)
+    assert np.array_equal(idk.cpu().numpy(), want_idx)
+    assert normwise_err(got, want) <= TOL[dtype]
+    Xl = oracle.x_to_nhwc(X)
+    Xlg = to_gpu(Xl)
+    assert normwise_err(B.conv_wgrad_approx_nhwc(d, Xlg, dYg, layout).cpu().numpy(),
+                        oracle.wgrad_approx_nhwc(g, Xl, dY, 1.0, layout)[0]) <= TOL[dtype]
+    assert normwise_err(B.conv_wgrad_exact_nhwc(d, Xlg, dYg, layout).cpu().numpy(),
+                        oracle.wgrad_exact_nhwc(g, Xl, dY, layout)) <= TOL[dtype]
