@@ -60,3 +60,44 @@ def test_every_entry_point_on_a_random_shape(t, dtype, k, layout):
                         oracle.wgrad_approx_nhwc(g, Xl, dY, 1.0, layout)[0]) <= TOL[dtype]
     assert normwise_err(B.conv_wgrad_exact_nhwc(d, Xlg, dYg, layout).cpu().numpy(),
                         oracle.wgrad_exact_nhwc(g, Xl, dY, layout)) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_random_stack_and_mask_through_schedule_run(seed):
+    """A random stack (up to 44 layers drawn from a few shapes, so that groups of more than eight layers, more than six
+    groups and more than 32 reductions occur) under a random method mask, every layer against the oracle."""
+    import torch
+    from paper_1908_05460_amd import schedule as sch
+    rng = np.random.default_rng(4000 + seed)
+    dtype = "bf16" if seed % 3 == 2 else "fp32"
+    N = int(rng.integers(2, 24))
+    pool = []
+    while len(pool) < int(rng.integers(1, 9)) or not pool:
+        hw = int(rng.choice([2, 4, 8, 16, 32, 7]))
+        C = int(rng.choice([3, 16, 32, 64])); K = int(rng.choice([16, 32, 64, 128]))
+        st = int(rng.choice([1, 1, 2])) if hw >= 8 else 1
+        if N * K * hw * hw * C * 9 <= 6e7:
+            pool.append((C, hw, K, st))
+    nl = int(rng.integers(1, 45))
+    layers = [pool[int(rng.integers(0, len(pool)))] for _ in range(nl)]
+    methods = rng.integers(0, 4, nl).astype(np.uint8)
+    descs = [B.desc(N, C, hw, hw, K, stride=st, dtype=B.BF16 if dtype == "bf16" else B.F32) for (C, hw, K, st) in layers]
+    data = [rand_inputs(d, 100 * seed + i, dtype) for i, d in enumerate(descs)]
+    dWs = [torch.full((d.K, d.C, 3, 3), float("nan"), device="cuda") for d in descs]
+    s = B.Schedule(descs, [to_gpu(x) for x, _ in data], [to_gpu(y) for _, y in data], dWs)
+    ws = B.alloc_workspace(s.workspace_bytes(methods))
+    rseed, offset, sigma, scale = 77 + seed, int(rng.integers(0, 1 << 20)), 1 / 128, 0.25
+    s.run(methods, ws, scale=scale, sigma=sigma, seed=rseed, offset=offset)
+    off = offset
+    for i, d in enumerate(descs):
+        got = dWs[i].cpu().numpy()
+        g = oracle_shape(d)
+        if methods[i] == sch.EXACT:
+            assert normwise_err(got, oracle.wgrad_exact(g, *data[i])) <= TOL[dtype], (i, layers[i])
+        elif methods[i] == sch.APPROX:
+            assert normwise_err(got, oracle.wgrad_approx(g, *data[i], scale=scale)[0]) <= TOL[dtype], (i, layers[i])
+        elif methods[i] == sch.ZERO:
+            assert not got.any(), (i, layers[i])
+        else:
+            assert np.abs(got.ravel() - oracle.random_normal(rseed, off, got.size, sigma)).max() <= 2e-5 * sigma, (i, layers[i])
+        off += got.size
