@@ -281,6 +281,9 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
     int napprox = 0;
     for (int i = 0; i < nlayers; ++i) napprox += method[i] == WGRAD_APPROX && group[i] == i;
     FusedQueue *fq = napprox > 1 && tune_int("WGRAD_FUSED_MULTI", 1) ? fused_queue_new() : nullptr;
+    // groups that run on the bf16 matrix core (exact ones, and approximated ones through the sparse operand)
+    // are collected for launches that carry several shapes
+    Bf16Queue *bq = tune_int("WGRAD_BF16_MULTI", 1) ? bf16_queue_new() : nullptr;
     char *ws_next = (char *)ws;
     int rc = WGRAD_OK;
     for (int i = 0; i < nlayers && rc == WGRAD_OK; ++i) {
@@ -294,12 +297,16 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
             int share = 0;
             // 768 in all: three per CU, all resident at once, so a workgroup's fixed cost is paid once per CU slot
             if (mq) share = (int)(tune_int("WGRAD_MULTI_TOTAL", 768) * group_flops(i) / exact_flops + 0.5);
-            rc = launch_exact(g, plan_exact(g), b, ws_next, st, &queue, mq, share < 8 ? 8 : share);
+            rc = launch_exact(g, plan_exact(g), b, ws_next, st, &queue, mq, share < 8 ? 8 : share, bq);
         }
-        else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue, fq);
+        else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue, fq, bq);
         ws_next += align_up(method_ws(g, method[i])) * b.n;
     }
     if (rc == WGRAD_OK && mq) rc = multi_flush(multi, st);
+    if (bq) {
+        if (rc == WGRAD_OK) rc = bf16_flush(*bq, st);
+        bf16_queue_delete(bq);
+    }
     if (fq) {
         if (rc == WGRAD_OK) rc = fused_flush(*fq, st);
         fused_queue_delete(fq);

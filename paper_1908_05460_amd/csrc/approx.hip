@@ -964,7 +964,8 @@ bool topk_gather_lds(const Geometry &g, const void *X, const int32_t *hw, const 
 }
 
 int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, float scale,
-                  int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer, FusedQueue *fq)
+                  int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer, FusedQueue *fq,
+                  Bf16Queue *bq)
 {
     bool aligned = true;
     for (int i = 0; i < b.n; ++i)
@@ -1027,7 +1028,7 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
             out[i] = ex.splits > 1 ? (float *)((char *)ws + (size_t)i * plan.ws_bytes + pl.off_part) : b.dW[i];
         }
         sp.scale = ex.splits > 1 ? 1.0f : scale;
-        rc = launch_exact_bf16(g, ex, b, out, st, &sp);
+        rc = launch_exact_bf16(g, ex, b, out, st, &sp, bq);
         if (rc != WGRAD_OK) return rc;
         if (ex.splits > 1)
             return launch_combine((const float *)((char *)ws + pl.off_part), prob_stride, ex.splits, outs, scale, b.dW, b.n, st, defer);

@@ -99,11 +99,16 @@ struct SparseA {
     const float *sum[kMaxBatch];
     float scale;                     // applied by the kernel when it writes dW itself (one split)
 };
+// launches of the bf16 matrix-core kernel collected for one launch that carries several shapes
+struct Bf16Queue;
+Bf16Queue *bf16_queue_new();
+void bf16_queue_delete(Bf16Queue *q);
+int bf16_flush(Bf16Queue &q, hipStream_t st);
 int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st,
-                      const SparseA *sparse = nullptr);
+                      const SparseA *sparse = nullptr, Bf16Queue *queue = nullptr);
 struct CombineQueue;
 int launch_exact(const Geometry &g, const ExactPlan &pl, const Batch &b, void *ws, hipStream_t st,
-                 CombineQueue *defer = nullptr, MultiQueue *mq = nullptr, int mq_blocks = 0);
+                 CombineQueue *defer = nullptr, MultiQueue *mq = nullptr, int mq_blocks = 0, Bf16Queue *bq = nullptr);
 int choose_splits(const ExactPlan &pl, int nprob, int want_blocks = 0);
 size_t exact_ws_per_problem(const Geometry &g, const ExactPlan &pl);
 
@@ -119,7 +124,7 @@ struct FusedQueue;
 int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, hipStream_t st);
 int launch_approx(const Geometry &g, const ApproxPlan &pl, const Batch &b, float scale,
                   int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer = nullptr,
-                  FusedQueue *fq = nullptr);
+                  FusedQueue *fq = nullptr, Bf16Queue *bq = nullptr);
 // groups of layers that the fused approximation kernel takes, collected for one launch
 FusedQueue *fused_queue_new();
 void fused_queue_delete(FusedQueue *q);

@@ -83,11 +83,109 @@ static void bf16_inst(const Bf16Params &p, int grid, size_t lds, hipStream_t st)
     }
 }
 
-// Enqueues the kernel (not the combine); the caller has checked pointer alignment (16 bytes).
-int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st,
-                      const SparseA *sparse)
+static int bf16_launch_now(const Bf16Launch &L, hipStream_t st)
 {
-    Bf16Params p{};
+    if (L.gpw == 2 && L.rowp == 4) bf16_inst<2, 4>(L.p, L.grid, L.lds, st);
+    else if (L.gpw == 2 && L.rowp == 12) bf16_inst<2, 12>(L.p, L.grid, L.lds, st);
+    else if (L.gpw == 2 && L.rowp == 20) bf16_inst<2, 20>(L.p, L.grid, L.lds, st);
+    else if (L.gpw == 2 && L.rowp == 36) bf16_inst<2, 36>(L.p, L.grid, L.lds, st);
+    else if (L.gpw == 1 && L.rowp == 8) bf16_inst<1, 8>(L.p, L.grid, L.lds, st);
+    else return WGRAD_UNSUPPORTED;
+    return launch_status();
+}
+
+// ---- one launch for several shapes: the groups of a run each fill the chip once (512 workgroups, all resident), so
+//      back to back every group pays its ramp and its tail with most of the chip idle; as one grid, the workgroups of
+//      the next group start as those of the current one finish.  A workgroup looks its group up in the kernel arguments
+//      (read through the kernel-argument segment pointer: indexing the by-value argument with a run-time group number
+//      would make the compiler copy all of it to scratch memory) and runs that group's instantiation of the body. ----
+struct Bf16Multi {
+    int n;
+    int begin[kBf16MultiMax + 1];    // first workgroup of each group (multiples of 8: the XCD numbering of a group
+                                     // then starts on XCD 0); begin[n] = grid size
+    int count[kBf16MultiMax];        // workgroups of the group
+    int variant[kBf16MultiMax];
+    Bf16Params p[kBf16MultiMax];
+};
+static_assert(sizeof(Bf16Multi) <= 4096, "kernel arguments");
+
+// (id, GPW, ROWP, FULL)
+#define WGRAD_BF16_VARIANTS(X) \
+    X(0, 2, 4, false) X(1, 2, 4, true) X(2, 2, 12, false) X(3, 2, 12, true) X(4, 2, 20, false) X(5, 2, 20, true) \
+    X(6, 2, 36, false) X(7, 2, 36, true) X(8, 1, 8, false) X(9, 1, 8, true)
+
+static int bf16_variant(int gpw, int rowp, int full)
+{
+#define X(ID, GPW, ROWP, FULL) if (gpw == GPW && rowp == ROWP && (full != 0) == FULL) return ID;
+    WGRAD_BF16_VARIANTS(X)
+#undef X
+    return -1;
+}
+
+template <bool SPARSE>
+__global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16_multi(const Bf16Multi)
+{
+    extern __shared__ float smem[];
+    const Bf16Multi *mp = (const Bf16Multi *)__builtin_amdgcn_kernarg_segment_ptr();
+    const int n = mp->n;
+    int gi = 0;
+    for (int i = 1; i < n; ++i) gi += (int)blockIdx.x >= mp->begin[i];
+    const int bid = (int)blockIdx.x - mp->begin[gi], nblk = mp->count[gi];
+    if (bid >= nblk) return;
+    const Bf16Params &p = mp->p[gi];
+    switch (mp->variant[gi]) {
+#define X(ID, GPW, ROWP, FULL) case ID: bf16_body<GPW, ROWP, FULL, ROWP == 4, SPARSE>(p, smem, bid, nblk); break;
+        WGRAD_BF16_VARIANTS(X)
+#undef X
+        default: break;
+    }
+}
+
+Bf16Queue *bf16_queue_new() { return new Bf16Queue(); }
+void bf16_queue_delete(Bf16Queue *q) { delete q; }
+
+int bf16_flush(Bf16Queue &q, hipStream_t st)
+{
+    if (q.n == 0) return WGRAD_OK;
+    if (q.n == 1) {
+        q.n = 0;
+        return bf16_launch_now(q.item[0], st);
+    }
+    Bf16Multi m{};
+    m.n = q.n;
+    size_t lds = 0;
+    int blocks = 0;
+    for (int i = 0; i < q.n; ++i) {
+        const Bf16Launch &L = q.item[i];
+        m.begin[i] = blocks;
+        m.count[i] = L.grid;
+        m.variant[i] = bf16_variant(L.gpw, L.rowp, L.full);
+        m.p[i] = L.p;
+        blocks += (L.grid + 7) / 8 * 8;
+        if (L.lds > lds) lds = L.lds;
+    }
+    m.begin[q.n] = blocks;
+    const bool sparse = q.sparse;
+    q.n = 0;
+    if (sparse) {
+        if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)wgrad_exact_bf16_multi<true>,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return WGRAD_LAUNCH_FAILED;
+        WGRAD_LAUNCH((wgrad_exact_bf16_multi<true>), dim3((unsigned)blocks), dim3(kBlock), lds, st, m);
+    } else {
+        if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)wgrad_exact_bf16_multi<false>,
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return WGRAD_LAUNCH_FAILED;
+        WGRAD_LAUNCH((wgrad_exact_bf16_multi<false>), dim3((unsigned)blocks), dim3(kBlock), lds, st, m);
+    }
+    return launch_status();
+}
+
+// Enqueues the kernel (not the combine); the caller has checked pointer alignment (16 bytes).  With a queue the
+// launch is only recorded there (bf16_flush issues it, together with the others recorded).
+int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st,
+                      const SparseA *sparse, Bf16Queue *queue)
+{
+    Bf16Launch L{};
+    Bf16Params &p = L.p;
     for (int i = 0; i < kMaxBatch; ++i) {          // unused slots repeat problem 0
         const int j = i < b.n ? i : 0;
         p.X[i] = b.X[j]; p.dY[i] = b.dY[j]; p.out[i] = out[j];
@@ -108,14 +206,18 @@ int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, fl
     p.d_seg = FastDiv(p.seg);
     p.d_wo = FastDiv(g.Wo);
     p.d_htiles = FastDiv(pl.h_tiles);
-    const int grid = pl.ktiles * pl.ctiles * pl.splits * b.n;
-    if (pl.gpw == 2 && pl.rowp == 4) bf16_inst<2, 4>(p, grid, pl.lds_bytes, st);
-    else if (pl.gpw == 2 && pl.rowp == 12) bf16_inst<2, 12>(p, grid, pl.lds_bytes, st);
-    else if (pl.gpw == 2 && pl.rowp == 20) bf16_inst<2, 20>(p, grid, pl.lds_bytes, st);
-    else if (pl.gpw == 2 && pl.rowp == 36) bf16_inst<2, 36>(p, grid, pl.lds_bytes, st);
-    else if (pl.gpw == 1 && pl.rowp == 8) bf16_inst<1, 8>(p, grid, pl.lds_bytes, st);
-    else return WGRAD_UNSUPPORTED;
-    return launch_status();
+    L.gpw = pl.gpw; L.rowp = pl.rowp; L.full = pl.q == 128 * pl.gpw;
+    L.grid = pl.ktiles * pl.ctiles * pl.splits * b.n;
+    L.lds = pl.lds_bytes;
+    if (bf16_variant(L.gpw, L.rowp, L.full) < 0) return WGRAD_UNSUPPORTED;
+    if (!queue) return bf16_launch_now(L, st);
+    if (queue->n == kBf16MultiMax || (queue->n > 0 && queue->sparse != (sparse != nullptr))) {
+        const int rc = bf16_flush(*queue, st);
+        if (rc != WGRAD_OK) return rc;
+    }
+    queue->sparse = sparse != nullptr;
+    queue->item[queue->n++] = L;
+    return WGRAD_OK;
 }
 
 #if defined(WGRAD_TUNING) && !defined(WGRAD_NO_TRACE)

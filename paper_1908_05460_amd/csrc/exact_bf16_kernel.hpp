@@ -69,14 +69,15 @@ __host__ __device__ constexpr int bf16_xslots(int gpw, int rowp) { return rowp >
 // elsewhere.  Nothing of dY is read.
 // P4: 2x2 planes (H = W = 2).  A map is four elements, so a lane's eight positions are two images
 // (two 8-byte loads of dY), and an input plane is staged whole: one 8-byte piece per (image, channel).
+// The body takes the workgroup's number `bid` among the `nblk` workgroups of its launch (or of its group in
+// a launch that carries several shapes) and the dynamic LDS.
 template <int GPW, int ROWP, bool FULL, bool P4, bool SPARSE>
-__global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p)
+__device__ __forceinline__ void bf16_body(const Bf16Params &p, float *smem, int bid, int nblk)
 {
     constexpr int MT = kBf16MT, KT = kBf16KT, NT = 9, NCB = NT * 16;
     constexpr bool ROW8 = ROWP >= 12;                   // map rows of 8, 16 or 32: a lane's eight positions share a row
     constexpr int QT = 128 * GPW;
     constexpr int XS = bf16_xslots(GPW, ROWP), XV = bf16_xv(ROWP);
-    extern __shared__ float smem[];
     uint32_t *Xs0 = (uint32_t *)smem;                   // [2][buf_words]
     int *xoffp = (int *)(Xs0 + 2 * p.buf_words);        // [QT / 2] byte offsets of position pairs
 
@@ -85,7 +86,7 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
     const int i16 = lane & 15, kk = lane >> 4;
     const int L = g.Ho * g.Wo, CRS = g.C * 9;
 
-    const int logical_all = xcd_contiguous_id(blockIdx.x, gridDim.x);
+    const int logical_all = xcd_contiguous_id(bid, nblk);
     const int prob = logical_all / p.per_prob;
     const int logical = logical_all - prob * p.per_prob;
     const char *const Xp = (const char *)p.X[prob];
@@ -440,5 +441,24 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p
     TRACE(10);
     TRACE_BLK(1);
 }
+
+template <int GPW, int ROWP, bool FULL, bool P4, bool SPARSE>
+__global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16(const Bf16Params p)
+{
+    extern __shared__ float smem[];
+    bf16_body<GPW, ROWP, FULL, P4, SPARSE>(p, smem, blockIdx.x, gridDim.x);
+}
+
+// A prepared launch, and a queue of them for one launch that carries several shapes.
+constexpr int kBf16MultiMax = 6;        // groups per launch (their parameters are kernel arguments, 4 KB at most)
+struct Bf16Launch {
+    Bf16Params p;
+    int gpw, rowp, full, grid;
+    size_t lds;
+};
+struct Bf16Queue {
+    int n = 0, sparse = 0;
+    Bf16Launch item[kBf16MultiMax];
+};
 
 }  // namespace wgrad

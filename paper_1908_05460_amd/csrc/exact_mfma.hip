@@ -618,7 +618,7 @@ static int launch_exact_staged(const Geometry &g, const ExactPlan &pl, const voi
                                void *ws, hipStream_t st, CombineQueue *defer);
 
 int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void *ws, hipStream_t st, CombineQueue *defer,
-                 MultiQueue *mq, int mq_blocks)
+                 MultiQueue *mq, int mq_blocks, Bf16Queue *bq)
 {
     if ((plan.stream || plan.mm16) && batch_aligned(g, b, plan.xv, plan.mm16 ? 8 : 4)) {
         // one launch for the whole batch; problem i owns the i-th slice of the workspace.  The
@@ -637,7 +637,7 @@ int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void 
         float *out[kMaxBatch];
         const long prob_stride = (long)pl.splits * g.dw_elems();
         for (int i = 0; i < b.n; ++i) out[i] = pl.splits > 1 ? (float *)ws + i * prob_stride : b.dW[i];
-        int rc = pl.mm16 ? launch_exact_bf16(g, pl, b, out, st) : launch_exact_stream(g, pl, b, out, st, mq);
+        int rc = pl.mm16 ? launch_exact_bf16(g, pl, b, out, st, nullptr, bq) : launch_exact_stream(g, pl, b, out, st, mq);
         if (rc != WGRAD_OK) return rc;
         if (pl.splits > 1)
             return launch_combine((const float *)ws, prob_stride, pl.splits, g.dw_elems(), 1.0f, b.dW, b.n, st, defer);
