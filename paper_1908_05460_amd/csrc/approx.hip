@@ -37,6 +37,45 @@ __device__ __forceinline__ uint32_t mag_key(uint32_t bits)   // bits of the valu
     return m > 0x7f800000u ? 0u : m;
 }
 
+// Reductions over the 64 lanes of a wavefront with data-parallel-primitive moves (no LDS, a few cycles per step):
+// an inclusive scan inside each row of 16 lanes (shifts by 1, 2, 4, 8), then lane 15 of row 0 is folded into row 1 and
+// of row 2 into row 3 (row_bcast:15), then lane 31 into rows 2 and 3 (row_bcast:31); lane 63 holds the result, which is
+// returned as a wavefront-uniform value.  Lanes without a source keep the identity (0 for both operations used here).
+// All 64 lanes must be active.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ uint32_t dpp_move(uint32_t v)
+{
+    return (uint32_t)__builtin_amdgcn_update_dpp(0, (int)v, CTRL, ROW_MASK, 0xf, false);
+}
+__device__ __forceinline__ uint32_t wave_max_u32(uint32_t v)
+{
+    v = max(v, dpp_move<0x111, 0xf>(v));     // row_shr:1
+    v = max(v, dpp_move<0x112, 0xf>(v));     // row_shr:2
+    v = max(v, dpp_move<0x114, 0xf>(v));     // row_shr:4
+    v = max(v, dpp_move<0x118, 0xf>(v));     // row_shr:8
+    v = max(v, dpp_move<0x142, 0xa>(v));     // row_bcast:15 into rows 1 and 3
+    v = max(v, dpp_move<0x143, 0xc>(v));     // row_bcast:31 into rows 2 and 3
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+__device__ __forceinline__ float wave_sum_f32(float v)
+{
+    v += __uint_as_float(dpp_move<0x111, 0xf>(__float_as_uint(v)));
+    v += __uint_as_float(dpp_move<0x112, 0xf>(__float_as_uint(v)));
+    v += __uint_as_float(dpp_move<0x114, 0xf>(__float_as_uint(v)));
+    v += __uint_as_float(dpp_move<0x118, 0xf>(__float_as_uint(v)));
+    v += __uint_as_float(dpp_move<0x142, 0xa>(__float_as_uint(v)));
+    v += __uint_as_float(dpp_move<0x143, 0xc>(__float_as_uint(v)));
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 63));
+}
+// The largest (magnitude key, inverted position) pair of the wavefront, lexicographically: first the largest key, then,
+// among the lanes that hold it, the largest inverted position (the smallest position).  A lane without a candidate
+// passes (0, 0); a real inverted position is never 0.
+__device__ __forceinline__ void wave_max_pair(uint32_t key, uint32_t inv_pos, uint32_t &key_max, uint32_t &inv_pos_max)
+{
+    key_max = wave_max_u32(key);
+    inv_pos_max = wave_max_u32(key == key_max ? inv_pos : 0u);
+}
+
 // Per-problem pointers of a batched approximation launch (problem = blockIdx.y or .z).
 struct ApproxBatch {
     const void *X[kMaxBatch];
@@ -554,15 +593,11 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
                         }
                     }
                 }
-#pragma unroll
-                for (int d = 32; d > 0; d >>= 1) {
-                    const unsigned long long other = __shfl_xor(best, d, 64);
-                    best = other > best ? other : best;
-                    if (t == 0) sum += __shfl_xor(sum, d, 64);
-                }
-                if (t == 0) S = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sum)));
-                const int pos = __builtin_amdgcn_readfirstlane((int)~(uint32_t)best);
-                below = best;
+                uint32_t key_max, inv_pos_max;
+                wave_max_pair((uint32_t)(best >> 32), (uint32_t)best, key_max, inv_pos_max);
+                if (t == 0) S = wave_sum_f32(sum);
+                const int pos = (int)~inv_pos_max;
+                below = ((unsigned long long)key_max << 32) | inv_pos_max;
                 if (lane == 0) {
                     if (fp.flat_out) fp.flat_out[((long)n * g.K + k) * fp.tk + t] = pos;
                     if (fp.sum_out && t == 0) fp.sum_out[(long)n * g.K + k] = S;
@@ -599,16 +634,10 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
             }
         }
         if (n + 4 < n_end) load_map(n + 4, cur);
-        unsigned long long packed = have ? ((unsigned long long)best_key << 32) | (uint32_t)~best_pos : 0ull;
-#pragma unroll
-        for (int d = 32; d > 0; d >>= 1) {
-            const unsigned long long other = __shfl_xor(packed, d, 64);
-            const float osum = __shfl_xor(sum, d, 64);
-            packed = other > packed ? other : packed;
-            sum += osum;
-        }
-        const int pos = __builtin_amdgcn_readfirstlane((int)~(uint32_t)packed);
-        const float S = __builtin_bit_cast(float, __builtin_amdgcn_readfirstlane(__builtin_bit_cast(int, sum)));
+        uint32_t key_max, inv_pos_max;
+        wave_max_pair(have ? best_key : 0u, have ? ~best_pos : 0u, key_max, inv_pos_max);
+        const int pos = (int)~inv_pos_max;
+        const float S = wave_sum_f32(sum);
         if (lane == 0) {
             if (fp.flat_out) fp.flat_out[(long)n * g.K + k] = pos;
             if (fp.sum_out) fp.sum_out[(long)n * g.K + k] = S;
