@@ -474,8 +474,9 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
     const int n_end = n_begin + fp.chunk_n < g.N ? n_begin + fp.chunk_n : g.N;
 
     // the dW entries j = lane + 64*jj of channel k that this lane accumulates
-    // xo: element offset of the entry's tap from the patch origin (bits 0-23), its tap row (24-27) and
-    // column (28-30); negative for an entry beyond C*R*S
+    // xo: element offset of the entry's tap from the patch origin (bits 0-23) and the tap's number r*S + s
+    // (bits 24-29); an entry beyond C*R*S has offset 0 and tap number 63, which no filter of the shapes
+    // this form takes has (R*S <= 63)
     int xo[kFusedJ];
     float acc[kFusedJ];
 #pragma unroll
@@ -486,7 +487,7 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
         else      fp.d_rs.divmod(j, c, tap);
         fp.d_s.divmod(tap, r, s2);
         const uint32_t off = NHWC ? (r * g.W + s2) * g.C + c : c * HW + r * g.W + s2;
-        xo[jj] = j < CRS ? (int)(off | r << 24 | s2 << 28) : (int)0x80000000u;   // beyond C*R*S: offset 0, sign bit set
+        xo[jj] = j < CRS ? (int)(off | tap << 24) : (int)(63u << 24);
         acc[jj] = 0.f;
     }
 
@@ -542,13 +543,21 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
                 else      x_pend[jj] = *(const float *)(Ximg + off);
             }
         } else {
+            // which taps lie inside X depends on the position alone: one bit per tap number, built on the
+            // scalar unit from the valid tap rows [r_lo, r_hi) and columns [s_lo, s_hi)
+            const int r_lo = ihb < 0 ? -ihb : 0, r_hi = g.H - ihb < g.R ? g.H - ihb : g.R;
+            const int s_lo = iwb < 0 ? -iwb : 0, s_hi = g.W - iwb < g.S ? g.W - iwb : g.S;
+            unsigned long long taps = 0;
+            if (s_hi > s_lo) {
+                const unsigned long long cols = ((1ull << s_hi) - 1) & ~((1ull << s_lo) - 1);
+                for (int r = r_lo; r < r_hi; ++r) taps |= cols << (r * g.S);
+            }
             pend_inside = 0;
 #pragma unroll
             for (int jj = 0; jj < kFusedJ; ++jj) {
-                const int ih = ihb + ((xo[jj] >> 24) & 15), iw = iwb + ((xo[jj] >> 28) & 7);
-                const bool inside = xo[jj] >= 0 && ih >= 0 && ih < g.H && iw >= 0 && iw < g.W;
+                const uint32_t inside = (uint32_t)(taps >> ((uint32_t)xo[jj] >> 24)) & 1u;
                 const uint32_t off = inside ? (uint32_t)(origin + (xo[jj] & 0xffffff)) * ESZ : 0u;
-                pend_inside |= (uint32_t)inside << jj;
+                pend_inside |= inside << jj;
                 if (BF16) x_pend[jj] = __uint_as_float((uint32_t)*(const uint16_t *)(Ximg + off));
                 else      x_pend[jj] = *(const float *)(Ximg + off);
             }
@@ -876,7 +885,9 @@ ApproxPlan plan_approx(const Geometry &g, bool allow_lds, bool allow_fused, bool
         const long max_chunks = (g.N + pl.nb - 1) / pl.nb;
         if (chunks > max_chunks) chunks = max_chunks;
     } else if (allow_fused && tune_int("WGRAD_APPROX_FUSED", 1) && (g.Ho * g.Wo) % 4 == 0
-               && g.Ho * g.Wo <= 64 * kFusedV * 4 && g.crs() <= 64 * kFusedJ) {
+               && g.Ho * g.Wo <= 64 * kFusedV * 4 && g.crs() <= 64 * kFusedJ && g.R * g.S <= 63
+               && ((long)g.H + 2l * g.ph + g.R) * ((long)g.W + 2l * g.pw + g.S) * g.C < (1l << 24)) {
+        // (the last two: a tap's number and its offset inside the padded input share one 32-bit word)
         // fused form: one workgroup per (output channel, batch chunk); four images at a time
         pl.fused = 1;
         chunks = (tune_int("WGRAD_FUSED_BLOCKS", 768) + g.K - 1) / g.K;

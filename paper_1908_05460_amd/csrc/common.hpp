@@ -83,6 +83,7 @@ struct ExactPlan {
     int xv;                          // elements per staging access (4, 2; 0 = element-wise staging)
     int stream, gpw, xbuf, rowp;           // streaming form: A operand from global memory, window double-buffered
     int mm16;                        // bf16 matrix-core form of the streaming kernel
+    int direct;                      // general form: no tile of whole output rows fits the LDS
     size_t lds_bytes, ws_bytes;
     bool ok;
 };
@@ -92,6 +93,10 @@ struct MultiQueue;
 int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st,
                         MultiQueue *mq = nullptr);
 bool plan_exact_bf16(const Geometry &g, ExactPlan &pl);
+struct CombineQueue;
+void plan_exact_direct(const Geometry &g, ExactPlan &pl);
+int launch_exact_direct(const Geometry &g, const ExactPlan &pl, const void *X, const void *dY, float *dW, void *ws,
+                        hipStream_t st, CombineQueue *defer);
 // The A operand of the bf16 matrix-core kernel given as the sparsified gradient of the
 // approximation: per problem, every map's selected position (row << 16 | col) and sum.
 struct SparseA {

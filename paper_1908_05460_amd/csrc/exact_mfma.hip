@@ -555,10 +555,14 @@ ExactPlan plan_exact(const Geometry &g, bool allow_stream)
             break;
         }
     }
-    if (!pl.ok) return pl;
     // fast-division bounds: dividend * divisor < 2^32
     const long plane = (long)pl.nti * pl.iht * pl.iwt;
-    if ((long)pl.ctch * plane * plane >= (1ll << 32) || (long)KT * pl.q * pl.q >= (1ll << 32)) { pl.ok = false; return pl; }
+    if (pl.ok && ((long)pl.ctch * plane * plane >= (1ll << 32) || (long)KT * pl.q * pl.q >= (1ll << 32))) pl.ok = false;
+    if (!pl.ok || tune_int("WGRAD_EXACT_DIRECT", 0)) {
+        // no tile of whole output rows fits (very wide or widely strided inputs): the general form
+        plan_exact_direct(g, pl);
+        return pl;
+    }
 
     pl.h_tiles = (g.Ho + pl.ht - 1) / pl.ht;
     pl.n_groups = (g.N + pl.nti - 1) / pl.nti;
@@ -647,6 +651,12 @@ int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void 
     // each in its own slice of the workspace
     const ExactPlan pl = (plan.stream || plan.mm16) ? plan_exact(g, false) : plan;
     for (int i = 0; i < b.n; ++i) {
+        char *slice = (char *)ws + (size_t)i * align_up(plan.ws_bytes);
+        if (pl.direct) {
+            int rc = launch_exact_direct(g, pl, b.X[i], b.dY[i], b.dW[i], slice, st, defer);
+            if (rc != WGRAD_OK) return rc;
+            continue;
+        }
         int rc = launch_exact_staged(g, pl, b.X[i], b.dY[i], b.dW[i], (char *)ws + (size_t)i * align_up(plan.ws_bytes), st, defer);
         if (rc != WGRAD_OK) return rc;
     }

@@ -36,6 +36,9 @@ SMALL = [
     (33, 16, 4, 4, 64, 3, 3, 1, 1, 1, 1),       # 4x4 planes, a ragged last image group
     (5, 32, 6, 6, 144, 3, 3, 1, 1, 1, 1),       # 6x6 planes: a 16-byte piece of a plane wraps over rows (LDS gather)
     (9, 70, 2, 6, 130, 3, 3, 1, 1, 1, 1),       # 2x6 planes, ragged channel tile
+    (3, 1, 16, 16, 5, 3, 9, 1, 1, 4, 4),        # wide filter (S > 8), padding of several columns
+    (2, 2, 20, 20, 4, 17, 3, 1, 1, 8, 1),       # tall filter (R > 16)
+    (2, 1, 24, 24, 3, 9, 9, 1, 1, 4, 4),        # 81 taps: more than the fused form's tap mask holds
 ]
 
 
@@ -67,6 +70,52 @@ def test_approx_matches_oracle(t, dtype):
     want, _, _ = oracle.wgrad_approx(oracle_shape(d), X, dY)
     check_select(d, dY, idx.cpu().numpy(), S.cpu().numpy())
     assert normwise_err(got, want) <= TOL[dtype]
+
+
+def test_strided_input_whose_planes_exceed_the_fused_offset_field():
+    """70 channels of 512x512 under stride 16: maps of 1024 positions and 70 entries per output channel, the
+    shape class of the fused form, but tap offsets inside one image need more than 24 bits."""
+    d = mk((2, 70, 512, 512, 4, 1, 1, 16, 16, 0, 0))
+    X, dY = rand_inputs(d, 99)
+    Xg, dYg = to_gpu(X), to_gpu(dY)
+    g = oracle_shape(d)
+    assert normwise_err(B.conv_wgrad_approx(d, Xg, dYg).cpu().numpy(), oracle.wgrad_approx(g, X, dY)[0]) <= TOL["fp32"]
+    assert normwise_err(B.conv_wgrad_approx_topk(d, Xg, dYg, 3).cpu().numpy(),
+                        oracle.wgrad_approx_topk(g, X, dY, 3)[0]) <= TOL["fp32"]
+    assert normwise_err(B.conv_wgrad_exact(d, Xg, dYg).cpu().numpy(), oracle.wgrad_exact(g, X, dY)) <= TOL["fp32"]
+
+
+# shapes whose output rows are too wide (or whose strides spread them too far) for a tile of whole rows in
+# LDS: the general form of the exact kernel
+WIDE = [
+    (2, 5, 6, 1024, 7, 3, 3, 1, 1, 1, 1),       # wide and flat
+    (1, 3, 40, 300, 70, 3, 7, 1, 1, 1, 3),      # ragged everything, 63 entries per output channel
+    (2, 16, 4, 1024, 20, 1, 9, 1, 1, 0, 4),     # a 1-d convolution
+    (3, 70, 9, 640, 130, 2, 2, 3, 16, 1, 0),    # stride 16 along a wide row: ragged tiles both ways
+    (2, 64, 12, 512, 64, 3, 3, 1, 1, 1, 1),     # the matrix-core kernels' favourite filter on rows of 512
+]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("t", WIDE)
+def test_exact_general_form_matches_oracle(t, dtype):
+    d = mk(t, dtype)
+    X, dY = rand_inputs(d, 777, dtype)
+    g = oracle_shape(d)
+    want = oracle.wgrad_exact(g, X, dY)
+    got = B.conv_wgrad_exact(d, to_gpu(X), to_gpu(dY)).cpu().numpy()
+    assert normwise_err(got, want) <= TOL[dtype]
+    # the same through the channel-last entry point and through a schedule of two such layers
+    got = B.conv_wgrad_exact_nhwc(d, to_gpu(oracle.x_to_nhwc(X)), to_gpu(dY), B.DW_OIHW).cpu().numpy()
+    assert normwise_err(got, want) <= TOL[dtype]
+    import torch
+    Xg, dYg = to_gpu(X), to_gpu(dY)
+    dWs = [torch.full((d.K, d.C, d.R, d.S), float("nan"), device="cuda") for _ in range(2)]
+    sch = B.Schedule([d, d], [Xg, Xg], [dYg, dYg], dWs)
+    m = [B.EXACT, B.EXACT]
+    sch.run(m, B.alloc_workspace(sch.workspace_bytes(m), "cuda"))
+    for dW in dWs:
+        assert normwise_err(dW.cpu().numpy(), want) <= TOL[dtype]
 
 
 def test_approx_scale_is_applied_once_and_power_of_two_is_bit_exact():
