@@ -35,18 +35,23 @@ __device__ __forceinline__ unsigned long long wave_max(unsigned long long v)
     return v;
 }
 
-// One wavefront per map.  Pass j finds the largest key below the one pass j-1 found, so no
-// list of taken positions is kept; the map's sum rides along with pass 0.  Maps of up to
-// 64*REG entries stay in registers between the passes, longer ones are read again (from L2).
-template <bool BF16, int REG>
+// One wavefront per map (WIDE = false), or one workgroup per map for maps of more than 1024 positions
+// (WIDE = true: few, long maps would otherwise leave most of the chip idle).  Pass j finds the largest key
+// below the one pass j-1 found, so no list of taken positions is kept; the map's sum rides along with pass 0.
+// Maps of up to T*REG entries (T = 64 or 256 threads) stay in registers between the passes, longer ones are
+// read again (from L2).
+template <bool BF16, int REG, bool WIDE>
 __global__ __launch_bounds__(kBlock) void topk_select(const void *__restrict__ dY, long maps, int len, int Wo,
                                                       int k, int32_t *__restrict__ hw_out,
                                                       int32_t *__restrict__ flat_out, float *__restrict__ sum_a,
                                                       float *__restrict__ sum_b)
 {
-    const int lane = threadIdx.x & 63;
-    const long map = (long)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
-    if (map >= maps) return;                      // whole wavefronts leave together
+    constexpr int T = WIDE ? kBlock : 64;
+    __shared__ unsigned long long wg_best[2][kBlock / 64];      // WIDE: the wavefronts' maxima, double-buffered over passes
+    __shared__ float wg_sum[kBlock / 64];
+    const int lane = WIDE ? threadIdx.x : threadIdx.x & 63;
+    const long map = WIDE ? (long)blockIdx.x : (long)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+    if (map >= maps) return;                      // whole wavefronts leave together (WIDE: the grid is exactly maps)
     const long base = map * len;
 
     unsigned long long held[REG > 0 ? REG : 1];
@@ -54,7 +59,7 @@ __global__ __launch_bounds__(kBlock) void topk_select(const void *__restrict__ d
     if (REG > 0) {
 #pragma unroll
         for (int i = 0; i < REG; ++i) {
-            const int e = lane + 64 * i;
+            const int e = lane + T * i;
             held[i] = 0ull;                        // below every real key: ~pos is never 0 for pos < 2^32-1
             if (e < len) {
                 const uint32_t b = load_bits<BF16>(dY, base + e);
@@ -63,10 +68,15 @@ __global__ __launch_bounds__(kBlock) void topk_select(const void *__restrict__ d
             }
         }
     } else {
-        for (int e = lane; e < len; e += 64) sum += __uint_as_float(load_bits<BF16>(dY, base + e));
+        for (int e = lane; e < len; e += T) sum += __uint_as_float(load_bits<BF16>(dY, base + e));
     }
 #pragma unroll
     for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
+    if (WIDE) {
+        if ((threadIdx.x & 63) == 0) wg_sum[threadIdx.x >> 6] = sum;
+        __syncthreads();
+        sum = (wg_sum[0] + wg_sum[1]) + (wg_sum[2] + wg_sum[3]);
+    }
 
     unsigned long long below = ~0ull;
     for (int j = 0; j < k; ++j) {
@@ -78,21 +88,28 @@ __global__ __launch_bounds__(kBlock) void topk_select(const void *__restrict__ d
                 best = c > best ? c : best;
             }
         } else {
-            for (int e = lane; e < len; e += 64) {
+            for (int e = lane; e < len; e += T) {
                 unsigned long long c = rank_key(load_bits<BF16>(dY, base + e), (uint32_t)e);
                 c = c < below ? c : 0ull;
                 best = c > best ? c : best;
             }
         }
         best = wave_max(best);
+        if (WIDE) {
+            // pass j writes buffer j & 1; the barrier of pass j+1 separates its readers from pass j+2's writers
+            if ((threadIdx.x & 63) == 0) wg_best[j & 1][threadIdx.x >> 6] = best;
+            __syncthreads();
+#pragma unroll
+            for (int w = 0; w < kBlock / 64; ++w) best = wg_best[j & 1][w] > best ? wg_best[j & 1][w] : best;
+        }
         below = best;
-        if (lane == 0) {
+        if (threadIdx.x == 0 || (!WIDE && lane == 0)) {
             const int32_t pos = (int32_t)~(uint32_t)best;
             if (flat_out) flat_out[map * k + j] = pos;
             hw_out[map * k + j] = ((pos / Wo) << 16) | (pos % Wo);
         }
     }
-    if (lane == 0) {
+    if (threadIdx.x == 0 || (!WIDE && lane == 0)) {
         sum_a[map] = sum;
         if (sum_b) sum_b[map] = sum;
     }
@@ -179,14 +196,16 @@ int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *
     // maps of up to 1024 positions and C*R*S <= 576: selection and gather in one launch
     if (topk_fused(g, X, dY, k, scale, dW, idx_out, sum_out, partials, st, &rc)) return rc;
 
-    const long grid = (maps + kBlock / 64 - 1) / (kBlock / 64);
+    const bool wide = len > 1024;
+    const long grid = wide ? maps : (maps + kBlock / 64 - 1) / (kBlock / 64);
     if (grid >= (1l << 31)) return WGRAD_UNSUPPORTED;
 #define SEL_ARGS dim3((unsigned)grid), dim3(kBlock), 0, st, dY, maps, len, g.Wo, k, hw, idx_out, sum, sum_out
-#define SEL_PICK(BF)                                                              \
-    if (len <= 64)        WGRAD_LAUNCH((topk_select<BF, 1>), SEL_ARGS);           \
-    else if (len <= 256)  WGRAD_LAUNCH((topk_select<BF, 4>), SEL_ARGS);           \
-    else if (len <= 1024) WGRAD_LAUNCH((topk_select<BF, 16>), SEL_ARGS);          \
-    else                  WGRAD_LAUNCH((topk_select<BF, 0>), SEL_ARGS)
+#define SEL_PICK(BF)                                                                     \
+    if (len <= 64)        WGRAD_LAUNCH((topk_select<BF, 1, false>), SEL_ARGS);           \
+    else if (len <= 256)  WGRAD_LAUNCH((topk_select<BF, 4, false>), SEL_ARGS);           \
+    else if (len <= 1024) WGRAD_LAUNCH((topk_select<BF, 16, false>), SEL_ARGS);          \
+    else if (len <= 4096) WGRAD_LAUNCH((topk_select<BF, 16, true>), SEL_ARGS);           \
+    else                  WGRAD_LAUNCH((topk_select<BF, 0, true>), SEL_ARGS)
     if (g.bf16) { SEL_PICK(true); } else { SEL_PICK(false); }
 #undef SEL_PICK
 #undef SEL_ARGS

@@ -1,5 +1,7 @@
-"""Seeded random convolution shapes (filters 1..5, strides 1..3, paddings, odd sizes, both element types)
-through every entry point, against the oracle: selected positions bit-exact, gradients within tolerance."""
+"""Seeded random convolution shapes through every entry point, against the oracle: selected positions
+bit-exact, gradients within tolerance.  Two distributions: moderate shapes (filters 1..5, strides 1..3,
+padding below the filter size), and extreme ones (filters to 9x11, strides to 7, padding beyond the filter
+size, rows of up to 512 elements, single-channel and single-image cases)."""
 import numpy as np
 import pytest
 
@@ -10,32 +12,55 @@ from tests.gpu_util import TOL, check_select, normwise_err, oracle_shape, rand_i
 pytestmark = pytest.mark.gpu
 
 
-def random_cases(seed, count):
+def moderate(rng):
+    R = int(rng.choice([1, 2, 3, 3, 3, 5])); S = int(rng.choice([1, 2, 3, 3, 3, 4]))
+    sh = int(rng.choice([1, 1, 1, 2, 3])); sw = int(rng.choice([1, 1, 1, 2]))
+    ph = int(rng.integers(0, R)); pw = int(rng.integers(0, S))
+    H = int(rng.integers(max(1, R - 2 * ph), 20)); W = int(rng.integers(max(1, S - 2 * pw), 20))
+    if rng.random() < 0.3:
+        H = W = int(rng.choice([2, 4, 6, 8, 16]))
+    C = int(rng.choice([1, 3, 5, 16, 24, 32, 48, 64, 80, 128]))
+    K = int(rng.choice([1, 7, 16, 32, 64, 96, 128, 144, 256]))
+    N = int(rng.integers(1, 40))
+    return N, C, H, W, K, R, S, sh, sw, ph, pw
+
+
+def extreme(rng):
+    R = int(rng.choice([1, 2, 3, 3, 4, 5, 7, 9])); S = int(rng.choice([1, 2, 3, 3, 4, 6, 8, 11]))
+    sh = int(rng.choice([1, 1, 2, 3, 5])); sw = int(rng.choice([1, 1, 2, 4, 7]))
+    ph = int(rng.integers(0, R + 3)); pw = int(rng.integers(0, S + 3))
+    H = int(rng.integers(1, 40)); W = int(rng.integers(1, 40))
+    mode = rng.random()
+    if mode < 0.2:
+        W = int(rng.choice([64, 128, 224, 300, 512])); H = int(rng.integers(1, 6))
+    elif mode < 0.3:
+        H = int(rng.choice([64, 100, 256])); W = int(rng.integers(1, 6))
+    elif mode < 0.4:
+        H = W = int(rng.choice([32, 56, 64]))
+    C = int(rng.choice([1, 2, 3, 5, 16, 17, 32, 64, 70, 128]))
+    K = int(rng.choice([1, 2, 7, 16, 33, 64, 100, 128, 192, 260]))
+    N = int(rng.choice([1, 2, 3, 5, 8, 17, 32]))
+    return N, C, H, W, K, R, S, sh, sw, ph, pw
+
+
+def random_cases(seed, count, draw=moderate):
     rng = np.random.default_rng(seed)
     out = []
     while len(out) < count:
-        R = int(rng.choice([1, 2, 3, 3, 3, 5])); S = int(rng.choice([1, 2, 3, 3, 3, 4]))
-        sh = int(rng.choice([1, 1, 1, 2, 3])); sw = int(rng.choice([1, 1, 1, 2]))
-        ph = int(rng.integers(0, R)); pw = int(rng.integers(0, S))
-        H = int(rng.integers(max(1, R - 2 * ph), 20)); W = int(rng.integers(max(1, S - 2 * pw), 20))
-        if rng.random() < 0.3:
-            H = W = int(rng.choice([2, 4, 6, 8, 16]))
-        C = int(rng.choice([1, 3, 5, 16, 24, 32, 48, 64, 80, 128]))
-        K = int(rng.choice([1, 7, 16, 32, 64, 96, 128, 144, 256]))
-        N = int(rng.integers(1, 40))
+        N, C, H, W, K, R, S, sh, sw, ph, pw = draw(rng)
         dtype = "bf16" if rng.random() < 0.4 else "fp32"
         k = int(rng.integers(1, 6)); layout = int(rng.integers(0, 3))
         if H + 2 * ph < R or W + 2 * pw < S:
             continue
         Ho, Wo = (H + 2 * ph - R) // sh + 1, (W + 2 * pw - S) // sw + 1
-        if N * K * Ho * Wo * C * R * S > 2e8:
+        if N * K * Ho * Wo * C * R * S > 2e8 or N * C * H * W > 4e6 or K * C * R * S > 2e6:
             continue
         out.append(pytest.param((N, C, H, W, K, R, S, sh, sw, ph, pw), dtype, min(k, Ho * Wo), layout,
                                 id=f"N{N}C{C}H{H}W{W}K{K}R{R}S{S}s{sh}{sw}p{ph}{pw}-{dtype}"))
     return out
 
 
-@pytest.mark.parametrize("t,dtype,k,layout", random_cases(20190805, 48))
+@pytest.mark.parametrize("t,dtype,k,layout", random_cases(20190805, 48) + random_cases(1908, 64, extreme))
 def test_every_entry_point_on_a_random_shape(t, dtype, k, layout):
     import torch
     N, C, H, W, K, R, S, sh, sw, ph, pw = t

@@ -42,10 +42,12 @@ def test_topk_matches_oracle(t, k, dtype):
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("hw,k", [((1, 1), 1), ((2, 2), 4), ((1, 3), 2), ((4, 4), 16), ((8, 8), 5), ((7, 9), 63),
-                                  ((16, 16), 7), ((17, 16), 9), ((32, 32), 64), ((33, 31), 12), ((64, 48), 6)])
+                                  ((16, 16), 7), ((17, 16), 9), ((32, 32), 64), ((33, 31), 12), ((64, 48), 6),
+                                  ((41, 25), 4), ((64, 64), 3), ((80, 64), 5), ((3, 1700), 8)])
 def test_topk_order_under_heavy_ties(hw, k, dtype):
     # few distinct magnitudes: the order among equals (lower flat index first) decides nearly every rank;
-    # the map lengths cover every register-resident variant of the selection and the re-reading one
+    # the map lengths cover every register-resident variant of the selection (a wavefront per map up to 1024
+    # positions, a workgroup per map beyond) and the re-reading one (more than 4096 positions)
     Ho, Wo = hw
     d = B.desc(5, 2, Ho, Wo, 9, R=1, S=1, pad=0, dtype=B.BF16 if dtype == "bf16" else B.F32)
     rng = np.random.default_rng(Ho * 100 + Wo + k)
