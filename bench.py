@@ -45,6 +45,9 @@ def main():
     ap.add_argument("--copies", type=int, default=0, help="distinct input sets to rotate (0 = enough for 1 GB)")
     ap.add_argument("--layer-reps", type=int, default=20, help="back-to-back launches per layer in the per-layer pass")
     ap.add_argument("--cpu-budget-s", type=float, default=20.0, help="CPU seconds to spend on the oracle baseline (0 = skip)")
+    ap.add_argument("--event-every", type=int, default=5,
+                    help="timed steps between two steps whose phases are bracketed by HIP events (an event pair "
+                         "drains the stream: five per step cost 25 us of a 205 us step)")
     ap.add_argument("--scale", type=float, default=1.0 / 128)
     ap.add_argument("--topk", type=int, default=4, help="k of the top-k column of the per-layer pass (0 = skip)")
     ap.add_argument("--no-layouts", action="store_true",
@@ -118,7 +121,8 @@ def main():
     phases = ("exact", "approx", "zero", "random")
     on = set(args.phases.split(","))
     assert on <= set(phases) and on, "--phases takes a comma list of exact,approx,zero,random"
-    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(5)] for _ in range(args.steps)]
+    every = max(1, args.event_every)
+    ev = {i: [torch.cuda.Event(enable_timing=True) for _ in range(5)] for i in range(0, args.steps, every)}
 
     def step(i, events=None):
         s = sets[i % copies]
@@ -137,11 +141,11 @@ def main():
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for i in range(args.steps):
-        step(args.warmup + i, ev[i])
+        step(args.warmup + i, ev.get(i))
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    phase_ms = {p: float(np.median([ev[i][j].elapsed_time(ev[i][j + 1]) for i in range(args.steps)]))
+    phase_ms = {p: float(np.median([e[j].elapsed_time(e[j + 1]) for e in ev.values()]))
                 for j, p in enumerate(phases)}
 
     # ---- per-layer pass: groups of back-to-back launches of one layer between one event pair,
