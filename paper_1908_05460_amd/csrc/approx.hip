@@ -70,6 +70,24 @@ __device__ __forceinline__ float wave_sum_f32(float v)
 // The largest (magnitude key, inverted position) pair of the wavefront, lexicographically: first the largest key, then,
 // among the lanes that hold it, the largest inverted position (the smallest position).  A lane without a candidate
 // passes (0, 0); a real inverted position is never 0.
+// The same scans stopped after the row steps: lane 15 of each row of 16 lanes ends with its row's result.
+__device__ __forceinline__ uint32_t row_max_u32(uint32_t v)
+{
+    v = max(v, dpp_move<0x111, 0xf>(v));
+    v = max(v, dpp_move<0x112, 0xf>(v));
+    v = max(v, dpp_move<0x114, 0xf>(v));
+    v = max(v, dpp_move<0x118, 0xf>(v));
+    return v;
+}
+__device__ __forceinline__ float row_sum_f32(float v)
+{
+    v += __uint_as_float(dpp_move<0x111, 0xf>(__float_as_uint(v)));
+    v += __uint_as_float(dpp_move<0x112, 0xf>(__float_as_uint(v)));
+    v += __uint_as_float(dpp_move<0x114, 0xf>(__float_as_uint(v)));
+    v += __uint_as_float(dpp_move<0x118, 0xf>(__float_as_uint(v)));
+    return v;
+}
+
 __device__ __forceinline__ void wave_max_pair(uint32_t key, uint32_t inv_pos, uint32_t &key_max, uint32_t &inv_pos_max)
 {
     key_max = wave_max_u32(key);
@@ -453,7 +471,11 @@ struct FusedParams {
 // the same one-step-delayed accumulation with weight sum / tk.
 // V, FULLMAP: a map is V 16-byte pieces per lane; FULLMAP says that every lane holds all V of them (maps of
 // exactly 256*V positions), which leaves the image loop free of conditional loads and of branches.
-template <bool BF16, bool NHWC, bool TOPK, int V, bool FULLMAP>
+// ROWS (maps of up to 64 positions, V = 1): a map fills at most one row of 16 lanes, so a wavefront scans the
+// maps of four images at once, one per row, and reduces them with the row steps of the scans alone; the
+// four patches are then gathered one after the other as before.  The scan and the reductions, half of the
+// vector instructions of a small map, are shared by four maps.
+template <bool BF16, bool NHWC, bool TOPK, int V, bool FULLMAP, bool ROWS = false>
 __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry &g, const FusedParams &fp,
                                            float (&red)[4][kFusedJ * 64], int linear, int nk, int nchunks, int nprob)
 {
@@ -498,6 +520,11 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
     // arrives under the butterfly, the accumulation and the patch request
     raw4 cur[V];
     auto load_map = [&](int n, raw4 (&m)[V]) {
+        if (ROWS) {                            // row r of the wavefront: image n + 4r
+            const int nr = n + 4 * (lane >> 4), e = (lane & 15) * 4;
+            if (nr < n_end && e < L) m[0] = *(const raw4 *)(dY + (((long)nr * g.K + k) * L + e) * ESZ);
+            return;
+        }
         const char *base = dY + ((long)n * g.K + k) * L * ESZ;
 #pragma unroll
         for (int v = 0; v < V; ++v) {
@@ -575,7 +602,58 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
 #pragma unroll
         for (int i = 0; i < (int)(sizeof(raw4) / 4); ++i) asm volatile("v_mov_b32 %0, %1" : "=v"(w[i]) : "v"(w[i]));
     }
-    for (int n = n_begin + wave; n < n_end; n += 4) {
+    for (int n = n_begin + wave; n < n_end; n += ROWS ? 16 : 4) {
+        if (ROWS) {
+            const int e = (lane & 15) * 4;
+            const bool have = n + 4 * (lane >> 4) < n_end && e < L;
+            uint32_t best_key = 0, best_pos = e;
+            float sum = 0.f;
+            if (have) {
+                uint32_t bits[4];
+                if (BF16) {
+                    const uint2 r2 = *(const uint2 *)&cur[0];
+                    bits[0] = r2.x << 16; bits[1] = r2.x & 0xffff0000u; bits[2] = r2.y << 16; bits[3] = r2.y & 0xffff0000u;
+                } else {
+                    const uint4 r4 = *(const uint4 *)&cur[0];
+                    bits[0] = r4.x; bits[1] = r4.y; bits[2] = r4.z; bits[3] = r4.w;
+                }
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t key = mag_key<BF16>(bits[i]);
+                    if (key > best_key) { best_key = key; best_pos = e + i; }
+                    sum += __uint_as_float(bits[i]);
+                }
+            }
+            if (n + 16 < n_end) load_map(n + 16, cur);
+            const uint32_t rmax = row_max_u32(best_key);
+            const float rsum = row_sum_f32(sum);
+            uint32_t kmax[4];
+            float S4[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                kmax[r] = (uint32_t)__builtin_amdgcn_readlane((int)rmax, 16 * r + 15);
+                S4[r] = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(rsum), 16 * r + 15));
+            }
+            // the lowest lane of a row that holds the row's maximum holds its lowest position: lanes hold
+            // ascending positions, and a lane keeps the first of equal values
+            const uint32_t mine = lane < 32 ? (lane < 16 ? kmax[0] : kmax[1]) : (lane < 48 ? kmax[2] : kmax[3]);
+            const unsigned long long eq = __ballot(have && best_key == mine);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int nr = n + 4 * r;
+                if (nr >= n_end) break;                              // wavefront-uniform
+                const uint32_t sub = (uint32_t)(eq >> (16 * r)) & 0xffffu;      // not zero: lane 0 of the row has data
+                const int pos = __builtin_amdgcn_readlane((int)best_pos, 16 * r + __builtin_ctz(sub));
+                if (lane == 0) {
+                    if (fp.flat_out) fp.flat_out[(long)nr * g.K + k] = pos;
+                    if (fp.sum_out) fp.sum_out[(long)nr * g.K + k] = S4[r];
+                }
+                accumulate_pending();
+                request_patch(nr, pos);
+                S_pend = S4[r];
+            }
+            continue;
+        }
         if (TOPK) {
             float sum = 0.f, S = 0.f;
             unsigned long long below = ~0ull;
@@ -675,13 +753,15 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
     }
 }
 
-// Picks the body for the map size: maps of exactly 1024 or 256 positions get the branch-free forms.
+// Picks the body for the map size: maps of exactly 1024 or 256 positions get the branch-free forms, maps of
+// up to 64 positions the four-maps-per-wavefront form.
 template <bool BF16, bool NHWC, bool TOPK>
 __device__ __forceinline__ void fused_dispatch(const ApproxBatch &ab, const Geometry &g, const FusedParams &fp,
                                                float (&red)[4][kFusedJ * 64], int linear, int nk, int nchunks, int nprob)
 {
     const int L = g.Ho * g.Wo;
-    if (L == 1024)     fused_body<BF16, NHWC, TOPK, 4, true>(ab, g, fp, red, linear, nk, nchunks, nprob);
+    if (L <= 64 && !TOPK) fused_body<BF16, NHWC, false, 1, false, true>(ab, g, fp, red, linear, nk, nchunks, nprob);
+    else if (L == 1024) fused_body<BF16, NHWC, TOPK, 4, true>(ab, g, fp, red, linear, nk, nchunks, nprob);
     else if (L == 256) fused_body<BF16, NHWC, TOPK, 1, true>(ab, g, fp, red, linear, nk, nchunks, nprob);
     else if (L < 256)  fused_body<BF16, NHWC, TOPK, 1, false>(ab, g, fp, red, linear, nk, nchunks, nprob);
     else               fused_body<BF16, NHWC, TOPK, kFusedV, false>(ab, g, fp, red, linear, nk, nchunks, nprob);
