@@ -196,6 +196,31 @@ int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, h
     return launch_select_impl(g, ab, 1, idx, nullptr, st);
 }
 
+// Maps of up to four positions (2x2 planes), fp32: one thread per map selects, sums and writes the map's
+// sparsified form -- the scaled sum at the selected position, zeros elsewhere.  The approximated gradient is the
+// exact gradient of that tensor (Section 2.4), and on planes this small the matrix-core kernel computes it faster
+// than a gather does (a quarter of the positions survive; the gather moves as much data as the exact kernel).
+__global__ __launch_bounds__(kBlock) void sparsify_small(ApproxBatch ab, long maps, int len, float scale,
+                                                         int32_t *__restrict__ flat_out, float *__restrict__ sum_b)
+{
+    const long map = (long)blockIdx.x * kBlock + threadIdx.x;
+    if (map >= maps) return;
+    const uint32_t *__restrict__ dY = (const uint32_t *)ab.dY[blockIdx.y] + map * len;
+    float *__restrict__ sparse = ab.out[blockIdx.y] + map * len;
+    uint32_t best_key = 0;
+    int best_pos = 0;
+    float sum = 0.f;
+    for (int e = 0; e < len; ++e) {
+        const uint32_t bits = dY[e];
+        const uint32_t key = mag_key<false>(bits);
+        if (key > best_key) { best_key = key; best_pos = e; }
+        sum += __uint_as_float(bits);
+    }
+    for (int e = 0; e < len; ++e) sparse[e] = e == best_pos ? sum * scale : 0.f;
+    if (flat_out) flat_out[map] = best_pos;
+    if (sum_b) sum_b[map] = sum;
+}
+
 // ------------------------------------------------------------------------------------
 // gather, direct form: one thread per filter-gradient entry (k, c, r, s) and batch
 // chunk; it walks the chunk's images, reads the map's (row, col, S) and the one input
@@ -939,6 +964,19 @@ ApproxPlan plan_approx(const Geometry &g, bool allow_lds, bool allow_fused, bool
             return pl;
         }
     }
+    // fp32 inputs on planes of up to four positions: the exact matrix-core kernel on the sparsified dY
+    if (allow_mm && !g.bf16 && g.Ho * g.Wo <= 4 && tune_int("WGRAD_APPROX_SX", 1)) {
+        const ExactPlan ex = plan_exact(g);
+        if (ex.ok && ex.stream) {
+            pl.sx = 1;
+            pl.ex = ex;
+            pl.chunks = 1; pl.chunk_n = g.N;
+            pl.off_sparse = 0;
+            pl.off_part = align_up((size_t)g.N * g.K * g.Ho * g.Wo * 4);
+            pl.ws_bytes = pl.off_part + align_up(ex.ws_bytes);
+            return pl;
+        }
+    }
     // LDS form when every input element is used several times over by the K patches of its image
     // haloed plane: rows/cols -pad .. max(last tap the positions can reach, last row/col of X)
     const int hp = std::max((g.Ho - 1) * g.sh + 3, g.H + g.ph), wp = std::max((g.Wo - 1) * g.sw + 3, g.W + g.pw);
@@ -1090,7 +1128,7 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
     bool aligned = true;
     for (int i = 0; i < b.n; ++i)
         aligned = aligned && ((uintptr_t)b.X[i] % (g.bf16 ? 8 : 16)) == 0 && ((uintptr_t)b.dY[i] % (g.bf16 ? 8 : 16)) == 0;
-    ApproxPlan pl = ((plan.use_lds || plan.fused || plan.mm) && !aligned) ? plan_approx(g, false, false, false) : plan;
+    ApproxPlan pl = ((plan.use_lds || plan.fused || plan.mm) && !aligned) ? plan_approx(g, false, false, false) : plan;   // (the sparsified form has no alignment needs: the exact launcher falls back by itself)
     const long outs = g.dw_elems();
     if (pl.use_lds && b.n > 1) {
         // the workgroup target is for the whole launch: a batch of layers chunks each layer's images less finely
@@ -1132,6 +1170,25 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
     }
     const float kscale = pl.chunks > 1 ? 1.0f : scale;
     int rc;
+    if (pl.sx) {
+        // the group's workspace (b.n slices of plan.ws_bytes, contiguous) is cut anew: the sparsified tensors of
+        // all problems first, then one region for the exact kernel's partials of the whole batch
+        ApproxBatch sb{};
+        Batch eb{};
+        eb.n = b.n;
+        for (int i = 0; i < kMaxBatch; ++i) {
+            const int j = i < b.n ? i : 0;
+            sb.dY[i] = b.dY[j];
+            sb.out[i] = (float *)((char *)ws + (size_t)j * pl.off_part);
+            eb.X[i] = b.X[j]; eb.dY[i] = sb.out[i]; eb.dW[i] = b.dW[j];
+        }
+        const long maps = (long)g.N * g.K;
+        const dim3 grid((unsigned)((maps + kBlock - 1) / kBlock), (unsigned)b.n);
+        WGRAD_LAUNCH(sparsify_small, grid, dim3(kBlock), 0, st, sb, maps, g.Ho * g.Wo, scale, idx_out, sum_out);
+        rc = launch_status();
+        if (rc != WGRAD_OK) return rc;
+        return launch_exact(g, pl.ex, eb, (char *)ws + (size_t)b.n * pl.off_part, st, defer);
+    }
     if (pl.mm) {
         rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st);
         if (rc != WGRAD_OK) return rc;

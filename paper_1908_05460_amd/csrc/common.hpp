@@ -121,8 +121,9 @@ struct ApproxPlan {
     int chunks, chunk_n;             // batch chunks whose partial sums are combined afterwards
     int use_lds, fused, m, nb, pitch, wp, ctiles, ktiles;   // LDS form of the gather: tile shape
     int mm;                          // contraction on the bf16 matrix core from the selection results
+    int sx;                          // fp32, planes of up to four positions: exact kernel on the sparsified dY
     ExactPlan ex;                    // its plan
-    size_t off_idx, off_sum, off_part, ws_bytes;
+    size_t off_idx, off_sum, off_part, off_sparse, ws_bytes;
 };
 ApproxPlan plan_approx(const Geometry &g, bool allow_lds = true, bool allow_fused = true, bool allow_mm = true);
 struct FusedQueue;

@@ -39,6 +39,7 @@ SMALL = [
     (3, 1, 16, 16, 5, 3, 9, 1, 1, 4, 4),        # wide filter (S > 8), padding of several columns
     (2, 2, 20, 20, 4, 17, 3, 1, 1, 8, 1),       # tall filter (R > 16)
     (2, 1, 24, 24, 3, 9, 9, 1, 1, 4, 4),        # 81 taps: more than the fused form's tap mask holds
+    (11, 16, 1, 4, 32, 3, 3, 1, 1, 1, 1),       # 1x4 planes: maps of four positions (fp32: exact kernel on the sparsified dY)
 ]
 
 
