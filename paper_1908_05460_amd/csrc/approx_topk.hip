@@ -25,33 +25,35 @@ __device__ __forceinline__ uint32_t load_bits(const void *p, long i)
     return BF16 ? (uint32_t)((const uint16_t *)p)[i] << 16 : ((const uint32_t *)p)[i];
 }
 
-__device__ __forceinline__ unsigned long long wave_max(unsigned long long v)
+// maximum over aligned groups of G lanes (G a power of two up to 64)
+__device__ __forceinline__ unsigned long long group_max(unsigned long long v, int G)
 {
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) {
+    for (int d = G >> 1; d > 0; d >>= 1) {
         const unsigned long long o = __shfl_xor(v, d, 64);
         v = o > v ? o : v;
     }
     return v;
 }
 
-// One wavefront per map (WIDE = false), or one workgroup per map for maps of more than 1024 positions
-// (WIDE = true: few, long maps would otherwise leave most of the chip idle).  Pass j finds the largest key
-// below the one pass j-1 found, so no list of taken positions is kept; the map's sum rides along with pass 0.
-// Maps of up to T*REG entries (T = 64 or 256 threads) stay in registers between the passes, longer ones are
+// A group of G lanes per map (WIDE = false; G a power of two, 64 / G maps per wavefront, so that maps of four
+// positions take a lane each and not a wavefront each), or one workgroup per map for maps of more than 1024
+// positions (WIDE = true: few, long maps would otherwise leave most of the chip idle).  Pass j finds the largest
+// key below the one pass j-1 found, so no list of taken positions is kept; the map's sum rides along with pass 0.
+// Maps of up to T*REG entries (T = G or 256 threads) stay in registers between the passes, longer ones are
 // read again (from L2).
 template <bool BF16, int REG, bool WIDE>
 __global__ __launch_bounds__(kBlock) void topk_select(const void *__restrict__ dY, long maps, int len, int Wo,
-                                                      int k, int32_t *__restrict__ hw_out,
+                                                      int k, int G, int32_t *__restrict__ hw_out,
                                                       int32_t *__restrict__ flat_out, float *__restrict__ sum_a,
-                                                      float *__restrict__ sum_b)
+                                                      float *__restrict__ sum_b, void *__restrict__ sparse, float w)
 {
-    constexpr int T = WIDE ? kBlock : 64;
+    const int T = WIDE ? kBlock : G;
     __shared__ unsigned long long wg_best[2][kBlock / 64];      // WIDE: the wavefronts' maxima, double-buffered over passes
     __shared__ float wg_sum[kBlock / 64];
-    const int lane = WIDE ? threadIdx.x : threadIdx.x & 63;
-    const long map = WIDE ? (long)blockIdx.x : (long)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
-    if (map >= maps) return;                      // whole wavefronts leave together (WIDE: the grid is exactly maps)
+    const int lane = WIDE ? threadIdx.x : (threadIdx.x & 63) % G;
+    const long map = WIDE ? (long)blockIdx.x
+                          : ((long)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6)) * (64 / G) + (threadIdx.x & 63) / G;
+    if (map >= maps) return;                      // whole groups leave together (WIDE: the grid is exactly maps)
     const long base = map * len;
 
     unsigned long long held[REG > 0 ? REG : 1];
@@ -70,8 +72,7 @@ __global__ __launch_bounds__(kBlock) void topk_select(const void *__restrict__ d
     } else {
         for (int e = lane; e < len; e += T) sum += __uint_as_float(load_bits<BF16>(dY, base + e));
     }
-#pragma unroll
-    for (int d = 32; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
+    for (int d = (WIDE ? 64 : G) >> 1; d > 0; d >>= 1) sum += __shfl_xor(sum, d, 64);
     if (WIDE) {
         if ((threadIdx.x & 63) == 0) wg_sum[threadIdx.x >> 6] = sum;
         __syncthreads();
@@ -94,7 +95,7 @@ __global__ __launch_bounds__(kBlock) void topk_select(const void *__restrict__ d
                 best = c > best ? c : best;
             }
         }
-        best = wave_max(best);
+        best = group_max(best, WIDE ? 64 : G);
         if (WIDE) {
             // pass j writes buffer j & 1; the barrier of pass j+1 separates its readers from pass j+2's writers
             if ((threadIdx.x & 63) == 0) wg_best[j & 1][threadIdx.x >> 6] = best;
@@ -112,6 +113,30 @@ __global__ __launch_bounds__(kBlock) void topk_select(const void *__restrict__ d
     if (threadIdx.x == 0 || (!WIDE && lane == 0)) {
         sum_a[map] = sum;
         if (sum_b) sum_b[map] = sum;
+    }
+    // optional: the sparsified map, sum * w at the kept positions (the k largest keys: those not below the
+    // last one found) and zero elsewhere, in the element type of the inputs
+    if (sparse) {
+        const float kept = sum * w;
+        auto put = [&](int e, bool is_kept) {
+            const float v = is_kept ? kept : 0.f;
+            if (BF16) {
+                const uint32_t b = __float_as_uint(v);           // round to nearest even; v is finite
+                ((uint16_t *)sparse)[base + e] = (uint16_t)((b + 0x7fffu + ((b >> 16) & 1u)) >> 16);
+            } else {
+                ((float *)sparse)[base + e] = v;
+            }
+        };
+        if (REG > 0) {
+#pragma unroll
+            for (int i = 0; i < REG; ++i) {
+                const int e = lane + T * i;
+                if (e < len) put(e, held[i] >= below);
+            }
+        } else {
+            for (int e = lane; e < len; e += T)
+                put(e, rank_key(load_bits<BF16>(dY, base + e), (uint32_t)e) >= below);
+        }
     }
 }
 
@@ -150,6 +175,27 @@ __global__ __launch_bounds__(kBlock) void topk_gather(const void *__restrict__ X
     out[(long)blockIdx.y * g.K * CRS + o] = acc * scale;
 }
 
+// When the kept positions are a sizeable share of a map, gathering their patches moves as much data as the
+// dense kernel and loses to the matrix core: the gradient is then computed as the exact gradient of the
+// sparsified dY (Section 2.4's identity).  Thresholds from measurements on the VGG-19 layers (N = 128): the
+// LDS gather costs about k/2 of the dense kernel on 4x4 planes and k/5 on 8x8 planes; the general gather
+// loses from three kept positions of 256 on; with bf16 inputs the dense kernel is twice as fast again.
+bool topk_sparse_exact(const Geometry &g, int k, ExactPlan &ex)
+{
+    if (!tune_int("WGRAD_TOPK_SX", 1)) return false;
+    const int L = g.Ho * g.Wo;
+    ex = plan_exact(g);
+    if (!ex.ok) return false;
+    // the bf16 matrix-core kernel runs a dense layer in the time the gather needs for one kept position
+    const bool fast_bf16 = ex.mm16 && k >= 2;
+    // large maps, few channels: the fused kernel, unless the bf16 matrix core beats it (maps of up to 256 positions)
+    if (plan_approx(g, /*allow_lds=*/false, /*allow_fused=*/true, /*allow_mm=*/false).fused) return fast_bf16 && L <= 256;
+    const ApproxPlan ap = plan_approx(g, /*allow_lds=*/true, /*allow_fused=*/false, /*allow_mm=*/false);
+    const bool lds = ap.use_lds && ap.m * k <= 64;
+    const bool dense_enough = L <= 4 || (lds ? k >= 2 && k * 14 >= L : k * 80 >= L);
+    return fast_bf16 || ((ex.stream || ex.mm16) && dense_enough);
+}
+
 int topk_chunks(const Geometry &g)
 {
     // enough (entry, chunk) threads to fill the chip, at least 4 images per chunk
@@ -179,7 +225,13 @@ static size_t topk_partial_bytes(const Geometry &g)
 size_t topk_ws_bytes(const Geometry &g, int k)
 {
     const size_t maps = (size_t)g.N * g.K;
-    return align_up(maps * k * sizeof(int32_t)) + align_up(maps * sizeof(float)) + topk_partial_bytes(g);
+    size_t tail = topk_partial_bytes(g);
+    ExactPlan ex;
+    if (topk_sparse_exact(g, k, ex)) {
+        const size_t sx = align_up(maps * g.Ho * g.Wo * (g.bf16 ? 2 : 4)) + align_up(ex.ws_bytes);
+        if (sx > tail) tail = sx;
+    }
+    return align_up(maps * k * sizeof(int32_t)) + align_up(maps * sizeof(float)) + tail;
 }
 
 int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *dW, int k, float scale,
@@ -193,16 +245,24 @@ int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *
     float *partials = (float *)w;
 
     int rc;
+    // kept positions a sizeable share of a map: the selection also writes the sparsified dY, and the exact
+    // kernel contracts it
+    ExactPlan ex;
+    const bool sx = topk_sparse_exact(g, k, ex);
+    void *sparse = sx ? (void *)partials : nullptr;
     // maps of up to 1024 positions and C*R*S <= 576: selection and gather in one launch
-    if (topk_fused(g, X, dY, k, scale, dW, idx_out, sum_out, partials, st, &rc)) return rc;
+    if (!sx && topk_fused(g, X, dY, k, scale, dW, idx_out, sum_out, partials, st, &rc)) return rc;
 
     const bool wide = len > 1024;
-    const long grid = wide ? maps : (maps + kBlock / 64 - 1) / (kBlock / 64);
+    // lanes per map: four positions each up to 256 positions, sixteen up to 1024
+    int G = 1;
+    while (G < 64 && G * 4 < len) G <<= 1;
+    const long waves = (maps + 64 / G - 1) / (64 / G);
+    const long grid = wide ? maps : (waves + kBlock / 64 - 1) / (kBlock / 64);
     if (grid >= (1l << 31)) return WGRAD_UNSUPPORTED;
-#define SEL_ARGS dim3((unsigned)grid), dim3(kBlock), 0, st, dY, maps, len, g.Wo, k, hw, idx_out, sum, sum_out
+#define SEL_ARGS dim3((unsigned)grid), dim3(kBlock), 0, st, dY, maps, len, g.Wo, k, G, hw, idx_out, sum, sum_out, sparse, scale / k
 #define SEL_PICK(BF)                                                                     \
-    if (len <= 64)        WGRAD_LAUNCH((topk_select<BF, 1, false>), SEL_ARGS);           \
-    else if (len <= 256)  WGRAD_LAUNCH((topk_select<BF, 4, false>), SEL_ARGS);           \
+    if (len <= 256)       WGRAD_LAUNCH((topk_select<BF, 4, false>), SEL_ARGS);           \
     else if (len <= 1024) WGRAD_LAUNCH((topk_select<BF, 16, false>), SEL_ARGS);          \
     else if (len <= 4096) WGRAD_LAUNCH((topk_select<BF, 16, true>), SEL_ARGS);           \
     else                  WGRAD_LAUNCH((topk_select<BF, 0, true>), SEL_ARGS)
@@ -211,6 +271,12 @@ int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *
 #undef SEL_ARGS
     rc = launch_status();
     if (rc != WGRAD_OK) return rc;
+
+    if (sx) {
+        Batch eb{};
+        eb.n = 1; eb.X[0] = X; eb.dY[0] = sparse; eb.dW[0] = dW;
+        return launch_exact(g, ex, eb, (char *)partials + align_up((size_t)maps * len * (g.bf16 ? 2 : 4)), st);
+    }
 
     // small planes and many output channels: the LDS-staged gather of the k = 1 path, over k positions per map
     if (topk_gather_lds(g, X, hw, sum, k, scale, dW, partials, topk_partial_bytes(g), st, &rc)) return rc;
