@@ -470,10 +470,16 @@ __global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch
 // and immediately gathers the C*R*S patch the selected position sees, one or more dW
 // entries per lane, accumulating in registers over its images.  The four wavefronts'
 // sums are added through LDS.  Position and sum never travel through memory; dY is read
-// exactly once.  Requires Ho*Wo <= 1024 (a multiple of 4) and C*R*S <= 576.
+// exactly once from HBM.  Requires Ho*Wo <= 1024 (a multiple of 4); the C*R*S entries of an output channel are
+// cut into slices of 576, one workgroup each (up to four: the slices of a channel scan the same maps, the
+// later ones out of L2).
 // ------------------------------------------------------------------------------------
 constexpr int kFusedJ = 9;       // dW entries of one output channel per lane
 constexpr int kFusedV = 4;       // 4-element pieces of one map per lane
+constexpr int kFusedSlices = 4;  // workgroups that share the entries of one output channel (C*R*S up to 4 * 576)
+
+// slices of kFusedJ * 64 entries that the C*R*S entries of one output channel are cut into
+static inline int fused_slices(const Geometry &g) { return (int)((g.crs() + 64 * kFusedJ - 1) / (64 * kFusedJ)); }
 
 struct FusedParams {
     int chunk_n;
@@ -484,6 +490,7 @@ struct FusedParams {
     int dw_layout;               // channel-last form only: where the result goes (WGRAD_DW_*)
     int tk;                      // top-k form only: kept positions per map, each weighted by sum * inv_k
     float inv_k;
+    int nslice;                  // workgroups per output channel, each owning kFusedJ * 64 of its C*R*S entries
 };
 
 // linear: the workgroup's number among the nk * nchunks * nprob of its group
@@ -510,8 +517,11 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // The K workgroups of one (problem, batch chunk) read the same input planes: number the workgroups so
     // that they sit on one XCD and find each other's planes in its L2.
+    // nk = K * fp.nslice: the slices of one output channel are neighbours (they scan the same maps)
     const int logical = xcd_contiguous_id(linear, nk * nchunks * nprob);
-    const int k = logical % nk;
+    const int kk = logical % nk;
+    const int k = kk / fp.nslice, j_base = (kk - k * fp.nslice) * (kFusedJ * 64);
+    const bool first_slice = j_base == 0;                  // writes the optional position / sum outputs
     const int by = (logical / nk) % nchunks, bz = logical / (nk * nchunks);
     const char *__restrict__ X = (const char *)ab.X[bz];
     const char *__restrict__ dY = (const char *)ab.dY[bz];
@@ -528,7 +538,7 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
     float acc[kFusedJ];
 #pragma unroll
     for (int jj = 0; jj < kFusedJ; ++jj) {
-        const int j = lane + 64 * jj;
+        const int j = j_base + lane + 64 * jj;
         uint32_t c, tap, r, s2;
         if (NHWC) fp.d_rs.divmod(j, tap, c);
         else      fp.d_rs.divmod(j, c, tap);
@@ -669,7 +679,7 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
                 if (nr >= n_end) break;                              // wavefront-uniform
                 const uint32_t sub = (uint32_t)(eq >> (16 * r)) & 0xffffu;      // not zero: lane 0 of the row has data
                 const int pos = __builtin_amdgcn_readlane((int)best_pos, 16 * r + __builtin_ctz(sub));
-                if (lane == 0) {
+                if (lane == 0 && first_slice) {
                     if (fp.flat_out) fp.flat_out[(long)nr * g.K + k] = pos;
                     if (fp.sum_out) fp.sum_out[(long)nr * g.K + k] = S4[r];
                 }
@@ -710,7 +720,7 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
                 if (t == 0) S = wave_sum_f32(sum);
                 const int pos = (int)~inv_pos_max;
                 below = ((unsigned long long)key_max << 32) | inv_pos_max;
-                if (lane == 0) {
+                if (lane == 0 && first_slice) {
                     if (fp.flat_out) fp.flat_out[((long)n * g.K + k) * fp.tk + t] = pos;
                     if (fp.sum_out && t == 0) fp.sum_out[(long)n * g.K + k] = S;
                 }
@@ -750,7 +760,7 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
         wave_max_pair(have ? best_key : 0u, have ? ~best_pos : 0u, key_max, inv_pos_max);
         const int pos = (int)~inv_pos_max;
         const float S = wave_sum_f32(sum);
-        if (lane == 0) {
+        if (lane == 0 && first_slice) {
             if (fp.flat_out) fp.flat_out[(long)n * g.K + k] = pos;
             if (fp.sum_out) fp.sum_out[(long)n * g.K + k] = S;
         }
@@ -765,8 +775,10 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
     for (int jj = 0; jj < kFusedJ; ++jj) red[wave][jj * 64 + lane] = acc[jj];
     __syncthreads();
     float *o = out + ((long)by * g.K + k) * CRS;
-    for (int j = tid; j < CRS; j += kBlock) {
-        const float v = (red[0][j] + red[1][j] + red[2][j] + red[3][j]) * fp.scale;
+    const int j_end = CRS - j_base < kFusedJ * 64 ? CRS - j_base : kFusedJ * 64;
+    for (int jl = tid; jl < j_end; jl += kBlock) {
+        const int j = j_base + jl;
+        const float v = (red[0][jl] + red[1][jl] + red[2][jl] + red[3][jl]) * fp.scale;
         if (!NHWC || fp.dw_layout == WGRAD_DW_OHWI) {
             o[j] = v;
         } else {
@@ -895,7 +907,7 @@ __global__ __launch_bounds__(kBlock) void approx_fused_multi(const FusedMulti)
     if (linear >= mp->count[gi]) return;
     FTRACE(0);
     const FusedGroup &G = mp->grp[gi];
-    fused_dispatch<BF16, false, false>(G.ab, G.g, G.fp, red, linear, G.g.K, G.nchunks, G.nprob);
+    fused_dispatch<BF16, false, false>(G.ab, G.g, G.fp, red, linear, G.g.K * G.fp.nslice, G.nchunks, G.nprob);
     FTRACE(3);
 }
 
@@ -920,7 +932,7 @@ int fused_flush(FusedQueue &q, hipStream_t st)
     for (int i = 0; i < q.n; ++i) {
         m.grp[i] = q.grp[i];
         m.begin[i] = blocks;
-        m.count[i] = q.grp[i].g.K * q.grp[i].nchunks * q.grp[i].nprob;
+        m.count[i] = q.grp[i].g.K * q.grp[i].fp.nslice * q.grp[i].nchunks * q.grp[i].nprob;
         blocks += (m.count[i] + 7) / 8 * 8;
     }
     m.begin[q.n] = blocks;
@@ -1003,12 +1015,13 @@ ApproxPlan plan_approx(const Geometry &g, bool allow_lds, bool allow_fused, bool
         const long max_chunks = (g.N + pl.nb - 1) / pl.nb;
         if (chunks > max_chunks) chunks = max_chunks;
     } else if (allow_fused && tune_int("WGRAD_APPROX_FUSED", 1) && (g.Ho * g.Wo) % 4 == 0
-               && g.Ho * g.Wo <= 64 * kFusedV * 4 && g.crs() <= 64 * kFusedJ && g.R * g.S <= 63
+               && g.Ho * g.Wo <= 64 * kFusedV * 4 && g.crs() <= 64 * kFusedJ * kFusedSlices && g.R * g.S <= 63
                && ((long)g.H + 2l * g.ph + g.R) * ((long)g.W + 2l * g.pw + g.S) * g.C < (1l << 24)) {
         // (the last two: a tap's number and its offset inside the padded input share one 32-bit word)
         // fused form: one workgroup per (output channel, batch chunk); four images at a time
         pl.fused = 1;
-        chunks = (tune_int("WGRAD_FUSED_BLOCKS", 768) + g.K - 1) / g.K;
+        const long wgs = (long)g.K * fused_slices(g);
+        chunks = (tune_int("WGRAD_FUSED_BLOCKS", 768) + wgs - 1) / wgs;
         if (chunks > (g.N + 7) / 8) chunks = (g.N + 7) / 8;         // at least two images per wavefront
     } else {
         chunks = (tune_int("WGRAD_APPROX_THREADS", WGRAD_APPROX_THREADS) + outs - 1) / outs;
@@ -1056,11 +1069,21 @@ size_t topk_borrowed_partial_bytes(const Geometry &g)
     return need;
 }
 
+// Whether the top-k form of this shape is the fused kernel's: its shape class, unless the LDS gather takes the
+// shape (many output channels on small planes), which is the faster of the two there.
+bool topk_takes_fused(const Geometry &g, int k)
+{
+    const ApproxPlan lds = plan_approx(g, /*allow_lds=*/true, /*allow_fused=*/false, /*allow_mm=*/false);
+    if (lds.use_lds && lds.m * k <= 64) return false;
+    return plan_approx(g, /*allow_lds=*/false, /*allow_fused=*/true, /*allow_mm=*/false).fused != 0;
+}
+
 // Top-k through the fused kernel (selection and gather in one launch, positions never leave registers).
 // False if the shape is not one the fused form takes.
 bool topk_fused(const Geometry &g, const void *X, const void *dY, int k, float scale, float *dW,
                 int32_t *idx_out, float *sum_out, float *partials, hipStream_t st, int *rc)
 {
+    if (!topk_takes_fused(g, k)) return false;
     const ApproxPlan pl = plan_approx(g, /*allow_lds=*/false, /*allow_fused=*/true, /*allow_mm=*/false);
     if (!pl.fused || ((uintptr_t)dY % (g.bf16 ? 8 : 16)) != 0) return false;
     const long outs = g.dw_elems();
@@ -1072,8 +1095,8 @@ bool topk_fused(const Geometry &g, const void *X, const void *dY, int k, float s
     FusedParams fp;
     fp.chunk_n = pl.chunk_n; fp.scale = pl.chunks > 1 ? 1.0f : scale;
     fp.d_rs = FastDiv(g.R * g.S); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
-    fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = k; fp.inv_k = 1.0f / k;
-    const dim3 grid(g.K, pl.chunks, 1);
+    fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = k; fp.inv_k = 1.0f / k; fp.nslice = fused_slices(g);
+    const dim3 grid(g.K * fp.nslice, pl.chunks, 1);
     if (g.bf16) WGRAD_LAUNCH((approx_fused_topk<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
     else        WGRAD_LAUNCH((approx_fused_topk<false>), grid, dim3(kBlock), 0, st, ab, g, fp);
     *rc = launch_status();
@@ -1150,7 +1173,8 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
             chunks = (g.N + 4 * per_wave - 1) / (4 * per_wave);
         } else {
             // the workgroup target is for the whole launch: a batch chunks each problem less finely
-            chunks = (tune_int("WGRAD_FUSED_BLOCKS", 768) + (long)g.K * b.n - 1) / ((long)g.K * b.n);
+            const long wgs = (long)g.K * fused_slices(g) * b.n;
+            chunks = (tune_int("WGRAD_FUSED_BLOCKS", 768) + wgs - 1) / wgs;
         }
         if (chunks < 1) chunks = 1;
         if (chunks < pl.chunks) {       // never more than planned: the workspace holds pl.chunks partials
@@ -1215,7 +1239,7 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         FusedParams fp;
         fp.chunk_n = pl.chunk_n; fp.scale = kscale;
         fp.d_rs = FastDiv(g.R * g.S); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
-        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = 1; fp.inv_k = 1.0f;
+        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = 1; fp.inv_k = 1.0f; fp.nslice = fused_slices(g);
         if (fq) {
             // part of a multi-group launch (groups of one element type)
             if (fq->n == kFusedMultiMax || (fq->n > 0 && fq->bf16 != g.bf16)) {
@@ -1226,7 +1250,7 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
             fq->bf16 = g.bf16;
             G.ab = ab; G.g = g; G.fp = fp; G.nchunks = pl.chunks; G.nprob = b.n;
         } else {
-            const dim3 grid((unsigned)g.K, (unsigned)pl.chunks, (unsigned)b.n);
+            const dim3 grid((unsigned)(g.K * fp.nslice), (unsigned)pl.chunks, (unsigned)b.n);
             if (g.bf16) WGRAD_LAUNCH((approx_fused<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
             else        WGRAD_LAUNCH((approx_fused<false>), grid, dim3(kBlock), 0, st, ab, g, fp);
             rc = launch_status();
@@ -1288,8 +1312,8 @@ int launch_approx_nhwc(const Geometry &g, const void *X, const void *dY, float *
         FusedParams fp;
         fp.chunk_n = pl.chunk_n; fp.scale = kscale;
         fp.d_rs = FastDiv(g.C); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
-        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = dw_layout; fp.tk = 1; fp.inv_k = 1.0f;
-        const dim3 grid(g.K, pl.chunks, 1);
+        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = dw_layout; fp.tk = 1; fp.inv_k = 1.0f; fp.nslice = fused_slices(g);
+        const dim3 grid(g.K * fp.nslice, pl.chunks, 1);
         if (g.bf16) WGRAD_LAUNCH((approx_fused_nhwc<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
         else        WGRAD_LAUNCH((approx_fused_nhwc<false>), grid, dim3(kBlock), 0, st, ab, g, fp);
         rc = launch_status();

@@ -189,7 +189,7 @@ bool topk_sparse_exact(const Geometry &g, int k, ExactPlan &ex)
     // the bf16 matrix-core kernel runs a dense layer in the time the gather needs for one kept position
     const bool fast_bf16 = ex.mm16 && k >= 2;
     // large maps, few channels: the fused kernel, unless the bf16 matrix core beats it (maps of up to 256 positions)
-    if (plan_approx(g, /*allow_lds=*/false, /*allow_fused=*/true, /*allow_mm=*/false).fused) return fast_bf16 && L <= 256;
+    if (topk_takes_fused(g, k)) return fast_bf16 && L <= 256;
     const ApproxPlan ap = plan_approx(g, /*allow_lds=*/true, /*allow_fused=*/false, /*allow_mm=*/false);
     const bool lds = ap.use_lds && ap.m * k <= 64;
     const bool dense_enough = L <= 4 || (lds ? k >= 2 && k * 14 >= L : k * 80 >= L);
@@ -250,7 +250,7 @@ int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *
     ExactPlan ex;
     const bool sx = topk_sparse_exact(g, k, ex);
     void *sparse = sx ? (void *)partials : nullptr;
-    // maps of up to 1024 positions and C*R*S <= 576: selection and gather in one launch
+    // maps of up to 1024 positions and C*R*S <= 2304: selection and gather in one launch
     if (!sx && topk_fused(g, X, dY, k, scale, dW, idx_out, sum_out, partials, st, &rc)) return rc;
 
     const bool wide = len > 1024;

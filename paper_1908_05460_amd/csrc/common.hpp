@@ -141,6 +141,7 @@ constexpr int kTopKMax = 64;
 bool topk_supported(const Geometry &g, int k);
 size_t topk_ws_bytes(const Geometry &g, int k);
 size_t topk_borrowed_partial_bytes(const Geometry &g);
+bool topk_takes_fused(const Geometry &g, int k);
 bool topk_fused(const Geometry &g, const void *X, const void *dY, int k, float scale, float *dW,
                 int32_t *idx_out, float *sum_out, float *partials, hipStream_t st, int *rc);
 bool topk_gather_lds(const Geometry &g, const void *X, const int32_t *hw, const float *sum, int k, float scale,

@@ -13,7 +13,7 @@ pytestmark = pytest.mark.gpu
 
 LAYOUTS = [B.DW_OIHW, B.DW_OHWI, B.DW_HWIO]
 assert (B.DW_OIHW, B.DW_OHWI, B.DW_HWIO) == (oracle.OIHW, oracle.OHWI, oracle.HWIO)
-CASES = [SMALL[i] for i in (0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 16, 17, 20, 24, 25, 26)]
+CASES = [SMALL[i] for i in (0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 12, 13, 14, 16, 17, 20, 24, 25, 26, 27, 28, 29, 30)]
 
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])

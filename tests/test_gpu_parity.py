@@ -40,6 +40,9 @@ SMALL = [
     (2, 2, 20, 20, 4, 17, 3, 1, 1, 8, 1),       # tall filter (R > 16)
     (2, 1, 24, 24, 3, 9, 9, 1, 1, 4, 4),        # 81 taps: more than the fused form's tap mask holds
     (11, 16, 1, 4, 32, 3, 3, 1, 1, 1, 1),       # 1x4 planes: maps of four positions (fp32: exact kernel on the sparsified dY)
+    (6, 128, 16, 16, 24, 3, 3, 1, 1, 1, 1),     # 1152 entries per output channel: two slices of the fused form
+    (3, 200, 8, 8, 10, 3, 3, 1, 1, 1, 1),       # 1800 entries: four slices, a ragged last one; 8x8 maps
+    (5, 70, 12, 12, 7, 5, 5, 1, 1, 2, 2),       # 1750 entries of a 5x5 filter
 ]
 
 

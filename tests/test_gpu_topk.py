@@ -30,7 +30,7 @@ def check(d, X, dY, k, dtype, scale=1.0):
 
 @pytest.mark.parametrize("dtype", ["fp32", "bf16"])
 @pytest.mark.parametrize("k", [1, 2, 3, 4, 8])
-@pytest.mark.parametrize("t", [SMALL[i] for i in (0, 1, 2, 4, 5, 6, 7, 8, 11, 13, 14, 15, 17, 20, 24, 25, 26)])
+@pytest.mark.parametrize("t", [SMALL[i] for i in (0, 1, 2, 4, 5, 6, 7, 8, 11, 13, 14, 15, 17, 20, 24, 25, 26, 27, 28, 29, 30)])
 def test_topk_matches_oracle(t, k, dtype):
     d = mk(t, dtype)
     if k > d.Ho * d.Wo:
