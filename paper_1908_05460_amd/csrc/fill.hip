@@ -85,7 +85,7 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 }
 
 // The four values of generator call c: stream positions 4c .. 4c+3.  Words (0,1) and (2,3) are two
-// Box-Muller pairs, u = ((word >> 8) + 0.5) / 2^24 (strictly inside (0,1), exact in fp32); a pair gives
+// Box-Muller pairs, u = ((word >> 8) + 0.5) / 2^24 (strictly inside (0,1)); a pair gives
 // sigma * sqrt(-2 ln u1) * cos(2 pi u2) for the even position and the sine for the odd one.
 __device__ __forceinline__ void normal4_at(uint64_t c, float sigma, uint64_t seed, float (&z)[4])
 {
@@ -93,13 +93,20 @@ __device__ __forceinline__ void normal4_at(uint64_t c, float sigma, uint64_t see
     philox4x32_10((uint32_t)c, (uint32_t)(c >> 32), 0u, 0u, (uint32_t)seed, (uint32_t)(seed >> 32), w);
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
-        const float u1 = ((float)(w[2 * p] >> 8) + 0.5f) * (1.0f / 16777216.0f);
-        const float u2 = ((float)(w[2 * p + 1] >> 8) + 0.5f) * (1.0f / 16777216.0f);
-        const float radius = sigma * sqrtf(-2.0f * logf(u1));
+        // k + 0.5 is exact in fp32 only for k < 2^23; the upper half of the range is taken from the other end,
+        // u = 1 - (m + 0.5) / 2^24 with m = 2^24 - 1 - k < 2^23, which is exact again: ln u = log1p(-(m + 0.5) / 2^24)
+        // (near u = 1, where the radius is small, a rounded u would cost the radius four digits), and the
+        // angle 2 pi u is the angle -2 pi (m + 0.5) / 2^24
+        const uint32_t k1 = w[2 * p] >> 8, k2 = w[2 * p + 1] >> 8;
+        const bool hi1 = k1 >= (1u << 23), hi2 = k2 >= (1u << 23);
+        const float f1 = ((float)(hi1 ? 16777215u - k1 : k1) + 0.5f) * (1.0f / 16777216.0f);
+        const float f2 = ((float)(hi2 ? 16777215u - k2 : k2) + 0.5f) * (1.0f / 16777216.0f);
+        const float ln_u1 = hi1 ? log1pf(-f1) : logf(f1);
+        const float radius = sigma * sqrtf(-2.0f * ln_u1);
         float sn, cs;
-        sincospif(2.0f * u2, &sn, &cs);
+        sincospif(2.0f * f2, &sn, &cs);
         z[2 * p] = radius * cs;
-        z[2 * p + 1] = radius * sn;
+        z[2 * p + 1] = radius * (hi2 ? -sn : sn);
     }
 }
 

@@ -223,6 +223,22 @@ def test_zero_gradient():
     assert not dW.any()
 
 
+def test_random_gradient_small_radii_are_accurate():
+    """19 million draws: a few of them have u1 within 1e-6 of 1, where the radius sqrt(-2 ln u1) is small and a
+    uniform that was rounded to fp32 would cost it several digits.  Absolute and relative accuracy of every value."""
+    import torch
+    d = B.desc(1, 1024, 8, 8, 2048)
+    n = d.K * d.C * 9
+    sigma, seed, offset = 1 / 128, 20190814, 3
+    dW = torch.empty((d.K, d.C, 3, 3), device="cuda")
+    B.conv_wgrad_random(d, dW, sigma, seed, offset)
+    got = dW.cpu().numpy().ravel().astype(np.float64)
+    want = oracle.random_normal(seed, offset, n, sigma)
+    assert np.abs(got - want).max() <= 2e-6 * sigma
+    big = np.abs(want) > 1e-4 * sigma
+    assert (np.abs(got - want)[big] / np.abs(want)[big]).max() <= 1e-4
+
+
 def test_random_gradient_matches_oracle_stream_value_by_value():
     import torch
     d = B.desc(1, 64, 8, 8, 129)                      # 74304 values
