@@ -283,7 +283,15 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
     FusedQueue *fq = napprox > 1 && tune_int("WGRAD_FUSED_MULTI", 1) ? fused_queue_new() : nullptr;
     // groups that run on the bf16 matrix core (exact ones, and approximated ones through the sparse operand)
     // are collected for launches that carry several shapes
-    Bf16Queue *bq = tune_int("WGRAD_BF16_MULTI", 1) ? bf16_queue_new() : nullptr;
+    // (a group alone keeps its own launch: it has to fill the chip by itself)
+    int nbf16 = 0;
+    for (int i = 0; i < nlayers; ++i) {
+        if ((method[i] != WGRAD_EXACT && method[i] != WGRAD_APPROX) || group[i] != i || layers[i].dtype != WGRAD_BF16) continue;
+        Geometry g;
+        make_geometry(&layers[i], g);
+        nbf16 += method[i] == WGRAD_EXACT ? plan_exact(g).mm16 : plan_approx(g).mm;
+    }
+    Bf16Queue *bq = nbf16 > 1 && tune_int("WGRAD_BF16_MULTI", 1) ? bf16_queue_new() : nullptr;
     char *ws_next = (char *)ws;
     int rc = WGRAD_OK;
     for (int i = 0; i < nlayers && rc == WGRAD_OK; ++i) {

@@ -1221,6 +1221,12 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
             const int splits = choose_splits(ex, b.n);
             if (splits < ex.splits) ex.splits = splits;
         }
+        if (bq) {
+            // one of several groups in a launch: fewer, longer workgroups (see launch_exact); the sparse operand
+            // costs no loads, so the partial results weigh more here and the best count is lower still
+            const int splits = choose_splits(ex, b.n, tune_int("WGRAD_BF16_MULTI_BLOCKS_SPARSE", 128));
+            if (splits < ex.splits) ex.splits = splits;
+        }
         SparseA sp{};
         float *out[kMaxBatch];
         const long prob_stride = (long)(plan.ws_bytes / 4);

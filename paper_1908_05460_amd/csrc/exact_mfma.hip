@@ -638,6 +638,13 @@ int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void 
             const int splits = choose_splits(pl, b.n, mq_blocks > 0 ? mq_blocks : 256);
             if (splits < pl.splits) pl.splits = splits;
         }
+        if (bq && pl.mm16) {
+            // one of several groups in a launch: the next group's workgroups fill the chip as this one's finish, so
+            // half as many, twice as long, do -- half the partial results, and a workgroup's set-up and
+            // write-out (a fifth of its life) paid half as often
+            const int splits = choose_splits(pl, b.n, tune_int("WGRAD_BF16_MULTI_BLOCKS", 256));
+            if (splits < pl.splits) pl.splits = splits;
+        }
         float *out[kMaxBatch];
         const long prob_stride = (long)pl.splits * g.dw_elems();
         for (int i = 0; i < b.n; ++i) out[i] = pl.splits > 1 ? (float *)ws + i * prob_stride : b.dW[i];
