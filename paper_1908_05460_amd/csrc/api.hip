@@ -303,8 +303,15 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
             if (group[j] == i) { b.X[b.n] = X[j]; b.dY[b.n] = dY[j]; b.dW[b.n] = dW[j]; ++b.n; }
         if (method[i] == WGRAD_EXACT) {
             int share = 0;
-            // 768 in all: three per CU, all resident at once, so a workgroup's fixed cost is paid once per CU slot
-            if (mq) share = (int)(tune_int("WGRAD_MULTI_TOTAL", 768) * group_flops(i) / exact_flops + 0.5);
+            // 768 in all -- three per CU, all resident at once, so a workgroup's fixed cost is paid once per CU
+            // slot -- while a workgroup's share stays near 100 us; stacks with more work than that get two or
+            // three rounds of 768, which evens out the groups' different speeds at the end of the launch
+            // (VGG-19 at N = 128, 102 GFLOP: 768 -> 2304 workgroups, exact phase -7 %)
+            if (mq) {
+                int rounds = (int)(exact_flops / 34e9 + 0.5);
+                rounds = rounds < 1 ? 1 : (rounds > 3 ? 3 : rounds);
+                share = (int)(tune_int("WGRAD_MULTI_TOTAL", 768 * rounds) * group_flops(i) / exact_flops + 0.5);
+            }
             rc = launch_exact(g, plan_exact(g), b, ws_next, st, &queue, mq, share < 8 ? 8 : share, bq);
         }
         else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue, fq, bq);

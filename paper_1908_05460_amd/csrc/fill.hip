@@ -94,14 +94,18 @@ __device__ __forceinline__ void normal4_at(uint64_t c, float sigma, uint64_t see
 #pragma unroll
     for (int p = 0; p < 2; ++p) {
         // k + 0.5 is exact in fp32 only for k < 2^23; the upper half of the range is taken from the other end,
-        // u = 1 - (m + 0.5) / 2^24 with m = 2^24 - 1 - k < 2^23, which is exact again: ln u = log1p(-(m + 0.5) / 2^24)
+        // u = 1 - (m + 0.5) / 2^24 with m = 2^24 - 1 - k < 2^23, which is exact again: ln u = ln(1 - (m + 0.5) / 2^24)
         // (near u = 1, where the radius is small, a rounded u would cost the radius four digits), and the
         // angle 2 pi u is the angle -2 pi (m + 0.5) / 2^24
         const uint32_t k1 = w[2 * p] >> 8, k2 = w[2 * p + 1] >> 8;
         const bool hi1 = k1 >= (1u << 23), hi2 = k2 >= (1u << 23);
         const float f1 = ((float)(hi1 ? 16777215u - k1 : k1) + 0.5f) * (1.0f / 16777216.0f);
         const float f2 = ((float)(hi2 ? 16777215u - k2 : k2) + 0.5f) * (1.0f / 16777216.0f);
-        const float ln_u1 = hi1 ? log1pf(-f1) : logf(f1);
+        // ln(1 - f1): below 2^-7 the series (its fifth-order term is under 1e-9 of the first), above it the
+        // rounding of 1 - f1 no longer matters to a radius of 0.125 and more
+        const float series = -f1 * (1.0f + f1 * (0.5f + f1 * ((1.0f / 3.0f) + f1 * 0.25f)));
+        const float lg = logf(hi1 ? 1.0f - f1 : f1);
+        const float ln_u1 = hi1 && f1 < 0.0078125f ? series : lg;
         const float radius = sigma * sqrtf(-2.0f * ln_u1);
         float sn, cs;
         sincospif(2.0f * f2, &sn, &cs);
