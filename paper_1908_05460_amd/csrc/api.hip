@@ -281,6 +281,7 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
     int napprox = 0;
     for (int i = 0; i < nlayers; ++i) napprox += method[i] == WGRAD_APPROX && group[i] == i;
     FusedQueue *fq = napprox > 1 && tune_int("WGRAD_FUSED_MULTI", 1) ? fused_queue_new() : nullptr;
+    GatherQueue *gq = napprox > 1 && tune_int("WGRAD_GATHER_MULTI", 1) ? gather_queue_new() : nullptr;
     // groups that run on the bf16 matrix core (exact ones, and approximated ones through the sparse operand)
     // are collected for launches that carry several shapes
     // (a group alone keeps its own launch: it has to fill the chip by itself)
@@ -314,13 +315,17 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
             }
             rc = launch_exact(g, plan_exact(g), b, ws_next, st, &queue, mq, share < 8 ? 8 : share, bq);
         }
-        else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue, fq, bq);
+        else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue, fq, bq, gq);
         ws_next += align_up(method_ws(g, method[i])) * b.n;
     }
     if (rc == WGRAD_OK && mq) rc = multi_flush(multi, st);
     if (bq) {
         if (rc == WGRAD_OK) rc = bf16_flush(*bq, st);
         bf16_queue_delete(bq);
+    }
+    if (gq) {
+        if (rc == WGRAD_OK) rc = gather_flush(*gq, st);
+        gather_queue_delete(gq);
     }
     if (fq) {
         if (rc == WGRAD_OK) rc = fused_flush(*fq, st);

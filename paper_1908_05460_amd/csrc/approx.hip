@@ -293,23 +293,24 @@ struct GatherParams {
 
 // TOPK: every map contributes tk patches (its kept positions, hw[(n*K + k)*tk + t]) with weight sum/tk
 // instead of one with weight sum; a group is then limited to nb*M*tk <= 64 (position, weight) pairs.
-template <bool BF16, int M, bool TOPK = false>
-__global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch ab, Geometry g, GatherParams gp)
+// (bx, by, bz): the workgroup's tile (channel tile fastest), batch chunk and problem
+template <bool BF16, int M, bool TOPK>
+__device__ __forceinline__ void gather_lds_body(const ApproxBatch &ab, const Geometry &g, const GatherParams &gp,
+                                                float *__restrict__ xs, int bx, int by, int bz)
 {
-    const void *__restrict__ X = ab.X[blockIdx.z];
-    const int32_t *__restrict__ hw = ab.hw[blockIdx.z];
-    const float *__restrict__ sum = ab.sum[blockIdx.z];
-    float *__restrict__ out = ab.out[blockIdx.z];
+    const void *__restrict__ X = ab.X[bz];
+    const int32_t *__restrict__ hw = ab.hw[bz];
+    const float *__restrict__ sum = ab.sum[bz];
+    float *__restrict__ out = ab.out[bz];
     typedef typename Raw4<BF16>::type raw4;
-    extern __shared__ float xs[];                         // [2][nb][64][pitch]
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int ctile = blockIdx.x % gp.ctiles, ktile = blockIdx.x / gp.ctiles;
+    const int ctile = bx % gp.ctiles, ktile = bx / gp.ctiles;
     const int c0 = ctile * kGatherCT;
     const int k_base = ktile * (kGatherBlock / 64 * M) + wave * M;
     const int HW = g.H * g.W, hw4 = HW >> 2;
     const int nb = gp.nb, pitch = gp.pitch, WP = gp.wp;
-    const int n_begin = blockIdx.y * gp.chunk_n;
+    const int n_begin = by * gp.chunk_n;
     const int n_end = n_begin + gp.chunk_n < g.N ? n_begin + gp.chunk_n : g.N;
     const int cvalid = g.C - c0 < kGatherCT ? g.C - c0 : kGatherCT;   // channels of this tile inside X
     const int run4 = cvalid * hw4;                        // 16-byte pieces per image
@@ -451,7 +452,7 @@ __global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch
         }
     }
     if (lane < cvalid) {
-        float *o = out + (long)blockIdx.y * g.K * g.C * 9;
+        float *o = out + (long)by * g.K * g.C * 9;
 #pragma unroll
         for (int j = 0; j < M; ++j) {
             const int k = k_base + j;
@@ -460,6 +461,43 @@ __global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch
             for (int t = 0; t < 9; ++t) o[((long)k * g.C + c0 + lane) * 9 + t] = acc[j][t] * gp.scale;
         }
     }
+}
+
+template <bool BF16, int M, bool TOPK = false>
+__global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch ab, Geometry g, GatherParams gp)
+{
+    extern __shared__ float xs[];                         // [2][nb][64][pitch]
+    gather_lds_body<BF16, M, TOPK>(ab, g, gp, xs, blockIdx.x, blockIdx.y, blockIdx.z);
+}
+
+// The gathers of several layer groups of a schedule run as one grid (the groups' ramps and tails overlap instead
+// of adding up): a workgroup looks its group up in a table in the kernel arguments, read in place (see the
+// fused form's multi-group launch for why).
+constexpr int kGatherMultiMax = 6;
+struct GatherGroup {
+    ApproxBatch ab;
+    Geometry g;
+    GatherParams gp;
+    int gx, gy;                      // tiles and batch chunks of the group's own grid (z = problems)
+};
+struct GatherMulti {
+    int n;
+    int begin[kGatherMultiMax + 1];  // first workgroup of each group; begin[n] = grid size
+    GatherGroup grp[kGatherMultiMax];
+};
+
+template <bool BF16, int M>
+__global__ __launch_bounds__(kGatherBlock) void approx_gather_lds_multi(const GatherMulti)
+{
+    extern __shared__ float xs[];
+    const GatherMulti *mp = (const GatherMulti *)__builtin_amdgcn_kernarg_segment_ptr();
+    const int n = mp->n;
+    int gi = 0;
+    for (int i = 1; i < n; ++i) gi += (int)blockIdx.x >= mp->begin[i];
+    const GatherGroup &G = mp->grp[gi];
+    const int linear = (int)blockIdx.x - mp->begin[gi];
+    const int bx = linear % G.gx, rest = linear / G.gx;
+    gather_lds_body<BF16, M, false>(G.ab, G.g, G.gp, xs, bx, rest % G.gy, rest / G.gy);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1043,9 +1081,7 @@ ApproxPlan plan_approx(const Geometry &g, bool allow_lds, bool allow_fused, bool
     return pl;
 }
 
-template <bool BF16>
-static void launch_gather_lds(const ApproxPlan &pl, dim3 grid, size_t lds, hipStream_t st, const ApproxBatch &ab,
-                              const Geometry &g, float scale)
+static GatherParams gather_params(const ApproxPlan &pl, const Geometry &g, float scale)
 {
     GatherParams gp;
     gp.ctiles = pl.ctiles; gp.nb = pl.nb; gp.chunk_n = pl.chunk_n; gp.wp = pl.wp; gp.pitch = pl.pitch;
@@ -1053,10 +1089,52 @@ static void launch_gather_lds(const ApproxPlan &pl, dim3 grid, size_t lds, hipSt
     gp.d_w = FastDiv(g.W);
     gp.scale = scale;
     gp.tk = 1; gp.inv_k = 1.0f;
+    return gp;
+}
+
+template <bool BF16>
+static void launch_gather_lds(const ApproxPlan &pl, dim3 grid, size_t lds, hipStream_t st, const ApproxBatch &ab,
+                              const Geometry &g, float scale)
+{
+    const GatherParams gp = gather_params(pl, g, scale);
 #define GL_ARGS grid, dim3(kGatherBlock), lds, st, ab, g, gp
     if (pl.m == 2) WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 2>), GL_ARGS);
     else WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 1>), GL_ARGS);
 #undef GL_ARGS
+}
+
+// LDS gathers of a schedule run collected for one launch: groups of one element type and one M
+struct GatherQueue {
+    int n = 0, bf16 = 0, m = 0;
+    size_t lds = 0;                  // the largest window buffer among the groups
+    int nprob[kGatherMultiMax];
+    GatherGroup grp[kGatherMultiMax];
+};
+
+GatherQueue *gather_queue_new() { return new GatherQueue; }
+void gather_queue_delete(GatherQueue *q) { delete q; }
+
+int gather_flush(GatherQueue &q, hipStream_t st)
+{
+    if (q.n == 0) return WGRAD_OK;
+    GatherMulti m{};
+    m.n = q.n;
+    long blocks = 0;
+    for (int i = 0; i < q.n; ++i) {
+        m.grp[i] = q.grp[i];
+        m.begin[i] = (int)blocks;
+        blocks += (long)q.grp[i].gx * q.grp[i].gy * q.nprob[i];
+    }
+    m.begin[q.n] = (int)blocks;
+    const int bf16 = q.bf16, mm = q.m;
+    const size_t lds = q.lds;
+    q.n = 0; q.lds = 0;
+    if (blocks >= (1l << 31)) return WGRAD_UNSUPPORTED;
+#define GM_ARGS dim3((unsigned)blocks), dim3(kGatherBlock), lds, st, m
+    if (bf16) { if (mm == 2) WGRAD_LAUNCH((approx_gather_lds_multi<true, 2>), GM_ARGS); else WGRAD_LAUNCH((approx_gather_lds_multi<true, 1>), GM_ARGS); }
+    else      { if (mm == 2) WGRAD_LAUNCH((approx_gather_lds_multi<false, 2>), GM_ARGS); else WGRAD_LAUNCH((approx_gather_lds_multi<false, 1>), GM_ARGS); }
+#undef GM_ARGS
+    return launch_status();
 }
 
 // Batch-chunk partials (bytes) that the top-k forms borrowed from this file may need.
@@ -1146,17 +1224,21 @@ bool topk_gather_lds(const Geometry &g, const void *X, const int32_t *hw, const 
 
 int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, float scale,
                   int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer, FusedQueue *fq,
-                  Bf16Queue *bq)
+                  Bf16Queue *bq, GatherQueue *gq)
 {
+    if (!defer) gq = nullptr;       // a queued gather needs its reduction queued behind it
     bool aligned = true;
     for (int i = 0; i < b.n; ++i)
         aligned = aligned && ((uintptr_t)b.X[i] % (g.bf16 ? 8 : 16)) == 0 && ((uintptr_t)b.dY[i] % (g.bf16 ? 8 : 16)) == 0;
     ApproxPlan pl = ((plan.use_lds || plan.fused || plan.mm) && !aligned) ? plan_approx(g, false, false, false) : plan;   // (the sparsified form has no alignment needs: the exact launcher falls back by itself)
     const long outs = g.dw_elems();
-    if (pl.use_lds && b.n > 1) {
+    if (pl.use_lds && (b.n > 1 || gq)) {
         // the workgroup target is for the whole launch: a batch of layers chunks each layer's images less finely
         const long tiles = (long)pl.ctiles * pl.ktiles * b.n;
-        const int want_blocks = tune_int("WGRAD_GATHER_BLOCKS", WGRAD_GATHER_BLOCKS);
+        // (a group that shares its launch with others: half as many, longer workgroups -- the next group's fill the chip
+        // as these finish, and the partial sums halve)
+        const int want_blocks = gq ? tune_int("WGRAD_GATHER_BLOCKS_SHARED", WGRAD_GATHER_BLOCKS / 2)
+                                   : tune_int("WGRAD_GATHER_BLOCKS", WGRAD_GATHER_BLOCKS);
         long chunks = tiles >= want_blocks ? 1 : (want_blocks + tiles - 1) / tiles;
         if (chunks < pl.chunks) {       // never more than planned: the workspace holds pl.chunks partials
             pl.chunk_n = (int)((g.N + chunks - 1) / chunks);
@@ -1270,6 +1352,23 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
     rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st);
     if (rc != WGRAD_OK) return rc;
 
+    if (pl.use_lds && gq) {
+        // part of a multi-group launch (groups of one element type and one M); its reduction is deferred with the others
+        if (gq->n == kGatherMultiMax || (gq->n > 0 && (gq->bf16 != g.bf16 || gq->m != pl.m))) {
+            rc = gather_flush(*gq, st);
+            if (rc != WGRAD_OK) return rc;
+        }
+        const size_t lds = (size_t)2 * pl.nb * kGatherCT * pl.pitch * 4;
+        GatherGroup &G = gq->grp[gq->n];
+        gq->nprob[gq->n++] = b.n;
+        gq->bf16 = g.bf16; gq->m = pl.m;
+        if (lds > gq->lds) gq->lds = lds;
+        G.ab = ab; G.g = g; G.gp = gather_params(pl, g, kscale); G.gx = pl.ctiles * pl.ktiles; G.gy = pl.chunks;
+        if (pl.chunks > 1)
+            return launch_combine((const float *)((char *)ws + pl.off_part), (long)(plan.ws_bytes / 4), pl.chunks, outs,
+                                  scale, b.dW, b.n, st, defer);
+        return WGRAD_OK;
+    }
     if (pl.use_lds) {
         const dim3 grid((unsigned)(pl.ctiles * pl.ktiles), (unsigned)pl.chunks, (unsigned)b.n);
         const size_t lds = (size_t)2 * pl.nb * kGatherCT * pl.pitch * 4;

@@ -127,10 +127,15 @@ struct ApproxPlan {
 };
 ApproxPlan plan_approx(const Geometry &g, bool allow_lds = true, bool allow_fused = true, bool allow_mm = true);
 struct FusedQueue;
+struct GatherQueue;
 int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, hipStream_t st);
 int launch_approx(const Geometry &g, const ApproxPlan &pl, const Batch &b, float scale,
                   int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer = nullptr,
-                  FusedQueue *fq = nullptr, Bf16Queue *bq = nullptr);
+                  FusedQueue *fq = nullptr, Bf16Queue *bq = nullptr, GatherQueue *gq = nullptr);
+// LDS-form gathers of several layer groups, collected for one launch
+GatherQueue *gather_queue_new();
+void gather_queue_delete(GatherQueue *q);
+int gather_flush(GatherQueue &q, hipStream_t st);
 // groups of layers that the fused approximation kernel takes, collected for one launch
 FusedQueue *fused_queue_new();
 void fused_queue_delete(FusedQueue *q);
