@@ -217,7 +217,7 @@ def main():
     phase_ms = {k: max(v, 1e-6) for k, v in phase_ms.items()}
     single = reps > 0
     achieved_tf = tot["flops"] / phase_ms["exact"] / 1e9
-    roofline = {"kernel": "exact phase = wgrad_exact_multi | wgrad_exact_stream | wgrad_exact_bf16 (layer groups folded into launches) + combine_table",
+    roofline = {"kernel": "exact phase = wgrad_exact_multi | wgrad_exact_stream | wgrad_exact_bf16_multi (layer groups folded into launches) + combine_table",
                 "bound": "mfma", "achieved": round(achieved_tf, 3), "peak": MFMA_PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
                 "frac": round(achieved_tf / MFMA_PEAK_TFLOPS[dtype], 4),
                 "traffic": traffic["exact_phase_bytes"] if traffic else None,
@@ -226,7 +226,7 @@ def main():
                 "single_layer_calls": {"sum_us": round(tot["exact_us"], 1),
                                        "tflops": round(tot["flops"] / tot["exact_us"] / 1e6, 2)} if single else None}
     achieved_gbs = tot["approx_bytes"] / phase_ms["approx"] / 1e6
-    roofline_approx = {"kernel": "approx phase = approx_fused_multi | approx_select + (approx_gather_lds3x3 | approx_gather_direct | wgrad_exact_bf16<SPARSE>), + combine_table",
+    roofline_approx = {"kernel": "approx phase = approx_fused_multi | approx_select + (approx_gather_lds_multi | approx_gather_direct | wgrad_exact_bf16_multi<SPARSE>) | sparsify_small + wgrad_exact_stream, + combine_table",
                        "bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
                        "traffic": traffic["approx_phase_bytes"] if traffic else None,
