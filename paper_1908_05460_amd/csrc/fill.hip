@@ -4,20 +4,36 @@
 
 namespace wgrad {
 
+// A workgroup clears kZeroPerBlock consecutive floats: four 16-byte stores per thread, each store instruction
+// of a wavefront covering 1 KB of consecutive addresses (a workgroup per 4 KB spent more time being dispatched
+// than storing).
+constexpr int kZeroPieces = 4;
+constexpr long kZeroPerBlock = (long)kBlock * 4 * kZeroPieces;
+
+__device__ __forceinline__ void zero_block(float *__restrict__ dW, long elems, long block)
+{
+    const bool aligned = ((uintptr_t)dW % 16) == 0;
+#pragma unroll
+    for (int p = 0; p < kZeroPieces; ++p) {
+        const long i = block * kZeroPerBlock + ((long)p * kBlock + threadIdx.x) * 4;
+        if (i + 3 < elems && aligned) {
+            *(float4 *)(dW + i) = make_float4(0.f, 0.f, 0.f, 0.f);
+        } else {
+            for (long j = i; j < elems && j < i + 4; ++j) dW[j] = 0.f;
+        }
+    }
+}
+
 __global__ __launch_bounds__(kBlock) void fill_zero(float *__restrict__ dW, long elems)
 {
-    const long i = ((long)blockIdx.x * kBlock + threadIdx.x) * 4;
-    if (i + 3 < elems && ((uintptr_t)dW % 16) == 0) {
-        *(float4 *)(dW + i) = make_float4(0.f, 0.f, 0.f, 0.f);
-    } else {
-        for (long j = i; j < elems && j < i + 4; ++j) dW[j] = 0.f;
-    }
+    zero_block(dW, elems, blockIdx.x);
 }
 
 int launch_zero(float *dW, long elems, hipStream_t st)
 {
-    const long threads = (elems + 3) / 4;
-    WGRAD_LAUNCH(fill_zero, dim3((unsigned)((threads + kBlock - 1) / kBlock)), dim3(kBlock), 0, st, dW, elems);
+    const long blocks = (elems + kZeroPerBlock - 1) / kZeroPerBlock;
+    if (blocks >= (1l << 31)) return WGRAD_UNSUPPORTED;
+    WGRAD_LAUNCH(fill_zero, dim3((unsigned)(blocks < 1 ? 1 : blocks)), dim3(kBlock), 0, st, dW, elems);
     return launch_status();
 }
 
@@ -40,14 +56,7 @@ __device__ __forceinline__ int table_entry(const FillTable &t)
 __global__ __launch_bounds__(kBlock) void fill_zero_table(const FillTable t)
 {
     const int it = table_entry(t);
-    float *dW = t.dst[it];
-    const long elems = t.elems[it];
-    const long i = ((long)((int)blockIdx.x - t.begin[it]) * kBlock + threadIdx.x) * 4;
-    if (i + 3 < elems && ((uintptr_t)dW % 16) == 0) {
-        *(float4 *)(dW + i) = make_float4(0.f, 0.f, 0.f, 0.f);
-    } else {
-        for (long j = i; j < elems && j < i + 4; ++j) dW[j] = 0.f;
-    }
+    zero_block(t.dst[it], t.elems[it], (long)((int)blockIdx.x - t.begin[it]));
 }
 
 int launch_zero_table(float *const *dW, const long *elems, int n, hipStream_t st)
@@ -57,7 +66,7 @@ int launch_zero_table(float *const *dW, const long *elems, int n, hipStream_t st
     long blocks = 0;
     for (int i = 0; i < n; ++i) {
         t.dst[i] = dW[i]; t.elems[i] = elems[i]; t.begin[i] = (int)blocks;
-        blocks += ((elems[i] + 3) / 4 + kBlock - 1) / kBlock;
+        blocks += (elems[i] + kZeroPerBlock - 1) / kZeroPerBlock;
     }
     if (blocks >= (1l << 31)) return WGRAD_UNSUPPORTED;
     t.begin[n] = (int)blocks;
