@@ -281,7 +281,8 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
     int napprox = 0;
     for (int i = 0; i < nlayers; ++i) napprox += method[i] == WGRAD_APPROX && group[i] == i;
     FusedQueue *fq = napprox > 1 && tune_int("WGRAD_FUSED_MULTI", 1) ? fused_queue_new() : nullptr;
-    GatherQueue *gq = napprox > 1 && tune_int("WGRAD_GATHER_MULTI", 1) ? gather_queue_new() : nullptr;
+    SelectQueue *sq = napprox > 1 && tune_int("WGRAD_SELECT_MULTI", 1) ? select_queue_new() : nullptr;
+    GatherQueue *gq = napprox > 1 && tune_int("WGRAD_GATHER_MULTI", 1) ? gather_queue_new(sq) : nullptr;
     // groups that run on the bf16 matrix core (exact ones, and approximated ones through the sparse operand)
     // are collected for launches that carry several shapes
     // (a group alone keeps its own launch: it has to fill the chip by itself)
@@ -292,7 +293,7 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
         make_geometry(&layers[i], g);
         nbf16 += method[i] == WGRAD_EXACT ? plan_exact(g).mm16 : plan_approx(g).mm;
     }
-    Bf16Queue *bq = nbf16 > 1 && tune_int("WGRAD_BF16_MULTI", 1) ? bf16_queue_new() : nullptr;
+    Bf16Queue *bq = nbf16 > 1 && tune_int("WGRAD_BF16_MULTI", 1) ? bf16_queue_new(sq) : nullptr;
     char *ws_next = (char *)ws;
     int rc = WGRAD_OK;
     for (int i = 0; i < nlayers && rc == WGRAD_OK; ++i) {
@@ -315,8 +316,11 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
             }
             rc = launch_exact(g, plan_exact(g), b, ws_next, st, &queue, mq, share < 8 ? 8 : share, bq);
         }
-        else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue, fq, bq, gq);
+        else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue, fq, bq, gq, sq);
         ws_next += align_up(method_ws(g, method[i])) * b.n;
+    }
+    if (sq) {
+        if (rc == WGRAD_OK) rc = select_flush(*sq, st);
     }
     if (rc == WGRAD_OK && mq) rc = multi_flush(multi, st);
     if (bq) {
@@ -327,6 +331,7 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
         if (rc == WGRAD_OK) rc = gather_flush(*gq, st);
         gather_queue_delete(gq);
     }
+    if (sq) select_queue_delete(sq);
     if (fq) {
         if (rc == WGRAD_OK) rc = fused_flush(*fq, st);
         fused_queue_delete(fq);

@@ -103,18 +103,18 @@ struct ApproxBatch {
     float *out[kMaxBatch];       // dW, or the batch-chunk partials
 };
 
+// (bx, by): the workgroup's number within its problem, and the problem
 template <bool BF16, int VEC>
-__global__ __launch_bounds__(kBlock) void approx_select(ApproxBatch ab, long maps, int len,
-                                                        int Wo, int G, int32_t *__restrict__ flat_out,
-                                                        float *__restrict__ sum_b)
+__device__ __forceinline__ void select_body(const ApproxBatch &ab, long maps, int len, int Wo, int G,
+                                            int32_t *__restrict__ flat_out, float *__restrict__ sum_b, int bx, int by)
 {
     // flat_out / sum_b: optional user outputs, single-problem launches only
-    const void *__restrict__ dY = ab.dY[blockIdx.y];
-    int32_t *__restrict__ hw_out = ab.hw[blockIdx.y];
-    float *__restrict__ sum_a = ab.sum[blockIdx.y];
+    const void *__restrict__ dY = ab.dY[by];
+    int32_t *__restrict__ hw_out = ab.hw[by];
+    float *__restrict__ sum_a = ab.sum[by];
     const int lane = threadIdx.x & 63;
     const int maps_per_wave = 64 / G;
-    const long wave_global = (long)blockIdx.x * (kBlock / 64) + (threadIdx.x >> 6);
+    const long wave_global = (long)bx * (kBlock / 64) + (threadIdx.x >> 6);
     const long map = wave_global * maps_per_wave + lane / G;
     const int gl = lane % G;
 
@@ -163,8 +163,74 @@ __global__ __launch_bounds__(kBlock) void approx_select(ApproxBatch ab, long map
     }
 }
 
+template <bool BF16, int VEC>
+__global__ __launch_bounds__(kBlock) void approx_select(ApproxBatch ab, long maps, int len,
+                                                        int Wo, int G, int32_t *__restrict__ flat_out,
+                                                        float *__restrict__ sum_b)
+{
+    select_body<BF16, VEC>(ab, maps, len, Wo, G, flat_out, sum_b, blockIdx.x, blockIdx.y);
+}
+
+// The selections of several layer groups of a schedule run as one grid (each is a few microseconds of HBM
+// streaming; launched one by one they are mostly ramp and tail).  Group table in the kernel arguments, read in place.
+constexpr int kSelectMultiMax = 6;
+struct SelectGroup {
+    ApproxBatch ab;
+    long maps;
+    int len, Wo, G, gx;              // gx: workgroups per problem
+};
+struct SelectMulti {
+    int n;
+    int begin[kSelectMultiMax + 1];  // first workgroup of each group; begin[n] = grid size
+    SelectGroup grp[kSelectMultiMax];
+};
+
+template <bool BF16, int VEC>
+__global__ __launch_bounds__(kBlock) void approx_select_multi(const SelectMulti)
+{
+    const SelectMulti *mp = (const SelectMulti *)__builtin_amdgcn_kernarg_segment_ptr();
+    const int n = mp->n;
+    int gi = 0;
+    for (int i = 1; i < n; ++i) gi += (int)blockIdx.x >= mp->begin[i];
+    const SelectGroup &G = mp->grp[gi];
+    const int linear = (int)blockIdx.x - mp->begin[gi];
+    select_body<BF16, VEC>(G.ab, G.maps, G.len, G.Wo, G.G, nullptr, nullptr, linear % G.gx, linear / G.gx);
+}
+
+struct SelectQueue {
+    int n = 0, bf16 = 0, vec = 0;
+    int nprob[kSelectMultiMax];
+    SelectGroup grp[kSelectMultiMax];
+};
+
+SelectQueue *select_queue_new() { return new SelectQueue; }
+void select_queue_delete(SelectQueue *q) { delete q; }
+
+int select_flush(SelectQueue &q, hipStream_t st)
+{
+    if (q.n == 0) return WGRAD_OK;
+    SelectMulti m{};
+    m.n = q.n;
+    long blocks = 0;
+    for (int i = 0; i < q.n; ++i) {
+        m.grp[i] = q.grp[i];
+        m.begin[i] = (int)blocks;
+        blocks += (long)q.grp[i].gx * q.nprob[i];
+    }
+    m.begin[q.n] = (int)blocks;
+    const int bf16 = q.bf16, vec = q.vec;
+    q.n = 0;
+    if (blocks >= (1l << 31)) return WGRAD_UNSUPPORTED;
+#define SM_ARGS dim3((unsigned)blocks), dim3(kBlock), 0, st, m
+    if (bf16) { if (vec == 8) WGRAD_LAUNCH((approx_select_multi<true, 8>), SM_ARGS); else WGRAD_LAUNCH((approx_select_multi<true, 1>), SM_ARGS); }
+    else      { if (vec == 4) WGRAD_LAUNCH((approx_select_multi<false, 4>), SM_ARGS); else WGRAD_LAUNCH((approx_select_multi<false, 1>), SM_ARGS); }
+#undef SM_ARGS
+    return launch_status();
+}
+
+// With a queue (and no user outputs) the launch is only recorded there; select_flush issues it with the others.
 static int launch_select_impl(const Geometry &g, const ApproxBatch &ab, int nprob, int32_t *flat_out,
-                              float *sum_b, hipStream_t st)
+                              float *sum_b, hipStream_t st, SelectQueue *sq = nullptr)
 {
     const int len = g.Ho * g.Wo;
     const long maps = (long)g.N * g.K;
@@ -177,6 +243,17 @@ static int launch_select_impl(const Geometry &g, const ApproxBatch &ab, int npro
     while (G < 64 && G * vec * 4 < len) G <<= 1;
     const long waves = (maps + 64 / G - 1) / (64 / G);
     const int grid = (int)((waves + kBlock / 64 - 1) / (kBlock / 64));
+    if (sq && !flat_out && !sum_b) {
+        if (sq->n == kSelectMultiMax || (sq->n > 0 && (sq->bf16 != g.bf16 || sq->vec != vec))) {
+            const int rc = select_flush(*sq, st);
+            if (rc != WGRAD_OK) return rc;
+        }
+        SelectGroup &S = sq->grp[sq->n];
+        sq->nprob[sq->n++] = nprob;
+        sq->bf16 = g.bf16; sq->vec = vec;
+        S.ab = ab; S.maps = maps; S.len = len; S.Wo = g.Wo; S.G = G; S.gx = grid;
+        return WGRAD_OK;
+    }
 #define SEL_ARGS dim3(grid, nprob), dim3(kBlock), 0, st, ab, maps, len, g.Wo, G, flat_out, sum_b
     if (g.bf16) {
         if (vec == 8) WGRAD_LAUNCH((approx_select<true, 8>), SEL_ARGS);
@@ -1105,18 +1182,28 @@ static void launch_gather_lds(const ApproxPlan &pl, dim3 grid, size_t lds, hipSt
 
 // LDS gathers of a schedule run collected for one launch: groups of one element type and one M
 struct GatherQueue {
+    SelectQueue *sel = nullptr;      // selections that must be issued before these gathers
     int n = 0, bf16 = 0, m = 0;
     size_t lds = 0;                  // the largest window buffer among the groups
     int nprob[kGatherMultiMax];
     GatherGroup grp[kGatherMultiMax];
 };
 
-GatherQueue *gather_queue_new() { return new GatherQueue; }
+GatherQueue *gather_queue_new(SelectQueue *selects)
+{
+    GatherQueue *q = new GatherQueue;
+    q->sel = selects;
+    return q;
+}
 void gather_queue_delete(GatherQueue *q) { delete q; }
 
 int gather_flush(GatherQueue &q, hipStream_t st)
 {
     if (q.n == 0) return WGRAD_OK;
+    if (q.sel) {
+        const int rc = select_flush(*q.sel, st);
+        if (rc != WGRAD_OK) return rc;
+    }
     GatherMulti m{};
     m.n = q.n;
     long blocks = 0;
@@ -1224,7 +1311,7 @@ bool topk_gather_lds(const Geometry &g, const void *X, const int32_t *hw, const 
 
 int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, float scale,
                   int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer, FusedQueue *fq,
-                  Bf16Queue *bq, GatherQueue *gq)
+                  Bf16Queue *bq, GatherQueue *gq, SelectQueue *sq)
 {
     if (!defer) gq = nullptr;       // a queued gather needs its reduction queued behind it
     bool aligned = true;
@@ -1296,7 +1383,7 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         return launch_exact(g, pl.ex, eb, (char *)ws + (size_t)b.n * pl.off_part, st, defer);
     }
     if (pl.mm) {
-        rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st);
+        rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st, bq ? sq : nullptr);   // (a queued consumer issues queued selections first)
         if (rc != WGRAD_OK) return rc;
         ExactPlan ex = pl.ex;
         if (b.n > 1) {
@@ -1349,7 +1436,7 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
                                   scale, b.dW, b.n, st, defer);
         return WGRAD_OK;
     }
-    rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st);
+    rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st, pl.use_lds && gq ? sq : nullptr);
     if (rc != WGRAD_OK) return rc;
 
     if (pl.use_lds && gq) {

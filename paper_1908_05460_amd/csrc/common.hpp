@@ -106,7 +106,8 @@ struct SparseA {
 };
 // launches of the bf16 matrix-core kernel collected for one launch that carries several shapes
 struct Bf16Queue;
-Bf16Queue *bf16_queue_new();
+struct SelectQueue;
+Bf16Queue *bf16_queue_new(SelectQueue *selects = nullptr);
 void bf16_queue_delete(Bf16Queue *q);
 int bf16_flush(Bf16Queue &q, hipStream_t st);
 int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st,
@@ -128,12 +129,19 @@ struct ApproxPlan {
 ApproxPlan plan_approx(const Geometry &g, bool allow_lds = true, bool allow_fused = true, bool allow_mm = true);
 struct FusedQueue;
 struct GatherQueue;
+// selections of several layer groups collected for one launch; the queues of their consumers (the LDS gathers, the
+// sparse-operand launches of the bf16 matrix-core kernel) issue it before they issue themselves
+struct SelectQueue;
+SelectQueue *select_queue_new();
+void select_queue_delete(SelectQueue *q);
+int select_flush(SelectQueue &q, hipStream_t st);
 int launch_select(const Geometry &g, const void *dY, int32_t *idx, float *sum, hipStream_t st);
 int launch_approx(const Geometry &g, const ApproxPlan &pl, const Batch &b, float scale,
                   int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer = nullptr,
-                  FusedQueue *fq = nullptr, Bf16Queue *bq = nullptr, GatherQueue *gq = nullptr);
+                  FusedQueue *fq = nullptr, Bf16Queue *bq = nullptr, GatherQueue *gq = nullptr,
+                  SelectQueue *sq = nullptr);
 // LDS-form gathers of several layer groups, collected for one launch
-GatherQueue *gather_queue_new();
+GatherQueue *gather_queue_new(SelectQueue *selects = nullptr);
 void gather_queue_delete(GatherQueue *q);
 int gather_flush(GatherQueue &q, hipStream_t st);
 // groups of layers that the fused approximation kernel takes, collected for one launch

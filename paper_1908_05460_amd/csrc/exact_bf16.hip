@@ -141,12 +141,21 @@ __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_bf16_multi(const Bf16Mu
     }
 }
 
-Bf16Queue *bf16_queue_new() { return new Bf16Queue(); }
+Bf16Queue *bf16_queue_new(SelectQueue *selects)
+{
+    Bf16Queue *q = new Bf16Queue();
+    q->sel = selects;
+    return q;
+}
 void bf16_queue_delete(Bf16Queue *q) { delete q; }
 
 int bf16_flush(Bf16Queue &q, hipStream_t st)
 {
     if (q.n == 0) return WGRAD_OK;
+    if (q.sel) {
+        const int rc = select_flush(*q.sel, st);
+        if (rc != WGRAD_OK) return rc;
+    }
     if (q.n == 1) {
         q.n = 0;
         return bf16_launch_now(q.item[0], st);

@@ -457,6 +457,7 @@ struct Bf16Launch {
     size_t lds;
 };
 struct Bf16Queue {
+    SelectQueue *sel = nullptr;          // selections that must be issued before the sparse-operand launches
     int n = 0, sparse = 0;
     Bf16Launch item[kBf16MultiMax];
 };
