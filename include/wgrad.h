@@ -49,7 +49,7 @@ typedef enum { WGRAD_EXACT = 0, WGRAD_APPROX = 1, WGRAD_ZERO = 2, WGRAD_RANDOM =
 typedef enum {
     WGRAD_OK = 0,
     WGRAD_INVALID_ARG = -1,         /* null pointer, non-positive size, empty output, bad dtype/method */
-    WGRAD_UNSUPPORTED = -2,         /* valid convolution this build has no kernel for                 */
+    WGRAD_UNSUPPORTED = -2,         /* sizes beyond the kernels' 32-bit index ranges; topk out of range */
     WGRAD_WORKSPACE_TOO_SMALL = -3, /* ws_bytes < conv_wgrad_workspace_bytes(), or ws misaligned      */
     WGRAD_LAUNCH_FAILED = -4        /* the HIP runtime refused a launch                               */
 } wgrad_status;
