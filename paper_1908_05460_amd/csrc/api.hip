@@ -380,7 +380,7 @@ const char *conv_wgrad_status_string(int status)
     switch (status) {
         case WGRAD_OK: return "ok";
         case WGRAD_INVALID_ARG: return "invalid argument (null pointer, non-positive size, empty output, bad dtype or method)";
-        case WGRAD_UNSUPPORTED: return "unsupported convolution (no kernel configuration fits it)";
+        case WGRAD_UNSUPPORTED: return "unsupported: a size beyond the kernels' 32-bit index ranges, or top-k out of range";
         case WGRAD_WORKSPACE_TOO_SMALL: return "workspace too small or not 256-byte aligned";
         case WGRAD_LAUNCH_FAILED: return "the HIP runtime refused a kernel launch";
         default: return "unknown status";
