@@ -178,6 +178,22 @@ int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void *const *X,
 size_t conv_wgrad_schedule_workspace_bytes(const wgrad_conv_desc *layers, const uint8_t *method,
                                            int32_t nlayers);
 
+/* conv_wgrad_schedule_run with the top-k form of the approximation (Section 2.3; see
+ * conv_wgrad_approx_topk) on the layers whose method is WGRAD_APPROX: every such
+ * layer keeps min(topk, Ho*Wo) positions per map.  1 <= topk <= 64, otherwise
+ * WGRAD_UNSUPPORTED.  The approximated layers are enqueued one by one (not folded
+ * into groups); everything else is as in conv_wgrad_schedule_run.
+ * ws: at least conv_wgrad_schedule_topk_workspace_bytes(layers, method, nlayers, topk). */
+int conv_wgrad_schedule_run_topk(const wgrad_conv_desc *layers, const void *const *X,
+                                 const void *const *dY, float *const *dW, const uint8_t *method,
+                                 int32_t nlayers, int32_t topk, float scale, float sigma,
+                                 uint64_t seed, uint64_t offset, void *ws, size_t ws_bytes,
+                                 void *stream);
+
+/* Scratch bytes of the call above; 0 for invalid arguments. */
+size_t conv_wgrad_schedule_topk_workspace_bytes(const wgrad_conv_desc *layers, const uint8_t *method,
+                                                int32_t nlayers, int32_t topk);
+
 /* Static, NUL-terminated description of a status code. */
 const char *conv_wgrad_status_string(int status);
 

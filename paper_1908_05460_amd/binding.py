@@ -21,7 +21,8 @@ EXPORTS = ("conv_wgrad_exact", "conv_wgrad_approx", "conv_wgrad_select", "conv_w
            "conv_wgrad_schedule_workspace_bytes", "conv_wgrad_status_string",
            "conv_wgrad_approx_topk", "conv_wgrad_topk_workspace_bytes",
            "conv_wgrad_approx_nhwc", "conv_wgrad_exact_nhwc", "conv_wgrad_nhwc_workspace_bytes",
-           "conv_wgrad_transpose_x", "conv_wgrad_permute_dw")
+           "conv_wgrad_transpose_x", "conv_wgrad_permute_dw",
+           "conv_wgrad_schedule_run_topk", "conv_wgrad_schedule_topk_workspace_bytes")
 DW_OIHW, DW_OHWI, DW_HWIO = 0, 1, 2
 
 
@@ -97,6 +98,12 @@ def load():
                                           ctypes.c_uint64, ctypes.c_uint64, vp, ctypes.c_size_t, vp]
     L.conv_wgrad_schedule_workspace_bytes.argtypes = [P(ConvDesc), P(ctypes.c_uint8), ctypes.c_int32]
     L.conv_wgrad_schedule_workspace_bytes.restype = ctypes.c_size_t
+    L.conv_wgrad_schedule_run_topk.argtypes = [P(ConvDesc), P(vp), P(vp), P(vp), P(ctypes.c_uint8),
+                                               ctypes.c_int32, ctypes.c_int32, ctypes.c_float, ctypes.c_float,
+                                               ctypes.c_uint64, ctypes.c_uint64, vp, ctypes.c_size_t, vp]
+    L.conv_wgrad_schedule_run_topk.restype = ctypes.c_int
+    L.conv_wgrad_schedule_topk_workspace_bytes.argtypes = [P(ConvDesc), P(ctypes.c_uint8), ctypes.c_int32, ctypes.c_int32]
+    L.conv_wgrad_schedule_topk_workspace_bytes.restype = ctypes.c_size_t
     L.conv_wgrad_status_string.argtypes = [ctypes.c_int]
     L.conv_wgrad_status_string.restype = ctypes.c_char_p
     for f in ("conv_wgrad_exact", "conv_wgrad_approx", "conv_wgrad_select", "conv_wgrad_zero",
@@ -321,6 +328,19 @@ class Schedule:
     def workspace_bytes(self, methods):
         m = (ctypes.c_uint8 * self.n)(*[int(x) for x in methods])
         return load().conv_wgrad_schedule_workspace_bytes(self.descs, m, self.n)
+
+    def workspace_bytes_topk(self, methods, topk):
+        m = (ctypes.c_uint8 * self.n)(*[int(x) for x in methods])
+        return load().conv_wgrad_schedule_topk_workspace_bytes(self.descs, m, self.n, int(topk))
+
+    def run_topk(self, methods, topk, ws, scale=1.0, sigma=1.0 / 128, seed=0, offset=0):
+        m = (ctypes.c_uint8 * self.n)(*[int(x) for x in methods])
+        p, nbytes = _ws_args(ws)
+        rc = load().conv_wgrad_schedule_run_topk(self.descs, self.X, self.dY, self.dW, m, self.n, int(topk),
+                                                 float(scale), float(sigma), int(seed), int(offset),
+                                                 p, nbytes, _stream())
+        if rc != OK:
+            raise WgradError(rc, "conv_wgrad_schedule_run_topk")
 
     def run(self, methods, ws, scale=1.0, sigma=1.0 / 128, seed=0, offset=0):
         m = (ctypes.c_uint8 * self.n)(*[int(x) for x in methods])

@@ -209,16 +209,36 @@ size_t method_ws(const Geometry &g, int method)
 
 }  // namespace
 
-extern "C" size_t conv_wgrad_schedule_workspace_bytes(const wgrad_conv_desc *layers, const uint8_t *method, int32_t nlayers)
+// topk > 0: approximated layers take the top-k form, one launch sequence each (they are not folded into groups);
+// a layer whose maps have fewer than topk positions keeps all of them
+static int layer_topk(const Geometry &g, int topk)
+{
+    const long L = (long)g.Ho * g.Wo;
+    return (long)topk < L ? topk : (int)L;
+}
+
+static void make_groups_topk(const wgrad_conv_desc *layers, const uint8_t *method, int n, int topk, int *group)
+{
+    make_groups(layers, method, n, group);
+    if (topk > 0)
+        for (int i = 0; i < n; ++i)
+            if (method[i] == WGRAD_APPROX) group[i] = i;
+}
+
+static size_t schedule_ws_bytes(const wgrad_conv_desc *layers, const uint8_t *method, int32_t nlayers, int topk)
 {
     if (!layers || !method || nlayers <= 0 || nlayers > 4096) return 0;
     int group[4096];
-    make_groups(layers, method, nlayers, group);
+    make_groups_topk(layers, method, nlayers, topk, group);
     size_t need = 0;
     for (int i = 0; i < nlayers; ++i) {
         if (group[i] != i) continue;
         Geometry g;
         if (make_geometry(&layers[i], g) != WGRAD_OK) return 0;
+        if (topk > 0 && method[i] == WGRAD_APPROX) {
+            need += align_up(topk_ws_bytes(g, layer_topk(g, topk)));
+            continue;
+        }
         int members = 0;
         for (int j = i; j < nlayers; ++j) members += group[j] == i;
         need += align_up(method_ws(g, method[i])) * members;       // every group keeps its partials until the final reduction
@@ -226,10 +246,21 @@ extern "C" size_t conv_wgrad_schedule_workspace_bytes(const wgrad_conv_desc *lay
     return need;
 }
 
-extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void *const *X, const void *const *dY,
-                            float *const *dW, const uint8_t *method, int32_t nlayers, float scale,
-                            float sigma, uint64_t seed, uint64_t offset, void *ws, size_t ws_bytes,
-                            void *stream)
+extern "C" size_t conv_wgrad_schedule_workspace_bytes(const wgrad_conv_desc *layers, const uint8_t *method, int32_t nlayers)
+{
+    return schedule_ws_bytes(layers, method, nlayers, 0);
+}
+
+extern "C" size_t conv_wgrad_schedule_topk_workspace_bytes(const wgrad_conv_desc *layers, const uint8_t *method,
+                                                           int32_t nlayers, int32_t topk)
+{
+    return topk >= 1 && topk <= kTopKMax ? schedule_ws_bytes(layers, method, nlayers, topk) : 0;
+}
+
+static int schedule_run_impl(const wgrad_conv_desc *layers, const void *const *X, const void *const *dY,
+                             float *const *dW, const uint8_t *method, int32_t nlayers, int topk, float scale,
+                             float sigma, uint64_t seed, uint64_t offset, void *ws, size_t ws_bytes,
+                             void *stream)
 {
     if (!layers || !X || !dY || !dW || !method || nlayers <= 0 || nlayers > 4096) return WGRAD_INVALID_ARG;
     // pass 1: validate every layer before anything is enqueued
@@ -246,13 +277,13 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
             return WGRAD_INVALID_ARG;
         }
     }
-    if (!ws_ok(ws, ws_bytes, conv_wgrad_schedule_workspace_bytes(layers, method, nlayers))) return WGRAD_WORKSPACE_TOO_SMALL;
+    if (!ws_ok(ws, ws_bytes, schedule_ws_bytes(layers, method, nlayers, topk))) return WGRAD_WORKSPACE_TOO_SMALL;
 
     // pass 2: enqueue on the caller's stream: one launch sequence per group of exact or approximated
     // layers, then one reduction of all their partial results, then the zero and the random fills
     hipStream_t st = (hipStream_t)stream;
     int group[4096];
-    make_groups(layers, method, nlayers, group);
+    make_groups_topk(layers, method, nlayers, topk, group);
     CombineQueue queue;
     MultiQueue multi;
     int nexact = 0;
@@ -279,7 +310,7 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
         for (int i = 0; i < nlayers; ++i)
             if (method[i] == WGRAD_EXACT && group[i] == i) exact_flops += group_flops(i);
     int napprox = 0;
-    for (int i = 0; i < nlayers; ++i) napprox += method[i] == WGRAD_APPROX && group[i] == i;
+    for (int i = 0; i < nlayers; ++i) napprox += topk == 0 && method[i] == WGRAD_APPROX && group[i] == i;
     FusedQueue *fq = napprox > 1 && tune_int("WGRAD_FUSED_MULTI", 1) ? fused_queue_new() : nullptr;
     SelectQueue *sq = napprox > 1 && tune_int("WGRAD_SELECT_MULTI", 1) ? select_queue_new() : nullptr;
     GatherQueue *gq = napprox > 1 && tune_int("WGRAD_GATHER_MULTI", 1) ? gather_queue_new(sq) : nullptr;
@@ -291,7 +322,7 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
         if ((method[i] != WGRAD_EXACT && method[i] != WGRAD_APPROX) || group[i] != i || layers[i].dtype != WGRAD_BF16) continue;
         Geometry g;
         make_geometry(&layers[i], g);
-        nbf16 += method[i] == WGRAD_EXACT ? plan_exact(g).mm16 : plan_approx(g).mm;
+        nbf16 += method[i] == WGRAD_EXACT ? plan_exact(g).mm16 : (topk == 0 ? plan_approx(g).mm : 0);
     }
     Bf16Queue *bq = nbf16 > 1 && tune_int("WGRAD_BF16_MULTI", 1) ? bf16_queue_new(sq) : nullptr;
     char *ws_next = (char *)ws;
@@ -315,6 +346,12 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
                 share = (int)(tune_int("WGRAD_MULTI_TOTAL", 768 * rounds) * group_flops(i) / exact_flops + 0.5);
             }
             rc = launch_exact(g, plan_exact(g), b, ws_next, st, &queue, mq, share < 8 ? 8 : share, bq);
+        }
+        else if (topk > 0) {
+            const int k = layer_topk(g, topk);
+            rc = launch_approx_topk(g, X[i], dY[i], dW[i], k, scale, nullptr, nullptr, ws_next, st);
+            ws_next += align_up(topk_ws_bytes(g, k));
+            continue;
         }
         else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue, fq, bq, gq, sq);
         ws_next += align_up(method_ws(g, method[i])) * b.n;
@@ -357,6 +394,23 @@ extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void
         }
     }
     return rc;
+}
+
+extern "C" int conv_wgrad_schedule_run(const wgrad_conv_desc *layers, const void *const *X, const void *const *dY,
+                            float *const *dW, const uint8_t *method, int32_t nlayers, float scale,
+                            float sigma, uint64_t seed, uint64_t offset, void *ws, size_t ws_bytes,
+                            void *stream)
+{
+    return schedule_run_impl(layers, X, dY, dW, method, nlayers, 0, scale, sigma, seed, offset, ws, ws_bytes, stream);
+}
+
+extern "C" int conv_wgrad_schedule_run_topk(const wgrad_conv_desc *layers, const void *const *X, const void *const *dY,
+                                 float *const *dW, const uint8_t *method, int32_t nlayers, int32_t topk, float scale,
+                                 float sigma, uint64_t seed, uint64_t offset, void *ws, size_t ws_bytes,
+                                 void *stream)
+{
+    if (topk < 1 || topk > kTopKMax) return WGRAD_UNSUPPORTED;
+    return schedule_run_impl(layers, X, dY, dW, method, nlayers, topk, scale, sigma, seed, offset, ws, ws_bytes, stream);
 }
 
 #ifdef WGRAD_TUNING

@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert set(names) == set(B.EXPORTS) and len(names) == 16
+    assert set(names) == set(B.EXPORTS) and len(names) == 18
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -177,3 +177,20 @@ def test_header_is_plain_c_and_a_c_program_can_call_the_library(lib, tmp_path):
             B.nhwc_workspace_bytes(d, B.APPROX)]
     assert [int(x) for x in out[0].split()] == want
     assert out[1].split()[0] == str(B.INVALID_ARG) and out[1].split(None, 1)[1] == B.status_string(B.INVALID_ARG)
+
+
+def test_topk_schedule_is_validated_on_the_host(lib):
+    d = (B.ConvDesc * 2)(B.desc(2, 3, 8, 8, 4), B.desc(2, 4, 2, 2, 4))
+    m = (ctypes.c_uint8 * 2)(B.APPROX, B.EXACT)
+    wsb = lib.conv_wgrad_schedule_topk_workspace_bytes
+    assert wsb(d, m, 2, 0) == 0 and wsb(d, m, 2, 65) == 0 and wsb(d, m, 2, 4) > 0
+    # a map shorter than topk keeps all of its positions: the 2x2 layer as an approximated one is accepted
+    m2 = (ctypes.c_uint8 * 2)(B.APPROX, B.APPROX)
+    assert wsb(d, m2, 2, 8) > 0
+    vp = ctypes.c_void_p
+    one = (vp * 2)(256, 256)
+    run = lib.conv_wgrad_schedule_run_topk
+    assert run(d, one, one, one, m, 2, 0, 1.0, 1.0, 0, 0, None, 0, None) == B.UNSUPPORTED
+    assert run(d, one, one, one, m, 2, 65, 1.0, 1.0, 0, 0, None, 0, None) == B.UNSUPPORTED
+    assert run(d, one, one, one, m, 2, 4, 1.0, 1.0, 0, 0, None, 0, None) == B.WORKSPACE_TOO_SMALL
+    assert run(d, None, one, one, m, 2, 4, 1.0, 1.0, 0, 0, None, 0, None) == B.INVALID_ARG

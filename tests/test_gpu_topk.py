@@ -147,3 +147,34 @@ def test_tensors_that_are_only_element_aligned(t, dtype):
     want, want_idx, _ = oracle.wgrad_approx_topk(oracle_shape(d), X, dY, k)
     assert np.array_equal(idx.cpu().numpy(), want_idx)
     assert normwise_err(got, want) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("k", [1, 3, 8])
+def test_topk_through_a_schedule_run(k, dtype):
+    """A mixed schedule whose approximated layers take the top-k form: every layer against the oracle; maps
+    shorter than k keep all their positions."""
+    import torch
+    from paper_1908_05460_amd import schedule as sch
+    N = 6
+    stack = [(3, 32, 16, 1), (16, 32, 16, 1), (16, 32, 16, 1), (16, 16, 32, 2), (32, 8, 64, 1), (64, 4, 128, 1),
+             (64, 4, 128, 1), (64, 2, 128, 1), (64, 2, 128, 1)]
+    descs = [B.desc(N, C, H, H, K, stride=st, dtype=B.BF16 if dtype == "bf16" else B.F32) for C, H, K, st in stack]
+    data = [rand_inputs(d, 70 + i, dtype) for i, d in enumerate(descs)]
+    dWs = [torch.full((d.K, d.C, 3, 3), float("nan"), device="cuda") for d in descs]
+    s = B.Schedule(descs, [to_gpu(x) for x, _ in data], [to_gpu(y) for _, y in data], dWs)
+    methods = np.array([sch.APPROX, sch.EXACT, sch.APPROX, sch.APPROX, sch.APPROX, sch.ZERO, sch.APPROX, sch.APPROX,
+                        sch.EXACT], np.uint8)
+    ws = B.alloc_workspace(s.workspace_bytes_topk(methods, k))
+    s.run_topk(methods, k, ws, scale=0.5)
+    for i, d in enumerate(descs):
+        got = dWs[i].cpu().numpy()
+        g = oracle_shape(d)
+        if methods[i] == sch.EXACT:
+            want = oracle.wgrad_exact(g, *data[i])
+        elif methods[i] == sch.APPROX:
+            want = oracle.wgrad_approx_topk(g, *data[i], min(k, d.Ho * d.Wo), scale=0.5)[0]
+        else:
+            assert not got.any()
+            continue
+        assert normwise_err(got, want) <= TOL[dtype], (i, stack[i])
