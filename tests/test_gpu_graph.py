@@ -46,3 +46,29 @@ def test_schedule_run_replays_from_a_graph(dtype):
             torch.cuda.synchronize()
             for i, (a, b) in enumerate(zip(eager, dWs)):
                 assert torch.equal(a, b), (replay, i, STACK[i], int(m[i]))
+
+
+def test_topk_schedule_replays_from_a_graph():
+    import torch
+    N = 8
+    descs = [B.desc(N, C, H, H, K, stride=st) for C, H, K, st in STACK]
+    data = [rand_inputs(d, 90 + i) for i, d in enumerate(descs)]
+    dWs = [torch.zeros((d.K, d.C, 3, 3), device="cuda") for d in descs]
+    s = B.Schedule(descs, [to_gpu(x) for x, _ in data], [to_gpu(y) for _, y in data], dWs)
+    m = np.array([sch.APPROX, sch.EXACT] * 5 + [sch.APPROX], np.uint8)
+    ws = B.alloc_workspace(s.workspace_bytes_topk(m, 4))
+    s.run_topk(m, 4, ws, scale=0.25)
+    torch.cuda.synchronize()
+    eager = [t.clone() for t in dWs]
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        s.run_topk(m, 4, ws, scale=0.25)
+    for replay in range(3):
+        for t in dWs:
+            t.fill_(float("nan"))
+        ws.fill_(replay + 7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for i, (a, b) in enumerate(zip(eager, dWs)):
+            assert torch.equal(a, b), (replay, i, STACK[i], int(m[i]))
