@@ -311,7 +311,9 @@ static int schedule_run_impl(const wgrad_conv_desc *layers, const void *const *X
             if (method[i] == WGRAD_EXACT && group[i] == i) exact_flops += group_flops(i);
     int napprox = 0;
     for (int i = 0; i < nlayers; ++i) napprox += topk == 0 && method[i] == WGRAD_APPROX && group[i] == i;
-    FusedQueue *fq = napprox > 1 && tune_int("WGRAD_FUSED_MULTI", 1) ? fused_queue_new() : nullptr;
+    int ntopk = 0;
+    for (int i = 0; i < nlayers; ++i) ntopk += topk > 0 && method[i] == WGRAD_APPROX;
+    FusedQueue *fq = (napprox > 1 || ntopk > 1) && tune_int("WGRAD_FUSED_MULTI", 1) ? fused_queue_new() : nullptr;
     SelectQueue *sq = napprox > 1 && tune_int("WGRAD_SELECT_MULTI", 1) ? select_queue_new() : nullptr;
     GatherQueue *gq = napprox > 1 && tune_int("WGRAD_GATHER_MULTI", 1) ? gather_queue_new(sq) : nullptr;
     // groups that run on the bf16 matrix core (exact ones, and approximated ones through the sparse operand)
@@ -349,7 +351,7 @@ static int schedule_run_impl(const wgrad_conv_desc *layers, const void *const *X
         }
         else if (topk > 0) {
             const int k = layer_topk(g, topk);
-            rc = launch_approx_topk(g, X[i], dY[i], dW[i], k, scale, nullptr, nullptr, ws_next, st);
+            rc = launch_approx_topk(g, X[i], dY[i], dW[i], k, scale, nullptr, nullptr, ws_next, st, fq, &queue);
             ws_next += align_up(topk_ws_bytes(g, k));
             continue;
         }

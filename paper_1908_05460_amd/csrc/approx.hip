@@ -1010,7 +1010,7 @@ struct FusedMulti {
     FusedGroup grp[kFusedMultiMax];
 };
 
-template <bool BF16>
+template <bool BF16, bool TOPK = false>
 __global__ __launch_bounds__(kBlock) void approx_fused_multi(const FusedMulti)
 {
     __shared__ float red[4][kFusedJ * 64];
@@ -1022,7 +1022,7 @@ __global__ __launch_bounds__(kBlock) void approx_fused_multi(const FusedMulti)
     if (linear >= mp->count[gi]) return;
     FTRACE(0);
     const FusedGroup &G = mp->grp[gi];
-    fused_dispatch<BF16, false, false>(G.ab, G.g, G.fp, red, linear, G.g.K * G.fp.nslice, G.nchunks, G.nprob);
+    fused_dispatch<BF16, false, TOPK>(G.ab, G.g, G.fp, red, linear, G.g.K * G.fp.nslice, G.nchunks, G.nprob);
     FTRACE(3);
 }
 
@@ -1034,7 +1034,7 @@ extern "C" int wgrad_debug_read_trace_fused(long long *host_out)
 #endif
 
 struct FusedQueue {
-    int n = 0, bf16 = 0;
+    int n = 0, bf16 = 0, topk = 0;   // groups of one element type and one form (k = 1 or top-k) per launch
     FusedGroup grp[kFusedMultiMax];
 };
 
@@ -1051,10 +1051,12 @@ int fused_flush(FusedQueue &q, hipStream_t st)
         blocks += (m.count[i] + 7) / 8 * 8;
     }
     m.begin[q.n] = blocks;
-    const bool bf16 = q.bf16;
+    const bool bf16 = q.bf16, topk = q.topk;
     q.n = 0;
-    if (bf16) WGRAD_LAUNCH((approx_fused_multi<true>), dim3((unsigned)blocks), dim3(kBlock), 0, st, m);
-    else      WGRAD_LAUNCH((approx_fused_multi<false>), dim3((unsigned)blocks), dim3(kBlock), 0, st, m);
+#define FM_ARGS dim3((unsigned)blocks), dim3(kBlock), 0, st, m
+    if (topk) { if (bf16) WGRAD_LAUNCH((approx_fused_multi<true, true>), FM_ARGS); else WGRAD_LAUNCH((approx_fused_multi<false, true>), FM_ARGS); }
+    else      { if (bf16) WGRAD_LAUNCH((approx_fused_multi<true, false>), FM_ARGS); else WGRAD_LAUNCH((approx_fused_multi<false, false>), FM_ARGS); }
+#undef FM_ARGS
     return launch_status();
 }
 
@@ -1246,11 +1248,22 @@ bool topk_takes_fused(const Geometry &g, int k)
 // Top-k through the fused kernel (selection and gather in one launch, positions never leave registers).
 // False if the shape is not one the fused form takes.
 bool topk_fused(const Geometry &g, const void *X, const void *dY, int k, float scale, float *dW,
-                int32_t *idx_out, float *sum_out, float *partials, hipStream_t st, int *rc)
+                int32_t *idx_out, float *sum_out, float *partials, hipStream_t st, int *rc,
+                FusedQueue *fq, CombineQueue *defer)
 {
     if (!topk_takes_fused(g, k)) return false;
-    const ApproxPlan pl = plan_approx(g, /*allow_lds=*/false, /*allow_fused=*/true, /*allow_mm=*/false);
+    ApproxPlan pl = plan_approx(g, /*allow_lds=*/false, /*allow_fused=*/true, /*allow_mm=*/false);
     if (!pl.fused || ((uintptr_t)dY % (g.bf16 ? 8 : 16)) != 0) return false;
+    if (!defer || idx_out || sum_out) fq = nullptr;    // a queued launch needs its reduction queued behind it
+    if (fq) {
+        // part of a launch of many layers: chunk for eight images per wavefront (see launch_approx), never finer
+        // than planned (the workspace holds pl.chunks partials)
+        const int chunks = (g.N + 4 * 8 - 1) / (4 * 8);
+        if (chunks >= 1 && chunks < pl.chunks) {
+            pl.chunk_n = (g.N + chunks - 1) / chunks;
+            pl.chunks = (g.N + pl.chunk_n - 1) / pl.chunk_n;
+        }
+    }
     const long outs = g.dw_elems();
     ApproxBatch ab{};
     for (int i = 0; i < kMaxBatch; ++i) {
@@ -1261,13 +1274,24 @@ bool topk_fused(const Geometry &g, const void *X, const void *dY, int k, float s
     fp.chunk_n = pl.chunk_n; fp.scale = pl.chunks > 1 ? 1.0f : scale;
     fp.d_rs = FastDiv(g.R * g.S); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
     fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = k; fp.inv_k = 1.0f / k; fp.nslice = fused_slices(g);
-    const dim3 grid(g.K * fp.nslice, pl.chunks, 1);
-    if (g.bf16) WGRAD_LAUNCH((approx_fused_topk<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
-    else        WGRAD_LAUNCH((approx_fused_topk<false>), grid, dim3(kBlock), 0, st, ab, g, fp);
-    *rc = launch_status();
+    if (fq) {
+        if (fq->n == kFusedMultiMax || (fq->n > 0 && (fq->bf16 != g.bf16 || !fq->topk))) {
+            *rc = fused_flush(*fq, st);
+            if (*rc != WGRAD_OK) return true;
+        }
+        FusedGroup &G = fq->grp[fq->n++];
+        fq->bf16 = g.bf16; fq->topk = 1;
+        G.ab = ab; G.g = g; G.fp = fp; G.nchunks = pl.chunks; G.nprob = 1;
+        *rc = WGRAD_OK;
+    } else {
+        const dim3 grid(g.K * fp.nslice, pl.chunks, 1);
+        if (g.bf16) WGRAD_LAUNCH((approx_fused_topk<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
+        else        WGRAD_LAUNCH((approx_fused_topk<false>), grid, dim3(kBlock), 0, st, ab, g, fp);
+        *rc = launch_status();
+    }
     if (*rc == WGRAD_OK && pl.chunks > 1) {
         float *dst[1] = {dW};
-        *rc = launch_combine(partials, 0, pl.chunks, outs, scale, dst, 1, st, nullptr);
+        *rc = launch_combine(partials, 0, pl.chunks, outs, scale, dst, 1, st, fq ? defer : nullptr);
     }
     return true;
 }
@@ -1417,12 +1441,12 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = 1; fp.inv_k = 1.0f; fp.nslice = fused_slices(g);
         if (fq) {
             // part of a multi-group launch (groups of one element type)
-            if (fq->n == kFusedMultiMax || (fq->n > 0 && fq->bf16 != g.bf16)) {
+            if (fq->n == kFusedMultiMax || (fq->n > 0 && (fq->bf16 != g.bf16 || fq->topk))) {
                 rc = fused_flush(*fq, st);
                 if (rc != WGRAD_OK) return rc;
             }
             FusedGroup &G = fq->grp[fq->n++];
-            fq->bf16 = g.bf16;
+            fq->bf16 = g.bf16; fq->topk = 0;
             G.ab = ab; G.g = g; G.fp = fp; G.nchunks = pl.chunks; G.nprob = b.n;
         } else {
             const dim3 grid((unsigned)(g.K * fp.nslice), (unsigned)pl.chunks, (unsigned)b.n);

@@ -234,8 +234,9 @@ size_t topk_ws_bytes(const Geometry &g, int k)
     return align_up(maps * k * sizeof(int32_t)) + align_up(maps * sizeof(float)) + tail;
 }
 
+// fq, defer: a schedule run's queue of fused launches and of reductions (the fused form then only records its work)
 int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *dW, int k, float scale,
-                       int32_t *idx_out, float *sum_out, void *ws, hipStream_t st)
+                       int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, FusedQueue *fq, CombineQueue *defer)
 {
     const long maps = (long)g.N * g.K;
     const int len = g.Ho * g.Wo;
@@ -251,7 +252,7 @@ int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *
     const bool sx = topk_sparse_exact(g, k, ex);
     void *sparse = sx ? (void *)partials : nullptr;
     // maps of up to 1024 positions and C*R*S <= 2304: selection and gather in one launch
-    if (!sx && topk_fused(g, X, dY, k, scale, dW, idx_out, sum_out, partials, st, &rc)) return rc;
+    if (!sx && topk_fused(g, X, dY, k, scale, dW, idx_out, sum_out, partials, st, &rc, fq, defer)) return rc;
 
     const bool wide = len > 1024;
     // lanes per map: four positions each up to 256 positions, sixteen up to 1024

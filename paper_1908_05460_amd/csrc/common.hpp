@@ -156,11 +156,13 @@ size_t topk_ws_bytes(const Geometry &g, int k);
 size_t topk_borrowed_partial_bytes(const Geometry &g);
 bool topk_takes_fused(const Geometry &g, int k);
 bool topk_fused(const Geometry &g, const void *X, const void *dY, int k, float scale, float *dW,
-                int32_t *idx_out, float *sum_out, float *partials, hipStream_t st, int *rc);
+                int32_t *idx_out, float *sum_out, float *partials, hipStream_t st, int *rc,
+                FusedQueue *fq = nullptr, CombineQueue *defer = nullptr);
 bool topk_gather_lds(const Geometry &g, const void *X, const int32_t *hw, const float *sum, int k, float scale,
                      float *dW, float *partials, size_t partial_cap_bytes, hipStream_t st, int *rc);
 int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *dW, int k, float scale,
-                       int32_t *idx_out, float *sum_out, void *ws, hipStream_t st);
+                       int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, FusedQueue *fq = nullptr,
+                       CombineQueue *defer = nullptr);
 
 // channel-last input and the other filter-gradient layouts (Section 2.4)
 bool dw_layout_ok(int layout);
