@@ -181,9 +181,9 @@ size_t conv_wgrad_schedule_workspace_bytes(const wgrad_conv_desc *layers, const 
 /* conv_wgrad_schedule_run with the top-k form of the approximation (Section 2.3; see
  * conv_wgrad_approx_topk) on the layers whose method is WGRAD_APPROX: every such
  * layer keeps min(topk, Ho*Wo) positions per map.  1 <= topk <= 64, otherwise
- * WGRAD_UNSUPPORTED.  The approximated layers are not folded into groups of one
- * shape (those that take the fused kernel share launches, six layers each);
- * everything else is as in conv_wgrad_schedule_run.
+ * WGRAD_UNSUPPORTED.  Approximated layers of one shape are folded into a group
+ * (and groups into launches) where the fused top-k kernel takes the shape, and
+ * run one by one otherwise; everything else is as in conv_wgrad_schedule_run.
  * ws: at least conv_wgrad_schedule_topk_workspace_bytes(layers, method, nlayers, topk). */
 int conv_wgrad_schedule_run_topk(const wgrad_conv_desc *layers, const void *const *X,
                                  const void *const *dY, float *const *dW, const uint8_t *method,

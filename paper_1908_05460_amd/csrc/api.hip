@@ -217,12 +217,19 @@ static int layer_topk(const Geometry &g, int topk)
     return (long)topk < L ? topk : (int)L;
 }
 
+// Approximated layers of one shape stay a group only where the fused top-k kernel takes the shape (it is the one
+// top-k form that runs several layers in one launch); the workspace is a slice per layer either way.
 static void make_groups_topk(const wgrad_conv_desc *layers, const uint8_t *method, int n, int topk, int *group)
 {
     make_groups(layers, method, n, group);
-    if (topk > 0)
-        for (int i = 0; i < n; ++i)
-            if (method[i] == WGRAD_APPROX) group[i] = i;
+    if (topk <= 0) return;
+    for (int i = 0; i < n; ++i) {
+        if (method[i] != WGRAD_APPROX || group[i] != i) continue;
+        Geometry g;
+        if (make_geometry(&layers[i], g) == WGRAD_OK && topk_takes_fused(g, layer_topk(g, topk))) continue;
+        for (int j = i + 1; j < n; ++j)
+            if (group[j] == i) group[j] = j;
+    }
 }
 
 static size_t schedule_ws_bytes(const wgrad_conv_desc *layers, const uint8_t *method, int32_t nlayers, int topk)
@@ -235,12 +242,12 @@ static size_t schedule_ws_bytes(const wgrad_conv_desc *layers, const uint8_t *me
         if (group[i] != i) continue;
         Geometry g;
         if (make_geometry(&layers[i], g) != WGRAD_OK) return 0;
-        if (topk > 0 && method[i] == WGRAD_APPROX) {
-            need += align_up(topk_ws_bytes(g, layer_topk(g, topk)));
-            continue;
-        }
         int members = 0;
         for (int j = i; j < nlayers; ++j) members += group[j] == i;
+        if (topk > 0 && method[i] == WGRAD_APPROX) {
+            need += align_up(topk_ws_bytes(g, layer_topk(g, topk))) * members;
+            continue;
+        }
         need += align_up(method_ws(g, method[i])) * members;       // every group keeps its partials until the final reduction
     }
     return need;
@@ -351,8 +358,13 @@ static int schedule_run_impl(const wgrad_conv_desc *layers, const void *const *X
         }
         else if (topk > 0) {
             const int k = layer_topk(g, topk);
-            rc = launch_approx_topk(g, X[i], dY[i], dW[i], k, scale, nullptr, nullptr, ws_next, st, fq, &queue);
-            ws_next += align_up(topk_ws_bytes(g, k));
+            const size_t slice = align_up(topk_ws_bytes(g, k));
+            // a group of layers in one fused launch where that form takes them; otherwise layer by layer
+            if (!(b.n > 1 && launch_topk_group(g, b, k, scale, ws_next, slice, st, &rc, fq, &queue)))
+                for (int j = 0; j < b.n && rc == WGRAD_OK; ++j)
+                    rc = launch_approx_topk(g, b.X[j], b.dY[j], b.dW[j], k, scale, nullptr, nullptr,
+                                            ws_next + (size_t)j * slice, st, fq, &queue);
+            ws_next += slice * b.n;
             continue;
         }
         else rc = launch_approx(g, plan_approx(g), b, scale, nullptr, nullptr, ws_next, st, &queue, fq, bq, gq, sq);

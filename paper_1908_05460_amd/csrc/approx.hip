@@ -1247,13 +1247,17 @@ bool topk_takes_fused(const Geometry &g, int k)
 
 // Top-k through the fused kernel (selection and gather in one launch, positions never leave registers).
 // False if the shape is not one the fused form takes.
-bool topk_fused(const Geometry &g, const void *X, const void *dY, int k, float scale, float *dW,
-                int32_t *idx_out, float *sum_out, float *partials, hipStream_t st, int *rc,
+// b: one problem, or (schedule runs) several layers of this geometry; problem i keeps its batch-chunk partials at
+// partials + i * partial_stride floats.
+bool topk_fused(const Geometry &g, const Batch &b, int k, float scale,
+                int32_t *idx_out, float *sum_out, float *partials, long partial_stride, hipStream_t st, int *rc,
                 FusedQueue *fq, CombineQueue *defer)
 {
     if (!topk_takes_fused(g, k)) return false;
     ApproxPlan pl = plan_approx(g, /*allow_lds=*/false, /*allow_fused=*/true, /*allow_mm=*/false);
-    if (!pl.fused || ((uintptr_t)dY % (g.bf16 ? 8 : 16)) != 0) return false;
+    if (!pl.fused) return false;
+    for (int i = 0; i < b.n; ++i)
+        if (((uintptr_t)b.dY[i] % (g.bf16 ? 8 : 16)) != 0) return false;
     if (!defer || idx_out || sum_out) fq = nullptr;    // a queued launch needs its reduction queued behind it
     if (fq) {
         // part of a launch of many layers: chunk for eight images per wavefront (see launch_approx), never finer
@@ -1267,8 +1271,9 @@ bool topk_fused(const Geometry &g, const void *X, const void *dY, int k, float s
     const long outs = g.dw_elems();
     ApproxBatch ab{};
     for (int i = 0; i < kMaxBatch; ++i) {
-        ab.X[i] = X; ab.dY[i] = dY;
-        ab.out[i] = pl.chunks > 1 ? partials : dW;
+        const int j = i < b.n ? i : 0;
+        ab.X[i] = b.X[j]; ab.dY[i] = b.dY[j];
+        ab.out[i] = pl.chunks > 1 ? partials + j * partial_stride : b.dW[j];
     }
     FusedParams fp;
     fp.chunk_n = pl.chunk_n; fp.scale = pl.chunks > 1 ? 1.0f : scale;
@@ -1281,18 +1286,16 @@ bool topk_fused(const Geometry &g, const void *X, const void *dY, int k, float s
         }
         FusedGroup &G = fq->grp[fq->n++];
         fq->bf16 = g.bf16; fq->topk = 1;
-        G.ab = ab; G.g = g; G.fp = fp; G.nchunks = pl.chunks; G.nprob = 1;
+        G.ab = ab; G.g = g; G.fp = fp; G.nchunks = pl.chunks; G.nprob = b.n;
         *rc = WGRAD_OK;
     } else {
-        const dim3 grid(g.K * fp.nslice, pl.chunks, 1);
+        const dim3 grid(g.K * fp.nslice, pl.chunks, (unsigned)b.n);
         if (g.bf16) WGRAD_LAUNCH((approx_fused_topk<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
         else        WGRAD_LAUNCH((approx_fused_topk<false>), grid, dim3(kBlock), 0, st, ab, g, fp);
         *rc = launch_status();
     }
-    if (*rc == WGRAD_OK && pl.chunks > 1) {
-        float *dst[1] = {dW};
-        *rc = launch_combine(partials, 0, pl.chunks, outs, scale, dst, 1, st, fq ? defer : nullptr);
-    }
+    if (*rc == WGRAD_OK && pl.chunks > 1)
+        *rc = launch_combine(partials, partial_stride, pl.chunks, outs, scale, b.dW, b.n, st, fq ? defer : nullptr);
     return true;
 }
 

@@ -234,6 +234,17 @@ size_t topk_ws_bytes(const Geometry &g, int k)
     return align_up(maps * k * sizeof(int32_t)) + align_up(maps * sizeof(float)) + tail;
 }
 
+bool launch_topk_group(const Geometry &g, const Batch &b, int k, float scale, void *ws, size_t slice_bytes,
+                       hipStream_t st, int *rc, FusedQueue *fq, CombineQueue *defer)
+{
+    ExactPlan ex;
+    if (topk_sparse_exact(g, k, ex)) return false;         // that form runs layer by layer
+    // a slice holds the kept positions, the sums, then the partials (as in launch_approx_topk)
+    const long maps = (long)g.N * g.K;
+    const size_t off = align_up((size_t)maps * k * sizeof(int32_t)) + align_up((size_t)maps * sizeof(float));
+    return topk_fused(g, b, k, scale, nullptr, nullptr, (float *)((char *)ws + off), (long)(slice_bytes / 4), st, rc, fq, defer);
+}
+
 // fq, defer: a schedule run's queue of fused launches and of reductions (the fused form then only records its work)
 int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *dW, int k, float scale,
                        int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, FusedQueue *fq, CombineQueue *defer)
@@ -252,7 +263,9 @@ int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *
     const bool sx = topk_sparse_exact(g, k, ex);
     void *sparse = sx ? (void *)partials : nullptr;
     // maps of up to 1024 positions and C*R*S <= 2304: selection and gather in one launch
-    if (!sx && topk_fused(g, X, dY, k, scale, dW, idx_out, sum_out, partials, st, &rc, fq, defer)) return rc;
+    Batch one{};
+    one.n = 1; one.X[0] = X; one.dY[0] = dY; one.dW[0] = dW;
+    if (!sx && topk_fused(g, one, k, scale, idx_out, sum_out, partials, 0, st, &rc, fq, defer)) return rc;
 
     const bool wide = len > 1024;
     // lanes per map: four positions each up to 256 positions, sixteen up to 1024

@@ -155,9 +155,13 @@ bool topk_supported(const Geometry &g, int k);
 size_t topk_ws_bytes(const Geometry &g, int k);
 size_t topk_borrowed_partial_bytes(const Geometry &g);
 bool topk_takes_fused(const Geometry &g, int k);
-bool topk_fused(const Geometry &g, const void *X, const void *dY, int k, float scale, float *dW,
-                int32_t *idx_out, float *sum_out, float *partials, hipStream_t st, int *rc,
+bool topk_fused(const Geometry &g, const Batch &b, int k, float scale,
+                int32_t *idx_out, float *sum_out, float *partials, long partial_stride, hipStream_t st, int *rc,
                 FusedQueue *fq = nullptr, CombineQueue *defer = nullptr);
+// layers of one geometry of a schedule run through the fused top-k form in one group; false if the form does not
+// take them (the caller then runs them one by one).  ws: the members' workspace slices, slice_bytes apart.
+bool launch_topk_group(const Geometry &g, const Batch &b, int k, float scale, void *ws, size_t slice_bytes,
+                       hipStream_t st, int *rc, FusedQueue *fq, CombineQueue *defer);
 bool topk_gather_lds(const Geometry &g, const void *X, const int32_t *hw, const float *sum, int k, float scale,
                      float *dW, float *partials, size_t partial_cap_bytes, hipStream_t st, int *rc);
 int launch_approx_topk(const Geometry &g, const void *X, const void *dY, float *dW, int k, float scale,

@@ -163,8 +163,18 @@ def test_topk_through_a_schedule_run(k, dtype):
     data = [rand_inputs(d, 70 + i, dtype) for i, d in enumerate(descs)]
     dWs = [torch.full((d.K, d.C, 3, 3), float("nan"), device="cuda") for d in descs]
     s = B.Schedule(descs, [to_gpu(x) for x, _ in data], [to_gpu(y) for _, y in data], dWs)
-    methods = np.array([sch.APPROX, sch.EXACT, sch.APPROX, sch.APPROX, sch.APPROX, sch.ZERO, sch.APPROX, sch.APPROX,
-                        sch.EXACT], np.uint8)
+    # two masks: a mixed one, and one whose repeated shapes are all approximated (those that the fused form takes run
+    # as one group of the multi-group launch, the others layer by layer)
+    for methods in (np.array([sch.APPROX, sch.EXACT, sch.APPROX, sch.APPROX, sch.APPROX, sch.ZERO, sch.APPROX, sch.APPROX,
+                              sch.EXACT], np.uint8),
+                    np.array([sch.APPROX] * 8 + [sch.EXACT], np.uint8)):
+        for t in dWs:
+            t.fill_(float("nan"))
+        check_topk_schedule(s, methods, k, descs, data, dWs, stack, dtype)
+
+
+def check_topk_schedule(s, methods, k, descs, data, dWs, stack, dtype):
+    from paper_1908_05460_amd import schedule as sch
     ws = B.alloc_workspace(s.workspace_bytes_topk(methods, k))
     s.run_topk(methods, k, ws, scale=0.5)
     for i, d in enumerate(descs):
