@@ -194,3 +194,16 @@ def test_topk_schedule_is_validated_on_the_host(lib):
     assert run(d, one, one, one, m, 2, 65, 1.0, 1.0, 0, 0, None, 0, None) == B.UNSUPPORTED
     assert run(d, one, one, one, m, 2, 4, 1.0, 1.0, 0, 0, None, 0, None) == B.WORKSPACE_TOO_SMALL
     assert run(d, None, one, one, m, 2, 4, 1.0, 1.0, 0, 0, None, 0, None) == B.INVALID_ARG
+
+
+def test_topk_schedule_workspace_is_a_slice_per_layer(lib):
+    shapes = [(3, 32, 16), (16, 32, 16), (16, 32, 16), (64, 4, 128), (64, 4, 128), (64, 2, 128)]
+    descs = [B.desc(8, C, H, H, K) for C, H, K in shapes]
+    arr = (B.ConvDesc * len(descs))(*descs)
+    m = (ctypes.c_uint8 * len(descs))(*([B.APPROX] * len(descs)))
+    for k in (1, 4, 9):
+        want = 0
+        for d in descs:
+            per = B.topk_workspace_bytes(d, min(k, d.Ho * d.Wo))
+            want += (per + 255) // 256 * 256
+        assert lib.conv_wgrad_schedule_topk_workspace_bytes(arr, m, len(descs), k) == want
