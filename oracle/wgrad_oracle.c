@@ -139,18 +139,27 @@ int oracle_wgrad_exact_at(const oracle_shape *g, const void *X_, const void *dY_
     return 0;
 }
 
+/* Magnitude used for ranking the positions of a map.  Algorithm 1 says nothing
+ * about NaN; the rule of this build: a NaN ranks as magnitude zero, i.e. it ties
+ * with the zeros of the map and the lowest position among them wins. */
+static double rank_magnitude(double v)
+{
+    double a = fabs(v);
+    return a != a ? 0.0 : a;
+}
+
 /* Algorithm 1, the two per-map quantities: for the map dY[n,k,:,:]
  *   idx = flat position h*Wo + w of the largest |dY|; the scan runs over
  *         ascending flat position with a strict '>' so the lowest position wins
  *         ties; +v and -v have equal magnitude; an all-zero map gives 0; a NaN
- *         never compares greater, so it is never selected;
+ *         ranks as a zero (see rank_magnitude);
  *   S   = the signed sum of the whole map, a scalar. */
 static void select_map(const double *map, int len, int32_t *idx, double *S)
 {
     double best = -1.0, sum = 0.0;
     int32_t where = 0;
     for (int p = 0; p < len; ++p) {
-        double a = fabs(map[p]);
+        double a = rank_magnitude(map[p]);
         if (a > best) { best = a; where = p; }
         sum += map[p];
     }
@@ -235,7 +244,7 @@ static void select_map_topk(const double *map, int len, int k, int32_t *where, d
             int taken = 0;
             for (int i = 0; i < j; ++i) taken |= where[i] == p;
             if (taken) continue;
-            const double a = fabs(map[p]);
+            const double a = rank_magnitude(map[p]);
             if (a > best) { best = a; at = p; }
         }
         where[j] = at;

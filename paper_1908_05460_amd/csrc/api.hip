@@ -11,17 +11,23 @@ static int make_geometry(const wgrad_conv_desc *d, Geometry &g)
         return WGRAD_INVALID_ARG;
     if (d->stride_h <= 0 || d->stride_w <= 0 || d->pad_h < 0 || d->pad_w < 0) return WGRAD_INVALID_ARG;
     if (d->dtype != WGRAD_F32 && d->dtype != WGRAD_BF16) return WGRAD_INVALID_ARG;
-    if (d->H + 2 * (long)d->pad_h < d->R || d->W + 2 * (long)d->pad_w < d->S) return WGRAD_INVALID_ARG;  // empty output
+    // output extent in 64-bit before anything is narrowed: a huge padding must not wrap
+    const long ho = ((long)d->H + 2 * (long)d->pad_h - d->R) / d->stride_h + 1;
+    const long wo = ((long)d->W + 2 * (long)d->pad_w - d->S) / d->stride_w + 1;
+    if ((long)d->H + 2 * (long)d->pad_h < d->R || (long)d->W + 2 * (long)d->pad_w < d->S) return WGRAD_INVALID_ARG;  // empty output
+    // (row, col) of a map is packed in 32 bits; window arithmetic of the kernels is 32-bit
+    if (ho < 1 || wo < 1 || ho >= 32768 || wo >= 32768) return WGRAD_UNSUPPORTED;
+    if (d->pad_h >= 32768 || d->pad_w >= 32768 || d->stride_h >= 32768 || d->stride_w >= 32768 ||
+        d->R >= 32768 || d->S >= 32768) return WGRAD_UNSUPPORTED;
     g.N = d->N; g.C = d->C; g.H = d->H; g.W = d->W; g.K = d->K; g.R = d->R; g.S = d->S;
     g.sh = d->stride_h; g.sw = d->stride_w; g.ph = d->pad_h; g.pw = d->pad_w;
-    g.Ho = (d->H + 2 * d->pad_h - d->R) / d->stride_h + 1;
-    g.Wo = (d->W + 2 * d->pad_w - d->S) / d->stride_w + 1;
+    g.Ho = (int)ho;
+    g.Wo = (int)wo;
     g.bf16 = d->dtype == WGRAD_BF16;
     // index arithmetic inside the kernels is 32-bit per tensor dimension product below
     const long lim = 1l << 31;
     if ((long)g.N * g.K >= lim || (long)g.Ho * g.Wo >= lim || g.dw_elems() >= lim || (long)g.H * g.W >= lim)
         return WGRAD_UNSUPPORTED;
-    if (g.Ho >= 32768 || g.Wo >= 32768) return WGRAD_UNSUPPORTED;   // (row, col) of a map is packed in 32 bits
     return WGRAD_OK;
 }
 

@@ -25,7 +25,7 @@ static __device__ long long g_trace_fused[4 * 8192];
 //
 // The comparison is done on the magnitude bits as unsigned integers, which orders
 // finite floats (and infinities) exactly as |v| does; +0/-0 and +v/-v compare equal.
-// A NaN gets key 0 so it can never displace anything, as with a strict '>' on floats.
+// A NaN gets key 0: it ranks as a zero of the map (lowest position among equal keys wins).
 // Ties go to the lowest position: within a lane positions are visited in ascending
 // order with a strict '>', and across lanes the packed key (mag << 32 | ~pos) is
 // maximised, which prefers the larger magnitude and then the smaller position.
@@ -1340,7 +1340,8 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
                   int32_t *idx_out, float *sum_out, void *ws, hipStream_t st, CombineQueue *defer, FusedQueue *fq,
                   Bf16Queue *bq, GatherQueue *gq, SelectQueue *sq)
 {
-    if (!defer) gq = nullptr;       // a queued gather needs its reduction queued behind it
+    // a queued launch needs its reduction queued behind it: without a reduction queue nothing is queued
+    if (!defer) { gq = nullptr; fq = nullptr; bq = nullptr; sq = nullptr; }
     bool aligned = true;
     for (int i = 0; i < b.n; ++i)
         aligned = aligned && ((uintptr_t)b.X[i] % (g.bf16 ? 8 : 16)) == 0 && ((uintptr_t)b.dY[i] % (g.bf16 ? 8 : 16)) == 0;

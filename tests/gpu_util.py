@@ -41,6 +41,14 @@ def normwise_err(got, want):
     return float(np.abs(got.astype(np.float64) - want).max() / (scale if scale > 0 else 1.0))
 
 
+def elementwise_pass_rate(got, want, tol):
+    """Share of entries with |g - o| <= tol*|o| + tol*rms(o): information beside the normwise bound."""
+    want = np.asarray(want, np.float64)
+    diff = np.abs(np.asarray(got, np.float64).reshape(want.shape) - want)
+    rms = float(np.sqrt(np.mean(want * want)))
+    return float(np.mean(diff <= tol * np.abs(want) + tol * rms))
+
+
 def check_select(d, dY, idx_gpu, S_gpu):
     want_idx, want_S = oracle.select(oracle_shape(d), dY)
     assert np.array_equal(idx_gpu, want_idx), "selected positions differ from the oracle"

@@ -60,6 +60,26 @@ def test_invalid_arguments_are_rejected_before_any_launch(lib):
     assert lib.conv_wgrad_random(ctypes.byref(good), None, 1.0, 0, 0, None) == B.INVALID_ARG
 
 
+def test_sizes_that_would_wrap_32_bit_arithmetic_are_refused(lib):
+    """Output extents are computed in 64 bits: a huge padding on ONE axis must not wrap into a negative
+    map length (with both axes huge the product of two negatives happened to look positive)."""
+    for kw in (dict(pad=1 << 30, pad_w=1), dict(pad=1, pad_w=1 << 30), dict(pad=1 << 30, pad_w=1 << 30),
+               dict(pad=(1 << 30) - 1, pad_w=0), dict(pad=40000, pad_w=1), dict(pad=1, pad_w=1, stride=40000)):
+        d = B.desc(2, 3, 8, 8, 4, **kw)
+        for method in (B.EXACT, B.APPROX):
+            assert B.workspace_bytes(d, method) == 0, kw
+        assert lib.conv_wgrad_zero(ctypes.byref(d), FAKE, None) == B.UNSUPPORTED, kw
+        assert lib.conv_wgrad_approx(ctypes.byref(d), FAKE, FAKE, FAKE, 1.0, None, None, FAKE, 1 << 30, None) == B.UNSUPPORTED, kw
+        assert lib.conv_wgrad_select(ctypes.byref(d), FAKE, FAKE, FAKE, None) == B.UNSUPPORTED, kw
+        assert lib.conv_wgrad_approx_topk(ctypes.byref(d), FAKE, FAKE, FAKE, 2, 1.0, None, None, FAKE, 1 << 30, None) == B.UNSUPPORTED, kw
+        assert lib.conv_wgrad_exact(ctypes.byref(d), FAKE, FAKE, FAKE, FAKE, 1 << 30, None) == B.UNSUPPORTED, kw
+    # a map of 32767 rows is the largest a packed (row, col) holds; one more is refused
+    ok = B.desc(1, 1, 32767, 4, 1, R=1, S=1, pad=0)
+    assert lib.conv_wgrad_zero(ctypes.byref(ok), None, None) == B.INVALID_ARG        # geometry accepted, null dW
+    too = B.desc(1, 1, 32768, 4, 1, R=1, S=1, pad=0)
+    assert lib.conv_wgrad_zero(ctypes.byref(too), FAKE, None) == B.UNSUPPORTED
+
+
 def test_workspace_is_checked(lib):
     d = B.desc(128, 16, 32, 32, 16)
     for method, call in ((B.EXACT, lambda ws, n: lib.conv_wgrad_exact(ctypes.byref(d), FAKE, FAKE, FAKE, ws, n, None)),

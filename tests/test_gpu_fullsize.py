@@ -1,15 +1,35 @@
 """GPU parity at the full benchmark sizes, through the same entry points and launch
-configuration bench.py times.  The exact gradient is checked on sampled entries the oracle
-computes one by one (each is a full N*Ho*Wo reduction); the approximation, whose oracle is
-cheap, is checked on every entry, with the selected positions bit-exact."""
+configuration bench.py times.  Every entry of every dW tensor is compared with the oracle,
+for the exact gradient (Section 2.4's definition) and for the approximation (Algorithm 1),
+whose selected positions must be bit-exact."""
 import numpy as np
 import pytest
 
 import oracle
 from paper_1908_05460_amd import binding as B, inputs
-from tests.gpu_util import TOL, check_select, normwise_err, oracle_shape, to_gpu
+from tests.gpu_util import TOL, check_select, elementwise_pass_rate, normwise_err, oracle_shape, to_gpu
 
 pytestmark = pytest.mark.gpu
+
+_ORACLE_EXACT = {}      # (workload, layer index) -> the oracle's full exact dW; both tests below use batch 0
+
+
+def oracle_exact_full(workload, index, g, X, dY):
+    key = (workload, index)
+    if key not in _ORACLE_EXACT:
+        _ORACLE_EXACT[key] = oracle.wgrad_exact(g, X, dY)
+    return _ORACLE_EXACT[key]
+
+
+def assert_exact_everywhere(got, want, dtype, what):
+    """max |gpu - oracle| over ALL entries against tol * max |oracle|; the element-wise pass rate
+    of |g - o| <= tol*|o| + tol*rms(o) is printed as information (entries are cancelling sums)."""
+    got = np.asarray(got, np.float64).reshape(want.shape)
+    assert np.isfinite(got).all(), what
+    err = normwise_err(got, want)
+    print(f"{what}: normwise {err:.2e}, element-wise pass rate {elementwise_pass_rate(got, want, TOL[dtype]):.6f}"
+          f" over {want.size} entries")
+    assert err <= TOL[dtype], (what, err)
 
 
 def distinct_layers(workload):
@@ -38,15 +58,9 @@ def test_layer_at_benchmark_size(workload, index):
     Xg, dYg = to_gpu(X), to_gpu(dY)
     ws = B.alloc_workspace(max(B.workspace_bytes(d, B.EXACT), B.workspace_bytes(d, B.APPROX)))
 
-    # exact: sampled entries (corners included), error relative to the largest sampled |dW|
-    got = B.conv_wgrad_exact(d, Xg, dYg, ws=ws).cpu().numpy().ravel()
-    total = got.size
-    rng = np.random.default_rng(index)
-    pick = np.unique(np.concatenate([[0, total - 1, total // 2], rng.integers(0, total, 509)]))
-    want = oracle.wgrad_exact_at(g, X, dY, pick)
-    scale = np.abs(want).max()
-    assert np.abs(got[pick].astype(np.float64) - want).max() <= TOL[dtype] * scale
-    assert np.isfinite(got).all()
+    # exact: every entry
+    got = B.conv_wgrad_exact(d, Xg, dYg, ws=ws).cpu().numpy()
+    assert_exact_everywhere(got, oracle_exact_full(workload, index, g, X, dY), dtype, f"{workload} {layer.name} single call")
 
     # approximation: everything
     idx = torch.empty((N, layer.K), dtype=torch.int32, device="cuda")
@@ -58,7 +72,7 @@ def test_layer_at_benchmark_size(workload, index):
 
 
 @pytest.mark.parametrize("workload", ["resnet20_n128_fp32", "vgg19_n128_fp32", "vgg19_n512_bf16"])
-def test_whole_stack_through_schedule_run_matches_per_layer_oracle_samples(workload):
+def test_whole_stack_through_schedule_run_matches_the_oracle_everywhere(workload):
     """The launch path bench.py uses: one conv_wgrad_schedule_run per method over the stack; then a mask that
     mixes the methods (every other layer approximated), as the schedule sweep runs it."""
     import torch
@@ -75,21 +89,18 @@ def test_whole_stack_through_schedule_run_matches_per_layer_oracle_samples(workl
     mixed = exact.copy(); mixed[1::2] = sch.APPROX
     ws = B.alloc_workspace(max(s.workspace_bytes(m) for m in (exact, approx, mixed)))
     s.run(exact, ws)
-    ex = [t.cpu().numpy().ravel().copy() for t in dWs]
+    ex = [t.cpu().numpy().copy() for t in dWs]
     s.run(approx, ws, scale=1.0)
     ap = [t.cpu().numpy().copy() for t in dWs]
     s.run(mixed, ws, scale=1.0)
     mx = [t.cpu().numpy().copy() for t in dWs]
-    rng = np.random.default_rng(5)
     for i, l in enumerate(stack):
         g = oracle_shape(descs[i])
-        pick = rng.integers(0, ex[i].size, 24)
-        want = oracle.wgrad_exact_at(g, data[i][0], data[i][1], pick)
-        bound = TOL[dtype] * max(np.abs(want).max(), np.abs(ex[i]).max())
-        assert np.abs(ex[i][pick] - want).max() <= bound, l.name
+        want = oracle_exact_full(workload, i, g, data[i][0], data[i][1])
+        assert_exact_everywhere(ex[i], want, dtype, f"{workload} {l.name} all-exact run")
         want_a = oracle.wgrad_approx(g, data[i][0], data[i][1])[0]
         assert normwise_err(ap[i], want_a) <= TOL[dtype], l.name
         if mixed[i] == sch.APPROX:
             assert normwise_err(mx[i], want_a) <= TOL[dtype], l.name
         else:
-            assert np.abs(mx[i].ravel()[pick] - want).max() <= bound, l.name
+            assert_exact_everywhere(mx[i], want, dtype, f"{workload} {l.name} mixed run")

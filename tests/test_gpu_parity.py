@@ -205,6 +205,39 @@ def test_select_with_heavy_ties(hw, dtype):
     check_select(d, dY, idx.cpu().numpy(), S.cpu().numpy())
 
 
+@pytest.mark.parametrize("dtype", ["fp32", "bf16"])
+@pytest.mark.parametrize("hw", [(2, 2), (4, 4), (8, 8), (16, 16), (32, 32), (7, 9)])
+def test_select_ranks_nan_as_zero(hw, dtype):
+    """A NaN ranks as a zero of its map (lowest position among equal magnitudes wins): positions bit-exact
+    against the oracle through the selection call, the approximation call (fused / LDS / sparsified forms)
+    and the top-k call; sums of maps that hold a NaN are NaN on both sides and are not compared."""
+    import torch
+    Ho, Wo = hw
+    d = B.desc(8, 16, Ho, Wo, 16, R=3, S=3, pad=1, dtype=B.BF16 if dtype == "bf16" else B.F32)
+    rng = np.random.default_rng(Ho * 37 + Wo)
+    dY = (rng.integers(-2, 3, size=(d.N, d.K, Ho, Wo)) * 0.5).astype(np.float32)
+    L = Ho * Wo
+    dY[0, 0] = 0.0; dY[0, 0].flat[0] = np.nan                       # NaN at position 0, zeros elsewhere
+    dY[0, 1] = 0.0; dY[0, 1].flat[L - 1] = np.nan                   # zeros, then a NaN at the end
+    dY[0, 2] = np.nan                                               # only NaNs
+    dY[0, 3] = 0.0; dY[0, 3].flat[0] = np.nan; dY[0, 3].flat[L - 1] = 1e-20   # a tiny value beats the NaN
+    dY[1, 0].flat[rng.integers(0, L, 3)] = -np.nan                  # NaNs inside an ordinary map
+    X = np.maximum(rng.standard_normal((d.N, d.C, Ho, Wo)).astype(np.float32), 0)
+    if dtype == "bf16":
+        dY, X = inputs.float32_to_bf16_bits(dY), inputs.float32_to_bf16_bits(X)
+    want_idx, _ = oracle.select(oracle_shape(d), dY)
+    assert want_idx[0, :4].tolist() == [0, 0, 0, L - 1]
+    idx, _ = B.conv_wgrad_select(d, to_gpu(dY))
+    assert np.array_equal(idx.cpu().numpy(), want_idx)
+    idx2 = torch.empty((d.N, d.K), dtype=torch.int32, device="cuda")
+    B.conv_wgrad_approx(d, to_gpu(X), to_gpu(dY), idx_out=idx2)
+    assert np.array_equal(idx2.cpu().numpy(), want_idx)
+    k = min(3, L)
+    idx3 = torch.empty((d.N, d.K, k), dtype=torch.int32, device="cuda")
+    B.conv_wgrad_approx_topk(d, to_gpu(X), to_gpu(dY), k, idx_out=idx3)
+    assert np.array_equal(idx3.cpu().numpy(), oracle.select_topk(oracle_shape(d), dY, k)[0])
+
+
 def test_select_on_workload_gradients_fp32_and_bf16():
     for dtype in ("fp32", "bf16"):
         d = B.desc(32, 1, 32, 32, 64, R=1, S=1, pad=0, dtype=B.BF16 if dtype == "bf16" else B.F32)

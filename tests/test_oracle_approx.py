@@ -46,6 +46,28 @@ def test_select_tie_rules():
     np.testing.assert_allclose(S[0], [0.0, 1.5, 0.0, 1e-30, 0.0, 0.5], rtol=1e-6)
 
 
+def test_nan_ranks_as_a_zero_of_the_map():
+    """Algorithm 1 is silent on NaN; the build's rule is that a NaN ranks as magnitude zero, so it ties with the
+    zeros of its map (lowest position wins) and loses to every non-zero.  Pinned against numpy's first-maximum
+    argmax of the magnitudes with the NaNs replaced by zero."""
+    g = oracle.shape(1, 1, 2, 3, 5, R=1, S=1, stride=1, pad=0)
+    nan = np.float32(np.nan)
+    dY = np.zeros((1, 5, 2, 3), np.float32)
+    dY[0, 0].flat[:] = [nan, 0, 0, 0, 0, 0]          # NaN first, then zeros: position 0 (tie, lowest wins)
+    dY[0, 1].flat[:] = [0, nan, 0, 0, 0, 0]          # a zero before the NaN: position 0
+    dY[0, 2].flat[:] = [nan, nan, 1e-30, 0, 0, nan]  # any non-zero beats a NaN
+    dY[0, 3].flat[:] = [nan] * 6                     # only NaNs: position 0
+    dY[0, 4].flat[:] = [-nan, 0.5, nan, -0.5, 0, 0]  # sign of the NaN does not matter; +v before -v
+    idx, _ = oracle.select(g, dY)
+    assert idx[0].tolist() == [0, 0, 2, 0, 1]
+    mag = np.nan_to_num(np.abs(dY.astype(np.float64)), nan=0.0).reshape(1, 5, -1)
+    assert np.array_equal(idx, mag.argmax(axis=2))
+    # top-k ranks the same way and never repeats a position, also once only NaNs and zeros remain
+    idx3, _ = oracle.select_topk(g, dY, 3)
+    assert idx3[0].tolist() == [[0, 1, 2], [0, 1, 2], [2, 0, 1], [0, 1, 2], [1, 3, 0]]
+    assert np.array_equal(idx3, np.argsort(-mag, axis=2, kind="stable")[:, :, :3])
+
+
 def test_select_on_bf16_maps_with_many_ties():
     from paper_1908_05460_amd import inputs
     g = oracle.shape(8, 1, 16, 16, 8, stride=1, pad=1)
