@@ -51,7 +51,8 @@ typedef enum {
     WGRAD_INVALID_ARG = -1,         /* null pointer, non-positive size, empty output, bad dtype/method */
     WGRAD_UNSUPPORTED = -2,         /* sizes beyond the kernels' 32-bit index ranges; topk out of range */
     WGRAD_WORKSPACE_TOO_SMALL = -3, /* ws_bytes < conv_wgrad_workspace_bytes(), or ws misaligned      */
-    WGRAD_LAUNCH_FAILED = -4        /* the HIP runtime refused a launch                               */
+    WGRAD_LAUNCH_FAILED = -4,       /* the HIP runtime refused a launch                               */
+    WGRAD_SCRATCH_LIMIT = -5        /* conv_wgrad_approx_static: the layer needs more than the static buffer */
 } wgrad_status;
 
 /* Exact filter gradient (Section 2: the third convolution of a layer's
@@ -74,6 +75,23 @@ int conv_wgrad_exact(const wgrad_conv_desc *desc, const void *X, const void *dY,
 int conv_wgrad_approx(const wgrad_conv_desc *desc, const void *X, const void *dY, float *dW,
                       float scale, int32_t *idx_out, float *sum_out,
                       void *ws, size_t ws_bytes, void *stream);
+
+/* conv_wgrad_approx for callers that cannot allocate device memory or pass a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).
+ * Same arguments, same kernels and same results as conv_wgrad_approx, but the scratch
+ * memory is a buffer of WGRAD_STATIC_SCRATCH_BYTES inside the library's device image:
+ * each GPU the library runs on holds it from the first call there until the process
+ * ends.  The call allocates and frees nothing.  The stream's device must be the current
+ * device; the first call on a device looks the buffer's address up (a runtime query, so
+ * make that call outside a graph capture).
+ * A layer with conv_wgrad_workspace_bytes(desc, WGRAD_APPROX) above the limit is refused
+ * with WGRAD_SCRATCH_LIMIT and nothing is launched (24 MiB hold every layer of the CIFAR
+ * ResNet-20 and VGG-19 stacks up to batch 512).
+ * All calls on one GPU share that GPU's buffer: calls that may overlap in time (different
+ * streams, or different host threads) race on it and must be ordered by the caller. */
+#define WGRAD_STATIC_SCRATCH_BYTES (24u << 20)
+int conv_wgrad_approx_static(const wgrad_conv_desc *desc, const void *X, const void *dY, float *dW,
+                             float scale, int32_t *idx_out, float *sum_out, void *stream);
 
 /* The two selection quantities of Algorithm 1 alone (its argmax and sum lines):
  * idx[n*K + k] and sum[n*K + k] for every map of dY.  X is not read; only the

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libwgrad.so")
 
 EXACT, APPROX, ZERO, RANDOM = 0, 1, 2, 3
 F32, BF16 = 0, 1
-OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, LAUNCH_FAILED = 0, -1, -2, -3, -4
+OK, INVALID_ARG, UNSUPPORTED, WORKSPACE_TOO_SMALL, LAUNCH_FAILED, SCRATCH_LIMIT = 0, -1, -2, -3, -4, -5
 
 EXPORTS = ("conv_wgrad_exact", "conv_wgrad_approx", "conv_wgrad_select", "conv_wgrad_zero",
            "conv_wgrad_random", "conv_wgrad_workspace_bytes", "conv_wgrad_schedule_run",
@@ -22,7 +22,9 @@ EXPORTS = ("conv_wgrad_exact", "conv_wgrad_approx", "conv_wgrad_select", "conv_w
            "conv_wgrad_approx_topk", "conv_wgrad_topk_workspace_bytes",
            "conv_wgrad_approx_nhwc", "conv_wgrad_exact_nhwc", "conv_wgrad_nhwc_workspace_bytes",
            "conv_wgrad_transpose_x", "conv_wgrad_permute_dw",
-           "conv_wgrad_schedule_run_topk", "conv_wgrad_schedule_topk_workspace_bytes")
+           "conv_wgrad_schedule_run_topk", "conv_wgrad_schedule_topk_workspace_bytes",
+           "conv_wgrad_approx_static")
+STATIC_SCRATCH_BYTES = 24 << 20
 DW_OIHW, DW_OHWI, DW_HWIO = 0, 1, 2
 
 
@@ -77,6 +79,7 @@ def load():
     L.conv_wgrad_exact.argtypes = [P(ConvDesc), vp, vp, fp, vp, ctypes.c_size_t, vp]
     L.conv_wgrad_approx.argtypes = [P(ConvDesc), vp, vp, fp, ctypes.c_float, i32p, fp, vp,
                                     ctypes.c_size_t, vp]
+    L.conv_wgrad_approx_static.argtypes = [P(ConvDesc), vp, vp, fp, ctypes.c_float, i32p, fp, vp]
     L.conv_wgrad_approx_topk.argtypes = [P(ConvDesc), vp, vp, fp, ctypes.c_int, ctypes.c_float, i32p, fp, vp,
                                          ctypes.c_size_t, vp]
     L.conv_wgrad_topk_workspace_bytes.argtypes = [P(ConvDesc), ctypes.c_int]
@@ -203,6 +206,17 @@ def conv_wgrad_approx(d, X, dY, scale=1.0, dW=None, idx_out=None, sum_out=None, 
 
 def topk_workspace_bytes(d, k):
     return load().conv_wgrad_topk_workspace_bytes(ctypes.byref(d), int(k))
+
+
+def conv_wgrad_approx_static(d, X, dY, scale=1.0, dW=None, idx_out=None, sum_out=None):
+    """conv_wgrad_approx on the library's static scratch buffer: no workspace is passed or allocated."""
+    _check_inputs(d, X, dY)
+    dW = _new_dW(d, X) if dW is None else dW
+    rc = load().conv_wgrad_approx_static(ctypes.byref(d), _ptr(X), _ptr(dY), _ptr(dW), float(scale),
+                                         _ptr(idx_out), _ptr(sum_out), _stream())
+    if rc != OK:
+        raise WgradError(rc, "conv_wgrad_approx_static")
+    return dW
 
 
 def conv_wgrad_approx_topk(d, X, dY, k, scale=1.0, dW=None, idx_out=None, sum_out=None, ws=None):

@@ -1,5 +1,7 @@
 // C ABI of libwgrad (declared in include/wgrad.h): argument validation and dispatch.
 // Everything here runs on the host; validation precedes the first launch.
+#include <mutex>
+
 #include "exact_stream_kernel.hpp"
 
 using namespace wgrad;
@@ -447,6 +449,50 @@ extern "C" int wgrad_debug_plan(const wgrad_conv_desc *desc, int nprob, int *out
 }
 #endif
 
+// ---- the approximation for callers that cannot allocate ----
+// The scratch memory of conv_wgrad_approx_static lives in the library's own device image: every GPU the library
+// runs on holds its copy of this array, at its own address, until the process ends.  `scratch` is only a
+// host-side stand-in for the symbol; the memory is reached through the per-device address looked up below.
+static __device__ __align__(256) unsigned char scratch[WGRAD_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mutex;
+void *g_scratch_ptr[kMaxDevices];           // device address of `scratch` on device i, once looked up
+
+// The array's address on the current device (looked up on the first call per device), or nullptr.
+void *static_scratch_of_current_device()
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" int conv_wgrad_approx_static(const wgrad_conv_desc *desc, const void *X, const void *dY, float *dW,
+                                        float scale, int32_t *idx_out, float *sum_out, void *stream)
+{
+    Geometry g;
+    int rc = make_geometry(desc, g);
+    if (rc != WGRAD_OK) return rc;
+    if (!X || !dY || !dW) return WGRAD_INVALID_ARG;
+    const ApproxPlan pl = plan_approx(g);
+    if (pl.ws_bytes > (size_t)WGRAD_STATIC_SCRATCH_BYTES) return WGRAD_SCRATCH_LIMIT;
+    // nothing in the approximation's kernels reads scratch it has not written in the same call (positions, sums
+    // and every partial result are overwritten), so the array's old contents need no clearing
+    void *ws = pl.ws_bytes ? static_scratch_of_current_device() : nullptr;
+    if (pl.ws_bytes && !ws) return WGRAD_LAUNCH_FAILED;
+    Batch b{};
+    b.n = 1; b.X[0] = X; b.dY[0] = dY; b.dW[0] = dW;
+    return launch_approx(g, pl, b, scale, idx_out, sum_out, ws, (hipStream_t)stream);
+}
+
 extern "C" {
 
 const char *conv_wgrad_status_string(int status)
@@ -457,6 +503,7 @@ const char *conv_wgrad_status_string(int status)
         case WGRAD_UNSUPPORTED: return "unsupported: a size beyond the kernels' 32-bit index ranges, or top-k out of range";
         case WGRAD_WORKSPACE_TOO_SMALL: return "workspace too small or not 256-byte aligned";
         case WGRAD_LAUNCH_FAILED: return "the HIP runtime refused a kernel launch";
+        case WGRAD_SCRATCH_LIMIT: return "the layer needs more scratch memory than the library's static buffer (WGRAD_STATIC_SCRATCH_BYTES) holds";
         default: return "unknown status";
     }
 }

@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
-    assert set(names) == set(B.EXPORTS) and len(names) == 18
+    assert set(names) == set(B.EXPORTS) and len(names) == 19
     for n in names:
         assert getattr(lib, n) is not None
 
@@ -78,6 +78,23 @@ def test_sizes_that_would_wrap_32_bit_arithmetic_are_refused(lib):
     assert lib.conv_wgrad_zero(ctypes.byref(ok), None, None) == B.INVALID_ARG        # geometry accepted, null dW
     too = B.desc(1, 1, 32768, 4, 1, R=1, S=1, pad=0)
     assert lib.conv_wgrad_zero(ctypes.byref(too), FAKE, None) == B.UNSUPPORTED
+
+
+def test_static_scratch_call_validates_and_enforces_its_limit_on_the_host(lib):
+    """conv_wgrad_approx_static: arguments and the size limit are checked before the GPU is touched."""
+    f = lib.conv_wgrad_approx_static
+    good = B.desc(16, 16, 32, 32, 16)
+    assert B.workspace_bytes(good, B.APPROX) <= B.STATIC_SCRATCH_BYTES
+    assert f(None, FAKE, FAKE, FAKE, 1.0, None, None, None) == B.INVALID_ARG
+    assert f(ctypes.byref(good), None, FAKE, FAKE, 1.0, None, None, None) == B.INVALID_ARG
+    assert f(ctypes.byref(good), FAKE, None, FAKE, 1.0, None, None, None) == B.INVALID_ARG
+    assert f(ctypes.byref(good), FAKE, FAKE, None, 1.0, None, None, None) == B.INVALID_ARG
+    big = B.desc(2048, 512, 4, 4, 512)              # batch 2048 of a 512 -> 512 layer: partial sums beyond 24 MiB
+    assert B.workspace_bytes(big, B.APPROX) > B.STATIC_SCRATCH_BYTES
+    assert f(ctypes.byref(big), FAKE, FAKE, FAKE, 1.0, None, None, None) == B.SCRATCH_LIMIT
+    header = open(os.path.join(ROOT, "include", "wgrad.h")).read()
+    assert "#define WGRAD_STATIC_SCRATCH_BYTES (24u << 20)" in header and B.STATIC_SCRATCH_BYTES == 24 << 20
+    assert b"static buffer" in lib.conv_wgrad_status_string(B.SCRATCH_LIMIT)
 
 
 def test_workspace_is_checked(lib):
