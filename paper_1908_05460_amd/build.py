@@ -8,6 +8,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwgrad.so")
+ROOFS_LIB = os.path.join(HERE, "libwgrad_roofs.so")   # bench-only kernels that measure the machine's ceilings
 SOURCES = ["api.hip", "exact_mfma.hip", "exact_stream.hip", "exact_stream_w1.hip", "exact_stream_w2.hip",
            "exact_stream_w4.hip", "exact_multi.hip", "exact_bf16.hip", "exact_direct.hip", "approx.hip", "approx_topk.hip", "combine.hip",
            "fill.hip", "layouts.hip"]
@@ -47,6 +48,9 @@ def build(extra_flags=(), out=LIB, objdir=None, verbose=False):
     # host process has already loaded (a process must never run two HIP runtimes side by side,
     # and PyTorch wheels bundle theirs).  A plain C program links -lamdhip64 itself.
     subprocess.run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-no-hip-rt", "-o", out, *objs], check=True)
+    if out == LIB:
+        roofs = compile_one("roofs.hip")
+        subprocess.run([cc, "--offload-arch=gfx950", "-shared", "-fPIC", "-no-hip-rt", "-o", ROOFS_LIB, roofs], check=True)
     return out
 
 
