@@ -14,8 +14,10 @@ namespace wgrad {
 #ifdef WGRAD_TUNING
 static __device__ long long g_trace_fused[4 * 8192];
 #define FTRACE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace_fused[4 * blockIdx.x + (i)] = wall_clock64(); } while (0)
+#define FTRACE_G(gi) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace_fused[4 * blockIdx.x] = (wall_clock64() & ~7ll) | (gi); } while (0)
 #else
 #define FTRACE(i) do { } while (0)
+#define FTRACE_G(gi) do { } while (0)
 #endif
 
 // ------------------------------------------------------------------------------------
@@ -606,7 +608,20 @@ struct FusedParams {
     int tk;                      // top-k form only: kept positions per map, each weighted by sum * inv_k
     float inv_k;
     int nslice;                  // workgroups per output channel, each owning kFusedJ * 64 of its C*R*S entries
+    int rows3;                   // filter-row form (fp32, NCHW, S = 3): (channel, row) pairs per lane, 1..3; 0 = element form
+    FastDiv d_r;
 };
+
+// Whether the filter-row form takes the shape, and with how many pairs per lane: width-3 filters on fp32 NCHW
+// input whose patches overhang a row of X by at most one column on either side.
+static inline int fused_rows3(const Geometry &g)
+{
+    if (g.bf16 || g.S != 3 || g.W < 3 || g.pw > 1 || g.R > 63) return 0;
+    if ((long)(g.Wo - 1) * g.sw - g.pw + 3 - g.W > 1) return 0;
+    const long cr = (long)g.C * g.R;
+    const long per_slice = cr < kFusedJ * 64 / 3 ? cr : kFusedJ * 64 / 3;
+    return (int)((per_slice + 63) / 64);
+}
 
 // linear: the workgroup's number among the nk * nchunks * nprob of its group
 //
@@ -905,6 +920,269 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
     }
 }
 
+
+// ------------------------------------------------------------------------------------
+// fused form, filter rows as the unit (fp32, NCHW, filters of width 3, one kept position per map).
+// The three taps of a filter row are three consecutive input elements, i.e. ONE 12-byte load (global loads of
+// several dwords need only 4-byte alignment), so a lane owns (channel, filter row) pairs -- J3 of them, pair
+// q = lane + 64*jj of the slice -- instead of single entries: a third of the load instructions and address
+// arithmetic of the element form, and no lane loads for entries beyond C*R*S.
+// Columns: the 12 bytes are read at column cw = clamp(iwb, 0, W-3), always inside the row; a patch whose first
+// (last) column lies in the padding is the same three registers used one tap to the right (left).  Which of the
+// three cases applies is wavefront-uniform (it depends on the position alone).  Rows outside X: the lane reads
+// a valid address instead and its weight is zero.
+// The wavefront works in batches of B maps: scan B maps, request the next batch's maps, accumulate the B patches
+// requested one batch ago, request this batch's B patches -- every load has a whole batch of work to arrive
+// under, and B times as many bytes are in flight per wavefront as with one map at a time (the kernel was bound by
+// memory latency, one patch in flight per wavefront, not by bandwidth).
+// ------------------------------------------------------------------------------------
+struct __attribute__((packed, aligned(4))) Row3 { float v[3]; };
+constexpr int kPairsPerSlice = kFusedJ * 64 / 3;     // (channel, filter row) pairs of one slice of 576 entries
+
+template <int V, bool FULLMAP, bool ROWS, int J3>
+__device__ __forceinline__ void fused3_body(const ApproxBatch &ab, const Geometry &g, const FusedParams &fp,
+                                            float (&red)[4][kFusedJ * 64], int linear, int nk, int nchunks, int nprob)
+{
+#ifndef WGRAD_FUSED_BV4
+#define WGRAD_FUSED_BV4 1
+#endif
+    constexpr int B = V == 1 ? 4 : WGRAD_FUSED_BV4;        // maps per batch (ROWS: the four rows of one load)
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int logical = xcd_contiguous_id(linear, nk * nchunks * nprob);
+    const int kk = logical % nk;
+    const int k = kk / fp.nslice, slice = kk - k * fp.nslice;
+    const bool first_slice = slice == 0;
+    const int by = (logical / nk) % nchunks, bz = logical / (nk * nchunks);
+    const char *__restrict__ X = (const char *)ab.X[bz];
+    const char *__restrict__ dY = (const char *)ab.dY[bz];
+    float *__restrict__ out = ab.out[bz];
+    const int L = g.Ho * g.Wo, CR = g.C * g.R, CRS = CR * 3, HW = g.H * g.W;
+    const int n_begin = by * fp.chunk_n;
+    const int n_end = n_begin + fp.chunk_n < g.N ? n_begin + fp.chunk_n : g.N;
+
+    // slot jj: pair q = (c, r); xo = element offset of the pair's row from the patch origin, r in bits 24-29.
+    // A slot beyond C*R duplicates pair (0, 0): its loads are valid, its sums are never written.
+    int xo[J3];
+    float acc[J3][3];
+#pragma unroll
+    for (int jj = 0; jj < J3; ++jj) {
+        const int q = slice * kPairsPerSlice + lane + 64 * jj;
+        uint32_t c, r;
+        fp.d_r.divmod(q, c, r);
+        xo[jj] = q < CR ? (int)((c * HW + r * g.W) | r << 24) : 0;
+        acc[jj][0] = acc[jj][1] = acc[jj][2] = 0.f;
+    }
+
+    // pending batch: the patches requested one batch ago
+    float x_pend[B][J3][3];
+    float S_pend[B];
+    int ihb_pend[B], shift_pend[B];
+    bool whole_pend[B];
+#pragma unroll
+    for (int b = 0; b < B; ++b) {
+        S_pend[b] = 0.f; ihb_pend[b] = 0; shift_pend[b] = 0; whole_pend[b] = true;
+#pragma unroll
+        for (int jj = 0; jj < J3; ++jj) x_pend[b][jj][0] = x_pend[b][jj][1] = x_pend[b][jj][2] = 0.f;
+    }
+    auto accumulate_pending = [&]() {
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+#pragma unroll
+            for (int jj = 0; jj < J3; ++jj) {
+                float wl = S_pend[b], y0 = x_pend[b][jj][0], y1 = x_pend[b][jj][1], y2 = x_pend[b][jj][2];
+                if (!whole_pend[b]) {                       // wavefront-uniform: the patch reaches into the padding
+                    if ((uint32_t)(ihb_pend[b] + (int)((uint32_t)xo[jj] >> 24)) >= (uint32_t)g.H) wl = 0.f;
+                    if (shift_pend[b] > 0)      { y2 = y1; y1 = y0; y0 = 0.f; }   // first column in the padding
+                    else if (shift_pend[b] < 0) { y0 = y1; y1 = y2; y2 = 0.f; }   // last column in the padding
+                }
+                acc[jj][0] = fmaf(wl, y0, acc[jj][0]);
+                acc[jj][1] = fmaf(wl, y1, acc[jj][1]);
+                acc[jj][2] = fmaf(wl, y2, acc[jj][2]);
+            }
+        }
+    };
+    auto request_patch = [&](int b, int n, int pos, float S) {
+        uint32_t h, w;
+        fp.d_wo.divmod(pos, h, w);
+        const int ihb = (int)h * g.sh - g.ph, iwb = (int)w * g.sw - g.pw;
+        const int cw = iwb < 0 ? 0 : (iwb > g.W - 3 ? g.W - 3 : iwb);
+        const char *Ximg = X + (long)n * g.C * HW * 4;
+        const bool whole = ihb >= 0 && ihb + g.R <= g.H && cw == iwb;
+        const int origin = ihb * g.W + cw;                  // may be negative when rows lie above X; a valid row's is not
+        S_pend[b] = S; ihb_pend[b] = ihb; shift_pend[b] = cw - iwb; whole_pend[b] = whole;
+        if (whole) {
+#pragma unroll
+            for (int jj = 0; jj < J3; ++jj) {
+#ifdef WGRAD_PROBE_COALESCED
+                const Row3 t = *(const Row3 *)(Ximg + (lane + 64 * jj) * 12 + (origin & 0));
+#else
+                const Row3 t = *(const Row3 *)(Ximg + (uint32_t)(origin + (xo[jj] & 0xffffff)) * 4u);
+#endif
+                x_pend[b][jj][0] = t.v[0]; x_pend[b][jj][1] = t.v[1]; x_pend[b][jj][2] = t.v[2];
+            }
+        } else {
+#pragma unroll
+            for (int jj = 0; jj < J3; ++jj) {
+                const bool ok = (uint32_t)(ihb + (int)((uint32_t)xo[jj] >> 24)) < (uint32_t)g.H;
+                const uint32_t off = ok ? (uint32_t)(origin + (xo[jj] & 0xffffff)) * 4u : 0u;
+#ifdef WGRAD_PROBE_COALESCED
+                const Row3 t = *(const Row3 *)(Ximg + (lane + 64 * jj) * 12 + (off & 0));
+#else
+                const Row3 t = *(const Row3 *)(Ximg + off);
+#endif
+                x_pend[b][jj][0] = t.v[0]; x_pend[b][jj][1] = t.v[1]; x_pend[b][jj][2] = t.v[2];
+            }
+        }
+    };
+
+    // ---- maps: image n + 4*b of the batch starting at image n (this wavefront's images are n_begin + wave + 4*i) ----
+    float4 cur[ROWS ? 1 : B][V];
+    auto load_maps = [&](int n) {
+        if (ROWS) {                                         // row b of the wavefront: image n + 4b, 16 lanes x 16 bytes
+            const int nr = n + 4 * (lane >> 4), e = (lane & 15) * 4;
+            if (nr < n_end && e < L) cur[0][0] = *(const float4 *)(dY + (((long)nr * g.K + k) * L + e) * 4);
+            return;
+        }
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            if (n + 4 * b >= n_end) break;                  // wavefront-uniform
+            const char *base = dY + ((long)(n + 4 * b) * g.K + k) * L * 4;
+#pragma unroll
+            for (int v = 0; v < V; ++v) {
+                const int e = (lane + 64 * v) * 4;
+                if (FULLMAP || e < L) cur[b][v] = *(const float4 *)(base + (long)e * 4);
+            }
+        }
+    };
+    FTRACE(1);
+    if (n_begin + wave < n_end) load_maps(n_begin + wave);
+    // the first maps pass through opaque moves: the wait for them sits here, and the loop is entered with no load
+    // pending on these registers (otherwise the wait before every scan would also drain the pending patches)
+#pragma unroll
+    for (int b = 0; b < (ROWS ? 1 : B); ++b)
+#pragma unroll
+        for (int v = 0; v < V; ++v) {
+            uint32_t *wd = (uint32_t *)&cur[b][v];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) asm volatile("v_mov_b32 %0, %1" : "=v"(wd[i]) : "v"(wd[i]));
+        }
+    for (int n = n_begin + wave; n < n_end; n += 4 * B) {
+        int pos[B];
+        float S[B];
+        if (ROWS) {
+            const int e = (lane & 15) * 4;
+            const bool have = n + 4 * (lane >> 4) < n_end && e < L;
+            uint32_t best_key = 0, best_pos = e;
+            float sum = 0.f;
+            if (have) {
+                const uint4 r4 = *(const uint4 *)&cur[0][0];
+                const uint32_t bits[4] = {r4.x, r4.y, r4.z, r4.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const uint32_t key = mag_key<false>(bits[i]);
+                    if (key > best_key) { best_key = key; best_pos = e + i; }
+                    sum += __uint_as_float(bits[i]);
+                }
+            }
+            const uint32_t rmax = row_max_u32(best_key);
+            const float rsum = row_sum_f32(sum);
+            uint32_t kmax[4];
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                kmax[r] = (uint32_t)__builtin_amdgcn_readlane((int)rmax, 16 * r + 15);
+                S[r] = __uint_as_float((uint32_t)__builtin_amdgcn_readlane((int)__float_as_uint(rsum), 16 * r + 15));
+            }
+            // the lowest lane of a row that holds the row's maximum holds its lowest position
+            const uint32_t mine = lane < 32 ? (lane < 16 ? kmax[0] : kmax[1]) : (lane < 48 ? kmax[2] : kmax[3]);
+            const unsigned long long eq = __ballot(have && best_key == mine);
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const uint32_t sub = (uint32_t)(eq >> (16 * r)) & 0xffffu;       // zero only for a row without an image
+                pos[r] = __builtin_amdgcn_readlane((int)best_pos, 16 * r + (sub ? __builtin_ctz(sub) : 0));
+            }
+        } else {
+#pragma unroll
+            for (int b = 0; b < B; ++b) {
+                uint32_t best_key = 0, best_pos = 0;
+                bool have = false;
+                float sum = 0.f;
+#pragma unroll
+                for (int v = 0; v < V; ++v) {
+                    const int e = (lane + 64 * v) * 4;
+                    if (FULLMAP || e < L) {
+                        const uint4 r4 = *(const uint4 *)&cur[b][v];
+                        const uint32_t bits[4] = {r4.x, r4.y, r4.z, r4.w};
+#pragma unroll
+                        for (int i = 0; i < 4; ++i) {
+                            const uint32_t key = mag_key<false>(bits[i]);
+                            if (!have || key > best_key) { best_key = key; best_pos = e + i; have = true; }
+                            sum += __uint_as_float(bits[i]);
+                        }
+                    }
+                }
+                if (V == 1) {
+                    // one piece per lane: lanes hold ascending positions, so the lowest lane that holds the
+                    // maximum holds its lowest position
+                    const uint32_t key_max = wave_max_u32(have ? best_key : 0u);
+                    const unsigned long long eq = __ballot(have && best_key == key_max);
+                    pos[b] = __builtin_amdgcn_readlane((int)best_pos, eq ? (int)__builtin_ctzll(eq) : 0);
+                } else {
+                    uint32_t key_max, inv_pos_max;
+                    wave_max_pair(have ? best_key : 0u, have ? ~best_pos : 0u, key_max, inv_pos_max);
+                    pos[b] = (int)~inv_pos_max;
+                }
+                S[b] = wave_sum_f32(sum);
+            }
+        }
+        if (n + 4 * B < n_end) load_maps(n + 4 * B);
+        accumulate_pending();
+#pragma unroll
+        for (int b = 0; b < B; ++b) {
+            const int nb = n + 4 * b;
+            if (nb >= n_end) { S_pend[b] = 0.f; continue; }            // wavefront-uniform
+            if (lane == 0 && first_slice) {
+                if (fp.flat_out) fp.flat_out[(long)nb * g.K + k] = pos[b];
+                if (fp.sum_out) fp.sum_out[(long)nb * g.K + k] = S[b];
+            }
+            request_patch(b, nb, pos[b], S[b]);
+        }
+    }
+    accumulate_pending();
+    FTRACE(2);
+    // ---- add the four wavefronts' sums and write this chunk's row of the result ----
+#pragma unroll
+    for (int jj = 0; jj < J3; ++jj)
+#pragma unroll
+        for (int t = 0; t < 3; ++t) red[wave][(lane + 64 * jj) * 3 + t] = acc[jj][t];
+    __syncthreads();
+    const int j_base = slice * (kFusedJ * 64);
+    float *o = out + ((long)by * g.K + k) * CRS;
+    const int j_end = CRS - j_base < kFusedJ * 64 ? CRS - j_base : kFusedJ * 64;
+    for (int jl = tid; jl < j_end; jl += kBlock)
+        o[j_base + jl] = (red[0][jl] + red[1][jl] + red[2][jl] + red[3][jl]) * fp.scale;
+}
+
+template <int J3>
+__device__ __forceinline__ void fused3_by_map(const ApproxBatch &ab, const Geometry &g, const FusedParams &fp,
+                                              float (&red)[4][kFusedJ * 64], int linear, int nk, int nchunks, int nprob)
+{
+    const int L = g.Ho * g.Wo;
+    if (L <= 64)        fused3_body<1, false, true, J3>(ab, g, fp, red, linear, nk, nchunks, nprob);
+    else if (L == 1024) fused3_body<4, true, false, J3>(ab, g, fp, red, linear, nk, nchunks, nprob);
+    else if (L == 256)  fused3_body<1, true, false, J3>(ab, g, fp, red, linear, nk, nchunks, nprob);
+    else if (L < 256)   fused3_body<1, false, false, J3>(ab, g, fp, red, linear, nk, nchunks, nprob);
+    else                fused3_body<kFusedV, false, false, J3>(ab, g, fp, red, linear, nk, nchunks, nprob);
+}
+
+__device__ __forceinline__ void fused3_dispatch(const ApproxBatch &ab, const Geometry &g, const FusedParams &fp,
+                                                float (&red)[4][kFusedJ * 64], int linear, int nk, int nchunks, int nprob)
+{
+    if (fp.rows3 == 1)      fused3_by_map<1>(ab, g, fp, red, linear, nk, nchunks, nprob);
+    else if (fp.rows3 == 2) fused3_by_map<2>(ab, g, fp, red, linear, nk, nchunks, nprob);
+    else                    fused3_by_map<3>(ab, g, fp, red, linear, nk, nchunks, nprob);
+}
+
 // Picks the body for the map size: maps of exactly 1024 or 256 positions get the branch-free forms, maps of
 // up to 64 positions the four-maps-per-wavefront form.
 template <bool BF16, bool NHWC, bool TOPK>
@@ -924,6 +1202,7 @@ __global__ __launch_bounds__(kBlock) void approx_fused(ApproxBatch ab, Geometry 
 {
     __shared__ float red[4][kFusedJ * 64];
     const int linear = blockIdx.x + gridDim.x * (blockIdx.y + gridDim.y * blockIdx.z);
+    if (!BF16 && fp.rows3) { fused3_dispatch(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z); return; }
     fused_dispatch<BF16, false, false>(ab, g, fp, red, linear, gridDim.x, gridDim.y, gridDim.z);
 }
 
@@ -1020,9 +1299,10 @@ __global__ __launch_bounds__(kBlock) void approx_fused_multi(const FusedMulti)
     for (int i = 1; i < n; ++i) gi += (int)blockIdx.x >= mp->begin[i];
     const int linear = (int)blockIdx.x - mp->begin[gi];
     if (linear >= mp->count[gi]) return;
-    FTRACE(0);
+    FTRACE_G(gi);
     const FusedGroup &G = mp->grp[gi];
-    fused_dispatch<BF16, false, TOPK>(G.ab, G.g, G.fp, red, linear, G.g.K * G.fp.nslice, G.nchunks, G.nprob);
+    if (!BF16 && !TOPK && G.fp.rows3) fused3_dispatch(G.ab, G.g, G.fp, red, linear, G.g.K * G.fp.nslice, G.nchunks, G.nprob);
+    else fused_dispatch<BF16, false, TOPK>(G.ab, G.g, G.fp, red, linear, G.g.K * G.fp.nslice, G.nchunks, G.nprob);
     FTRACE(3);
 }
 
@@ -1043,16 +1323,17 @@ int fused_flush(FusedQueue &q, hipStream_t st)
     if (q.n == 0) return WGRAD_OK;
     FusedMulti m{};
     m.n = q.n;
-    int blocks = 0;
+    long blocks = 0;
     for (int i = 0; i < q.n; ++i) {
         m.grp[i] = q.grp[i];
-        m.begin[i] = blocks;
+        m.begin[i] = (int)blocks;
         m.count[i] = q.grp[i].g.K * q.grp[i].fp.nslice * q.grp[i].nchunks * q.grp[i].nprob;
         blocks += (m.count[i] + 7) / 8 * 8;
     }
-    m.begin[q.n] = blocks;
+    m.begin[q.n] = (int)blocks;
     const bool bf16 = q.bf16, topk = q.topk;
     q.n = 0;
+    if (blocks >= (1l << 31)) return WGRAD_UNSUPPORTED;
 #define FM_ARGS dim3((unsigned)blocks), dim3(kBlock), 0, st, m
     if (topk) { if (bf16) WGRAD_LAUNCH((approx_fused_multi<true, true>), FM_ARGS); else WGRAD_LAUNCH((approx_fused_multi<false, true>), FM_ARGS); }
     else      { if (bf16) WGRAD_LAUNCH((approx_fused_multi<true, false>), FM_ARGS); else WGRAD_LAUNCH((approx_fused_multi<false, false>), FM_ARGS); }
@@ -1279,6 +1560,7 @@ bool topk_fused(const Geometry &g, const Batch &b, int k, float scale,
     fp.chunk_n = pl.chunk_n; fp.scale = pl.chunks > 1 ? 1.0f : scale;
     fp.d_rs = FastDiv(g.R * g.S); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
     fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = k; fp.inv_k = 1.0f / k; fp.nslice = fused_slices(g);
+    fp.rows3 = 0; fp.d_r = FastDiv(g.R);
     if (fq) {
         if (fq->n == kFusedMultiMax || (fq->n > 0 && (fq->bf16 != g.bf16 || !fq->topk))) {
             *rc = fused_flush(*fq, st);
@@ -1443,6 +1725,7 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         fp.chunk_n = pl.chunk_n; fp.scale = kscale;
         fp.d_rs = FastDiv(g.R * g.S); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
         fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = 1; fp.inv_k = 1.0f; fp.nslice = fused_slices(g);
+        fp.rows3 = tune_int("WGRAD_FUSED_ROWS3", 1) ? fused_rows3(g) : 0; fp.d_r = FastDiv(g.R);
         if (fq) {
             // part of a multi-group launch (groups of one element type)
             if (fq->n == kFusedMultiMax || (fq->n > 0 && (fq->bf16 != g.bf16 || fq->topk))) {
@@ -1533,6 +1816,7 @@ int launch_approx_nhwc(const Geometry &g, const void *X, const void *dY, float *
         fp.chunk_n = pl.chunk_n; fp.scale = kscale;
         fp.d_rs = FastDiv(g.C); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
         fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = dw_layout; fp.tk = 1; fp.inv_k = 1.0f; fp.nslice = fused_slices(g);
+        fp.rows3 = 0; fp.d_r = FastDiv(g.R);
         const dim3 grid(g.K * fp.nslice, pl.chunks, 1);
         if (g.bf16) WGRAD_LAUNCH((approx_fused_nhwc<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
         else        WGRAD_LAUNCH((approx_fused_nhwc<false>), grid, dim3(kBlock), 0, st, ab, g, fp);
