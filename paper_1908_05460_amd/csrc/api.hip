@@ -435,20 +435,6 @@ extern "C" int conv_wgrad_schedule_run_topk(const wgrad_conv_desc *layers, const
     return schedule_run_impl(layers, X, dY, dW, method, nlayers, topk, scale, sigma, seed, offset, ws, ws_bytes, stream);
 }
 
-#ifdef WGRAD_TUNING
-// development builds: the exact plan of a descriptor for a launch of nprob problems
-extern "C" int wgrad_debug_plan(const wgrad_conv_desc *desc, int nprob, int *out)
-{
-    Geometry g;
-    if (make_geometry(desc, g) != WGRAD_OK) return -1;
-    const ExactPlan pl = plan_exact(g);
-    out[0] = pl.stream; out[1] = pl.nt; out[2] = pl.wk; out[3] = pl.gpw; out[4] = (int)pl.lds_bytes;
-    out[5] = pl.ktiles * pl.ctiles; out[6] = pl.h_tiles * pl.n_groups; out[7] = pl.splits;
-    out[8] = nprob > 1 ? choose_splits(pl, nprob) : pl.splits; out[9] = pl.rowp; out[10] = pl.q; out[11] = pl.nti; out[12] = pl.ht;
-    return 0;
-}
-#endif
-
 // ---- the approximation for callers that cannot allocate ----
 // The scratch memory of conv_wgrad_approx_static lives in the library's own device image: every GPU the library
 // runs on holds its copy of this array, at its own address, until the process ends.  `scratch` is only a

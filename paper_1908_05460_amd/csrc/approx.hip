@@ -7,18 +7,10 @@
 //   combine:  sums the batch-chunk partials of the gather (shared with the exact path).
 #include <algorithm>
 
+#define WGRAD_TRACE_FUSED_HERE
 #include "common.hpp"
 
 namespace wgrad {
-
-#ifdef WGRAD_TUNING
-static __device__ long long g_trace_fused[4 * 8192];
-#define FTRACE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace_fused[4 * blockIdx.x + (i)] = wall_clock64(); } while (0)
-#define FTRACE_G(gi) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace_fused[4 * blockIdx.x] = (wall_clock64() & ~7ll) | (gi); } while (0)
-#else
-#define FTRACE(i) do { } while (0)
-#define FTRACE_G(gi) do { } while (0)
-#endif
 
 // ------------------------------------------------------------------------------------
 // select: a group of G lanes (power of two, <= 64) owns one map; each lane walks the
@@ -943,10 +935,7 @@ template <int V, bool FULLMAP, bool ROWS, int J3>
 __device__ __forceinline__ void fused3_body(const ApproxBatch &ab, const Geometry &g, const FusedParams &fp,
                                             float (&red)[4][kFusedJ * 64], int linear, int nk, int nchunks, int nprob)
 {
-#ifndef WGRAD_FUSED_BV4
-#define WGRAD_FUSED_BV4 1
-#endif
-    constexpr int B = V == 1 ? 4 : WGRAD_FUSED_BV4;        // maps per batch (ROWS: the four rows of one load)
+    constexpr int B = V == 1 ? 4 : 1;                      // maps per batch (ROWS: the four rows of one load)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int logical = xcd_contiguous_id(linear, nk * nchunks * nprob);
@@ -1014,11 +1003,7 @@ __device__ __forceinline__ void fused3_body(const ApproxBatch &ab, const Geometr
         if (whole) {
 #pragma unroll
             for (int jj = 0; jj < J3; ++jj) {
-#ifdef WGRAD_PROBE_COALESCED
-                const Row3 t = *(const Row3 *)(Ximg + (lane + 64 * jj) * 12 + (origin & 0));
-#else
                 const Row3 t = *(const Row3 *)(Ximg + (uint32_t)(origin + (xo[jj] & 0xffffff)) * 4u);
-#endif
                 x_pend[b][jj][0] = t.v[0]; x_pend[b][jj][1] = t.v[1]; x_pend[b][jj][2] = t.v[2];
             }
         } else {
@@ -1026,11 +1011,7 @@ __device__ __forceinline__ void fused3_body(const ApproxBatch &ab, const Geometr
             for (int jj = 0; jj < J3; ++jj) {
                 const bool ok = (uint32_t)(ihb + (int)((uint32_t)xo[jj] >> 24)) < (uint32_t)g.H;
                 const uint32_t off = ok ? (uint32_t)(origin + (xo[jj] & 0xffffff)) * 4u : 0u;
-#ifdef WGRAD_PROBE_COALESCED
-                const Row3 t = *(const Row3 *)(Ximg + (lane + 64 * jj) * 12 + (off & 0));
-#else
                 const Row3 t = *(const Row3 *)(Ximg + off);
-#endif
                 x_pend[b][jj][0] = t.v[0]; x_pend[b][jj][1] = t.v[1]; x_pend[b][jj][2] = t.v[2];
             }
         }
@@ -1306,12 +1287,7 @@ __global__ __launch_bounds__(kBlock) void approx_fused_multi(const FusedMulti)
     FTRACE(3);
 }
 
-#ifdef WGRAD_TUNING
-extern "C" int wgrad_debug_read_trace_fused(long long *host_out)
-{
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace_fused), sizeof(long long) * 4 * 8192);
-}
-#endif
+WGRAD_FUSED_TRACE_READER(wgrad_debug_read_trace_fused)
 
 struct FusedQueue {
     int n = 0, bf16 = 0, topk = 0;   // groups of one element type and one form (k = 1 or top-k) per launch

@@ -7,6 +7,9 @@
 #include <vector>
 
 #include "wgrad.h"
+#ifdef WGRAD_TUNING
+#include "dev_tuning.hpp"
+#endif
 
 namespace wgrad {
 
@@ -47,17 +50,18 @@ struct Geometry {                    // validated convolution geometry
     __host__ __device__ long dw_elems() const { return (long)K * C * R * S; }
 };
 
-// Tuning knob: a compile-time default; builds with -DWGRAD_TUNING (development sweeps only,
-// never the product build) let an environment variable of the same name override it.
-inline int tune_int(const char *name, int dflt)
-{
-#ifdef WGRAD_TUNING
-    if (const char *v = getenv(name)) return atoi(v);
-#else
-    (void)name;
+// Tuning constants are written tune_int("NAME", value): in this build that is the value.  (Development builds
+// define WGRAD_TUNING and take the definitions below from dev_tuning.hpp instead, which lets an environment
+// variable override a constant and adds timestamp traces.)
+#ifndef WGRAD_TUNING
+constexpr int tune_int(const char *, int dflt) { return dflt; }
+#define TRACE(i) do { } while (0)
+#define TRACE_BLK(which) do { } while (0)
+#define FTRACE(i) do { } while (0)
+#define FTRACE_G(gi) do { } while (0)
+#define WGRAD_TRACE_READER(name)
+#define WGRAD_FUSED_TRACE_READER(name)
 #endif
-    return dflt;
-}
 
 inline size_t align_up(size_t v, size_t a = kAlign) { return (v + a - 1) / a * a; }
 

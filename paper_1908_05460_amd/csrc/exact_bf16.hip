@@ -229,11 +229,7 @@ int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, fl
     return WGRAD_OK;
 }
 
-#if defined(WGRAD_TUNING) && !defined(WGRAD_NO_TRACE)
-extern "C" int wgrad_debug_read_trace_bf16(long long *host_out)
-{
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace), sizeof(long long) * (64 + 2 * 4096));
-}
-#endif
 
 }  // namespace wgrad
+
+WGRAD_TRACE_READER(wgrad_debug_read_trace_bf16)

@@ -321,9 +321,7 @@ __device__ __forceinline__ void bf16_body(const Bf16Params &p, float *smem, int 
         // under them; ahead of the matrix instructions it was a phase of its own in which the wavefront
         // issued none.
         auto stage_next = [&]() {
-#ifndef WGRAD_BF16_NOCOMMIT      // timing experiments only: results are then wrong
             commit_x(Xs0 + (par ^ 1) * p.buf_words);
-#endif
             if (wt == wt_begin + 2) TRACE(5);
             load_x(wt + 2);
             if (wt == wt_begin + 2) TRACE(6);
@@ -394,11 +392,7 @@ __device__ __forceinline__ void bf16_body(const Bf16Params &p, float *smem, int 
                 // the registers are free again: same piece of the next tile
 #pragma unroll
                 for (int m = 0; m < MT; ++m)
-#ifndef WGRAD_BF16_NOALOAD       // timing experiments only
                     ring[gi][m] = load_a(dyb + m * row_tile_bytes, a_next[gi]);
-#else
-                    ;
-#endif
             }
             if (wt == wt_begin + 2 && gi == 0) TRACE(11);
             if (gi == 0) stage_next();

@@ -6,18 +6,6 @@ namespace wgrad {
 
 typedef float float4_t __attribute__((ext_vector_type(4)));
 
-// Development builds (-DWGRAD_TUNING) can record phase timestamps of one workgroup; a file that
-// wants them defines WGRAD_TRACE_HERE before including this header.
-#if defined(WGRAD_TUNING) && defined(WGRAD_TRACE_HERE) && !defined(WGRAD_NO_TRACE)
-static __device__ long long g_trace[64 + 2 * 4096];
-#define TRACE_BLOCK 37
-#define TRACE_BLK(which) do { if (threadIdx.x == 0 && blockIdx.x < 4096) g_trace[64 + 2 * blockIdx.x + which] = wall_clock64(); } while (0)
-#define TRACE(i) do { if (blockIdx.x == TRACE_BLOCK && threadIdx.x == 0) { g_trace[i] = wall_clock64(); g_trace[32 + i] = clock64(); } } while (0)
-#else
-#define TRACE(i) do { } while (0)
-#define TRACE_BLK(which) do { } while (0)
-#endif
-
 template <bool BF16>
 __device__ __forceinline__ float load_elem(const void *p, long i)
 {

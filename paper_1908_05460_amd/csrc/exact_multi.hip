@@ -83,11 +83,7 @@ int multi_flush(MultiQueue &q, hipStream_t st)
     return launch_status();
 }
 
-#if defined(WGRAD_TUNING) && !defined(WGRAD_NO_TRACE)
-extern "C" int wgrad_debug_read_trace_multi(long long *host_out)
-{
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace), sizeof(long long) * (64 + 2 * 4096));
-}
-#endif
 
 }  // namespace wgrad
+
+WGRAD_TRACE_READER(wgrad_debug_read_trace_multi)

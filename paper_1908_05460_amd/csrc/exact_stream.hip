@@ -91,9 +91,6 @@ int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, 
     p.seg = pl.ht * g.Wo;
     p.xbuf = pl.xbuf;
     p.rowp = pl.rowp;
-#ifdef WGRAD_TUNING
-    p.repeat = tune_int("WGRAD_REPEAT", 1);
-#endif
     p.d_wv = FastDiv(g.W / pl.xv);
     p.d_rows = FastDiv(pl.nti * pl.iht);
     p.d_iht = FastDiv(pl.iht);

@@ -29,10 +29,6 @@ namespace wgrad {
 #ifndef WGRAD_STREAM_SCHED
 #define WGRAD_STREAM_SCHED 2
 #endif
-// WGRAD_STREAM_PRIO: wavefront priority while a tile's window is staged (the MFMA pipeline runs at 0)
-#ifndef WGRAD_STREAM_PRIO
-#define WGRAD_STREAM_PRIO 0
-#endif
 #if WGRAD_STREAM_SCHED == 1
 #define WGRAD_SCHED_FENCE() __builtin_amdgcn_sched_barrier(0)
 #else
@@ -64,9 +60,6 @@ struct StreamParams {
     int rowp;                   // LDS pitch of a window row (>= iwt)
     FastDiv d_wv, d_rows, d_iht, d_rs, d_s, d_seg, d_wo, d_htiles;
     int tile_c0[9], tile_toff[9], tile_tap[9];
-#ifdef WGRAD_TUNING
-    int repeat;                 // development builds: contract every tile this many times (timing experiments only)
-#endif
 };
 
 // Window staging slots (16- or 8-byte row pieces) per thread and tile.
@@ -313,7 +306,6 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
         if (wt == wt_begin) TRACE(3);
         if (wt == wt_begin + 1) TRACE(5);
         const char *Xw = (const char *)(Xs0 + par * p.xbuf);
-        if (WGRAD_STREAM_PRIO) __builtin_amdgcn_s_setprio(WGRAD_STREAM_PRIO);
         // window of the next tile: registers -> the other buffer, then request the one after it
         commit_x(Xs0 + (par ^ 1) * p.xbuf);
         if (wt == wt_begin + 1) TRACE(6);
@@ -323,11 +315,7 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
         int ih0;
         tile_origin(wt + 1, has_next, dyb, xb, ih0);
         if (wt == wt_begin + 1) TRACE(7);
-        if (WGRAD_STREAM_PRIO) __builtin_amdgcn_s_setprio(0);
 
-#ifdef WGRAD_TUNING
-        for (int rep = 0; rep < p.repeat; ++rep)
-#endif
         {
             // The 4 * GPW steps of the tile form one software pipeline: the LDS reads of step t+1
             // (and the position offsets of the next group) are issued before the MFMAs of step t,

@@ -10,11 +10,7 @@ void stream_launch_w1(const StreamParams &p, int nt, int xv, int gpw, int rowp, 
     else stream_pick<1, false>(p, nt, xv, gpw, rowp, grid, lds, st);
 }
 
-#if defined(WGRAD_TUNING) && !defined(WGRAD_NO_TRACE)
-extern "C" int wgrad_debug_read_trace(long long *host_out)
-{
-    return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(g_trace), sizeof(long long) * (64 + 2 * 4096));
-}
-#endif
 
 }  // namespace wgrad
+
+WGRAD_TRACE_READER(wgrad_debug_read_trace)
