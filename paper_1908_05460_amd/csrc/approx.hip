@@ -347,7 +347,7 @@ __global__ __launch_bounds__(kBlock) void approx_gather_direct(ApproxBatch ab, G
 // ------------------------------------------------------------------------------------
 constexpr int kGatherCT = 64;
 constexpr int kGatherBlock = 512;   // 8 wavefronts: two per SIMD, so one hides the LDS and scalar latencies of the other
-constexpr int kGatherSlots = 8;      // 16-byte loads per thread and group
+constexpr int kGatherSlots = 4;      // 16-byte loads per thread and group (registers that stay live under the patch loop)
 constexpr size_t kGatherLds = 64 * 1024;
 
 template <bool BF16> struct Raw4 { typedef float4 type; };
@@ -453,6 +453,8 @@ __device__ __forceinline__ void gather_lds_body(const ApproxBatch &ab, const Geo
             }
     };
 
+    FTRACE(0);
+    long long t_stage = 0, t_loop = 0, t_mark = FTRACE_CLOCK();
     prefetch(n_begin);
     int parity = 0;
     for (int n0 = n_begin; n0 < n_end; n0 += nb, parity ^= 1) {
@@ -499,15 +501,50 @@ __device__ __forceinline__ void gather_lds_body(const ApproxBatch &ab, const Geo
         asm volatile("v_mov_b32 %0, %1" : "=v"(sv_cur) : "v"(sv_next));
         __syncthreads();
         if (n0 + nb < n_end) prefetch(n0 + nb);
+        { const long long now = FTRACE_CLOCK(); t_stage += now - t_mark; t_mark = now; }
 
-        if (lane < cvalid) {
+        if (lane < cvalid && !TOPK) {
+            // One patch per (image, output channel) pair t = n_l * M + j of the group, nine LDS reads and nine
+            // multiply-adds each.  The reads of pair t + 1 are issued before the multiply-adds of pair t (two
+            // register sets, alternating), so a wavefront always has a patch in flight behind the one it is adding.
+            const float *plane = buf + lane * pitch;
+            const int T = nb_cur * M;
+            float v[2][9];
+            // (no branches inside the loop: a pair index beyond the group re-reads the last pair and adds it
+            // with weight zero)
+            auto issue = [&](int t, float (&dst)[9]) {
+                t = t < T ? t : T - 1;
+                const int p = __builtin_amdgcn_readlane(hw_cur, t);
+                const float *win = plane + (t / M) * (kGatherCT * pitch) + (p >> 16) * g.sh * WP + (p & 0xffff) * g.sw;
+#pragma unroll
+                for (int r = 0; r < 3; ++r)
+#pragma unroll
+                    for (int s3 = 0; s3 < 3; ++s3) dst[r * 3 + s3] = win[r * WP + s3];
+            };
+            auto add = [&](int t, int j, const float (&src)[9]) {
+                float sv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sv_cur), t < T ? t : T - 1));
+                sv = t < T ? sv : 0.f;
+#pragma unroll
+                for (int e = 0; e < 9; ++e) acc[j][e] = fmaf(sv, src[e], acc[j][e]);
+            };
+            constexpr int U = M == 1 ? 2 : M;           // pairs per trip: the output channel t % M and the register set
+            issue(0, v[0]);                             // t & 1 of a pair are compile-time constants
+            for (int t0 = 0; t0 < T; t0 += U) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    issue(t0 + u + 1, v[(u + 1) & 1]);
+                    add(t0 + u, u % M, v[u & 1]);
+                }
+            }
+        }
+        { const long long now = FTRACE_CLOCK(); t_loop += now - t_mark; t_mark = now; }
+        if (lane < cvalid && TOPK) {
             const float *plane = buf + lane * pitch;
             for (int n_l = 0; n_l < nb_cur; ++n_l, plane += kGatherCT * pitch) {
 #pragma unroll
                 for (int j = 0; j < M; ++j) {
-                    const int tk = TOPK ? gp.tk : 1;
-                    for (int t = 0; t < tk; ++t) {
-                        const int slot = TOPK ? (n_l * M + j) * tk + t : n_l * M + j;
+                    for (int t = 0; t < gp.tk; ++t) {
+                        const int slot = (n_l * M + j) * gp.tk + t;
                         const int p = __builtin_amdgcn_readlane(hw_cur, slot);
                         const float sv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sv_cur), slot));
                         const float *win = plane + (p >> 16) * g.sh * WP + (p & 0xffff) * g.sw;   // window origin
@@ -522,6 +559,7 @@ __device__ __forceinline__ void gather_lds_body(const ApproxBatch &ab, const Geo
             }
         }
     }
+    FTRACE_SET(1, t_stage); FTRACE_SET(2, t_loop);
     if (lane < cvalid) {
         float *o = out + (long)by * g.K * g.C * 9;
 #pragma unroll
@@ -532,10 +570,11 @@ __device__ __forceinline__ void gather_lds_body(const ApproxBatch &ab, const Geo
             for (int t = 0; t < 9; ++t) o[((long)k * g.C + c0 + lane) * 9 + t] = acc[j][t] * gp.scale;
         }
     }
+    FTRACE(3);
 }
 
 template <bool BF16, int M, bool TOPK = false>
-__global__ __launch_bounds__(kGatherBlock) void approx_gather_lds3x3(ApproxBatch ab, Geometry g, GatherParams gp)
+__global__ __launch_bounds__(kGatherBlock, 4) void approx_gather_lds3x3(ApproxBatch ab, Geometry g, GatherParams gp)
 {
     extern __shared__ float xs[];                         // [2][nb][64][pitch]
     gather_lds_body<BF16, M, TOPK>(ab, g, gp, xs, blockIdx.x, blockIdx.y, blockIdx.z);
@@ -558,7 +597,7 @@ struct GatherMulti {
 };
 
 template <bool BF16, int M>
-__global__ __launch_bounds__(kGatherBlock) void approx_gather_lds_multi(const GatherMulti)
+__global__ __launch_bounds__(kGatherBlock, 4) void approx_gather_lds_multi(const GatherMulti)
 {
     extern __shared__ float xs[];
     const GatherMulti *mp = (const GatherMulti *)__builtin_amdgcn_kernarg_segment_ptr();

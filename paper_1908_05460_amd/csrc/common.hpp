@@ -59,6 +59,8 @@ constexpr int tune_int(const char *, int dflt) { return dflt; }
 #define TRACE_BLK(which) do { } while (0)
 #define FTRACE(i) do { } while (0)
 #define FTRACE_G(gi) do { } while (0)
+#define FTRACE_SET(i, v) do { } while (0)
+#define FTRACE_CLOCK() 0ll
 #define WGRAD_TRACE_READER(name)
 #define WGRAD_FUSED_TRACE_READER(name)
 #endif

@@ -34,11 +34,15 @@ static __device__ long long g_trace[64 + 2 * 4096];
 static __device__ long long g_trace_fused[4 * 8192];
 #define FTRACE(i) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace_fused[4 * blockIdx.x + (i)] = wall_clock64(); } while (0)
 #define FTRACE_G(gi) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace_fused[4 * blockIdx.x] = (wall_clock64() & ~7ll) | (gi); } while (0)
+#define FTRACE_SET(i, v) do { if (threadIdx.x == 0 && blockIdx.x < 8192) g_trace_fused[4 * blockIdx.x + (i)] = (v); } while (0)
+#define FTRACE_CLOCK() wall_clock64()
 #define WGRAD_FUSED_TRACE_READER(name) \
     extern "C" int name(long long *host_out) { return (int)hipMemcpyFromSymbol(host_out, HIP_SYMBOL(::wgrad::g_trace_fused), sizeof(long long) * 4 * 8192); }
 #else
 #define FTRACE(i) do { } while (0)
 #define FTRACE_G(gi) do { } while (0)
+#define FTRACE_SET(i, v) do { } while (0)
+#define FTRACE_CLOCK() 0ll
 #define WGRAD_FUSED_TRACE_READER(name)
 #endif
 
