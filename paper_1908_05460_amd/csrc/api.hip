@@ -315,7 +315,7 @@ static int schedule_run_impl(const wgrad_conv_desc *layers, const void *const *X
                 double w = 2.0 * gj.N * gj.K * gj.Ho * gj.Wo * (double)gj.crs();
                 // layers that are not bound by the matrix core take longer than their FLOPs say: a handful of
                 // input channels (bound by the dY stream), strides (a window four times the tile)
-                if (gj.C < 16) w *= tune_int("WGRAD_MULTI_W_FLAT", 2);
+                if (gj.C < 16) w *= tune_int("WGRAD_MULTI_W_FLAT", 20) / 10.0;
                 if (gj.sh > 1 || gj.sw > 1) w *= tune_int("WGRAD_MULTI_W_STRIDE", 25) / 10.0;
                 f += w;
             }
@@ -323,7 +323,11 @@ static int schedule_run_impl(const wgrad_conv_desc *layers, const void *const *X
     };
     if (mq)
         for (int i = 0; i < nlayers; ++i)
-            if (method[i] == WGRAD_EXACT && group[i] == i) exact_flops += group_flops(i);
+            if (method[i] == WGRAD_EXACT && group[i] == i) {
+                Geometry gi;
+                make_geometry(&layers[i], gi);
+                if (!plan_exact(gi).plane2) exact_flops += group_flops(i);   // (those groups have a launch of their own)
+            }
     int napprox = 0;
     for (int i = 0; i < nlayers; ++i) napprox += topk == 0 && method[i] == WGRAD_APPROX && group[i] == i;
     int ntopk = 0;

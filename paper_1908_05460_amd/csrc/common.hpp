@@ -59,7 +59,7 @@ constexpr int tune_int(const char *, int dflt) { return dflt; }
 #define TRACE_BLK(which) do { } while (0)
 #define FTRACE(i) do { } while (0)
 #define FTRACE_G(gi) do { } while (0)
-#define FTRACE_SET(i, v) do { } while (0)
+#define FTRACE_SET(i, v) do { (void)(v); } while (0)
 #define FTRACE_CLOCK() 0ll
 #define WGRAD_TRACE_READER(name)
 #define WGRAD_FUSED_TRACE_READER(name)
@@ -90,6 +90,7 @@ struct ExactPlan {
     int stream, gpw, xbuf, rowp;           // streaming form: A operand from global memory, window double-buffered
     int mm16;                        // bf16 matrix-core form of the streaming kernel
     int direct;                      // general form: no tile of whole output rows fits the LDS
+    int plane2;                      // 2x2 planes, fp32: the plain matrix product over (position, element) pairs
     size_t lds_bytes, ws_bytes;
     bool ok;
 };
@@ -99,6 +100,9 @@ struct MultiQueue;
 int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st,
                         MultiQueue *mq = nullptr);
 bool plan_exact_bf16(const Geometry &g, ExactPlan &pl);
+bool plane2_takes(const Geometry &g);
+struct MultiQueue;
+int launch_exact_plane2(const Geometry &g, const Batch &b, hipStream_t st, MultiQueue *mq = nullptr);
 struct CombineQueue;
 void plan_exact_direct(const Geometry &g, ExactPlan &pl);
 int launch_exact_direct(const Geometry &g, const ExactPlan &pl, const void *X, const void *dY, float *dW, void *ws,

@@ -41,7 +41,7 @@ static __device__ long long g_trace_fused[4 * 8192];
 #else
 #define FTRACE(i) do { } while (0)
 #define FTRACE_G(gi) do { } while (0)
-#define FTRACE_SET(i, v) do { } while (0)
+#define FTRACE_SET(i, v) do { (void)(v); } while (0)
 #define FTRACE_CLOCK() 0ll
 #define WGRAD_FUSED_TRACE_READER(name)
 #endif

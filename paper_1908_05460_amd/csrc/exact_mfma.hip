@@ -487,6 +487,8 @@ ExactPlan plan_exact(const Geometry &g, bool allow_stream)
     ExactPlan pl{};
     const int RS = g.R * g.S;
     const long CRS = g.crs();
+    // (the rest of the plan is still made: tensors that are not 16-byte aligned take the general kernels)
+    pl.plane2 = allow_stream && tune_int("WGRAD_EXACT_PLANE2", 1) && plane2_takes(g);
     pl.wk = g.K <= 16 ? 1 : (g.K <= 32 ? 2 : 4);
     const int KT = 16 * pl.wk, WQ = 4 / pl.wk;
     if (g.C % 16 == 0 && RS == 9) { pl.tap_mode = 1; pl.nt = 9; }
@@ -624,6 +626,7 @@ static int launch_exact_staged(const Geometry &g, const ExactPlan &pl, const voi
 int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void *ws, hipStream_t st, CombineQueue *defer,
                  MultiQueue *mq, int mq_blocks, Bf16Queue *bq)
 {
+    if (plan.plane2 && batch_aligned(g, b, 4, 4)) return launch_exact_plane2(g, b, st, mq);   // no split, no partial sums
     if ((plan.stream || plan.mm16) && batch_aligned(g, b, plan.xv, plan.mm16 ? 8 : 4)) {
         // one launch for the whole batch; problem i owns the i-th slice of the workspace.  The
         // workgroup target is for the whole launch: a batch splits each reduction less finely.

@@ -6,7 +6,7 @@
 // streaming body.  Workgroups of different groups share the CUs, so one group's ramp and tail hide
 // under the others' matrix work, and each group can be cut into fewer, longer workgroups.
 #define WGRAD_TRACE_HERE
-#include "exact_stream_kernel.hpp"
+#include "exact_plane2_kernel.hpp"
 
 namespace wgrad {
 
@@ -25,6 +25,8 @@ struct MultiParams {
     X(0, 2, 1, 4, 8, 0)  X(1, 9, 1, 4, 4, 36) X(2, 9, 2, 4, 2, 36) X(3, 9, 2, 4, 8, 20)  \
     X(4, 9, 4, 4, 4, 20) X(5, 9, 4, 4, 8, 12) X(6, 2, 4, 4, 8, 0)  X(7, 9, 4, 4, 8, 36)  \
     X(8, 9, 4, 4, 8, 20) X(9, 9, 4, 4, 4, 12) X(10, 9, 4, 2, 4, 4)
+
+constexpr int kMultiPlane2 = 11;    // the 2x2-plane matrix-product form rides along as one more variant
 
 int multi_variant(int nt, int wk, int xv, int gpw, int rowp)
 {
@@ -50,6 +52,7 @@ __global__ __launch_bounds__(kBlock, 3) void wgrad_exact_multi(const MultiParams
 #define X(ID, NT, WK, XV, GPW, ROWP) case ID: stream_body<NT, WK, false, XV, GPW, ROWP>(p, smem, bid, nblk); break;
         WGRAD_MULTI_VARIANTS(X)
 #undef X
+        case kMultiPlane2: plane2_body(p, bid); break;
         default: break;
     }
 }
@@ -72,7 +75,7 @@ int multi_flush(MultiQueue &q, hipStream_t st)
         const StreamLaunch &L = q.item[i];
         mp.begin[i] = blocks;
         mp.count[i] = L.grid;
-        mp.variant[i] = multi_variant(L.nt, L.wk, L.xv, L.gpw, L.rowp_inst);
+        mp.variant[i] = L.plane2 ? kMultiPlane2 : multi_variant(L.nt, L.wk, L.xv, L.gpw, L.rowp_inst);
         mp.p[i] = L.p;
         blocks += (L.grid + 7) / 8 * 8;
         if (L.lds > lds) lds = L.lds;

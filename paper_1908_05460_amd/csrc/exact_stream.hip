@@ -66,7 +66,8 @@ bool plan_exact_stream(const Geometry &g, ExactPlan &pl)
 
 int launch_stream_now(const StreamLaunch &L, hipStream_t st)
 {
-    if (L.wk == 1) stream_launch_w1(L.p, L.nt, L.xv, L.gpw, L.rowp_inst, L.grid, L.lds, st);
+    if (L.plane2) launch_plane2_kernel(L, st);
+    else if (L.wk == 1) stream_launch_w1(L.p, L.nt, L.xv, L.gpw, L.rowp_inst, L.grid, L.lds, st);
     else if (L.wk == 2) stream_launch_w2(L.p, L.nt, L.xv, L.gpw, L.rowp_inst, L.grid, L.lds, st);
     else stream_launch_w4(L.p, L.nt, L.xv, L.gpw, L.rowp_inst, L.grid, L.lds, st);
     return launch_status();

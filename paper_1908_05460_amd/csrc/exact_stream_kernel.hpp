@@ -410,6 +410,7 @@ constexpr int kMultiMax = 6;        // groups per multi-shape launch (their para
 struct StreamLaunch {
     StreamParams p;
     int nt, wk, xv, gpw, rowp_inst, grid;
+    int plane2;                 // the 2x2-plane matrix-product form (exact_plane2_kernel.hpp): only the tensors, g and per_prob of p are set
     size_t lds;
 };
 struct MultiQueue {
@@ -418,6 +419,7 @@ struct MultiQueue {
 };
 int multi_variant(int nt, int wk, int xv, int gpw, int rowp);     // -1: not among the shapes a multi launch mixes
 int launch_stream_now(const StreamLaunch &L, hipStream_t st);
+void launch_plane2_kernel(const StreamLaunch &L, hipStream_t st);
 int multi_flush(MultiQueue &q, hipStream_t st);
 
 // Per-K-tile-width launchers, each instantiated in its own translation unit.
