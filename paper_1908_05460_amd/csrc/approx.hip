@@ -426,133 +426,198 @@ __device__ __forceinline__ void gather_lds_body(const ApproxBatch &ab, const Geo
         }
     }
 
-    // issue the loads of the group starting at image n0 (registers only)
-    auto prefetch = [&](int n0) {
-        // lane l of every wavefront: map (image n0 + l / M, channel k_base + l % M).  Issued before
-        // the plane loads: memory returns in order, so once the planes have arrived these have too.
-        if (TOPK) {
-            const int per_img = M * gp.tk;
-            const int n = n0 + lane / per_img, q = lane % per_img;
-            const int k = k_base + q / gp.tk, t = q % gp.tk;
-            const bool ok = lane < nb * per_img && n < n_end && k < g.K;
-            hw_next = ok ? hw[((long)n * g.K + k) * gp.tk + t] : 0;
-            sv_next = ok ? sum[(long)n * g.K + k] * gp.inv_k : 0.f;
-        } else {
-            const int n = n0 + lane / M, k = k_base + lane % M;
-            const bool ok = lane < nb * M && n < n_end && k < g.K;
-            hw_next = ok ? hw[(long)n * g.K + k] : 0;
-            sv_next = ok ? sum[(long)n * g.K + k] : 0.f;
-        }
+    // (position, sum) of the maps, one per lane, for a block of blk_groups groups at a time (not per group: with
+    // one image of 8x8 planes per group, two loads per wavefront and group that serve two lanes each cost as much
+    // of the load path as the planes themselves): lane l holds map (image b0 + l / M, channel k_base + l % M).
+    const int blk_groups = (64 / M) / nb;                  // nb <= 64 / M
+    const int blk_images = blk_groups * nb;
+    int hw_blk = 0, hw_blk_next = 0;
+    float sv_blk = 0.f, sv_blk_next = 0.f;
+    auto prefetch_maps = [&](int b0) {
+        const int n = b0 + lane / M, k = k_base + lane % M;
+        const bool ok = lane < blk_images * M && n < n_end && k < g.K;
+        hw_blk_next = ok ? hw[(long)n * g.K + k] : 0;
+        sv_blk_next = ok ? sum[(long)n * g.K + k] : 0.f;
+    };
+    // Issue the loads of slots [U0, U0 + UN) of the group starting at image n0 (registers only).  ALWAYS: every
+    // slot loads -- one without a piece re-reads the group's first piece -- so that the number of loads in flight
+    // is fixed and a later wait can name exactly the older ones.
+    auto prefetch_slots = [&](int n0, auto u0_c, auto un_c, auto always_c) {
+        constexpr int U0 = decltype(u0_c)::value, UN = decltype(un_c)::value;
+        constexpr bool ALWAYS = decltype(always_c)::value;
         const int nb_cur = n_end - n0 < nb ? n_end - n0 : nb;
         const long base = ((long)n0 * g.C + c0) * HW;
 #pragma unroll
-        for (int u = 0; u < kGatherSlots; ++u)
+        for (int u = 0; u < UN; ++u) {
+            const bool live = slot_dst[u] >= 0 && (slot_dst[u] >> 20) < nb_cur;
+            if (ALWAYS || live) {
+                const long src = base + (live ? slot_src[u] : 0u);
+                xr[U0 + u] = BF16 ? *(const raw4 *)((const uint16_t *)X + src) : *(const raw4 *)((const float *)X + src);
+            }
+        }
+    };
+    // top-k form: the kept positions and weights of the group's maps, one per lane
+    auto prefetch_topk = [&](int n0) {
+        const int per_img = M * gp.tk;
+        const int n = n0 + lane / per_img, q = lane % per_img;
+        const int k = k_base + q / gp.tk, t = q % gp.tk;
+        const bool ok = lane < nb * per_img && n < n_end && k < g.K;
+        hw_next = ok ? hw[((long)n * g.K + k) * gp.tk + t] : 0;
+        sv_next = ok ? sum[(long)n * g.K + k] * gp.inv_k : 0.f;
+    };
+    // registers of slots [U0, U0 + UN) -> LDS (interior of the haloed planes)
+    auto commit_slots = [&](int nb_cur, float *buf, auto u0_c, auto un_c) {
+        constexpr int U0 = decltype(u0_c)::value, UN = decltype(un_c)::value;
+#pragma unroll
+        for (int u = 0; u < UN; ++u)
             if (slot_dst[u] >= 0 && (slot_dst[u] >> 20) < nb_cur) {
-                const long src = base + slot_src[u];
-                xr[u] = BF16 ? *(const raw4 *)((const uint16_t *)X + src) : *(const raw4 *)((const float *)X + src);
+                float v[4];
+                if (BF16) {
+                    const uint2 r = *(const uint2 *)&xr[U0 + u];
+                    v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
+                    v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
+                } else {
+                    const float4 r = *(const float4 *)&xr[U0 + u];
+                    v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
+                }
+                float *dst = buf + (slot_dst[u] & 0xfffff);
+                if (rowmode == 0) {
+                    dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
+                } else if (rowmode == 1) {
+                    dst[0] = v[0]; dst[1] = v[1]; dst[WP] = v[2]; dst[WP + 1] = v[3];
+                } else {
+                    // dst is the cell of the piece's first element: walk on from its column
+                    const int cell0 = (slot_dst[u] & 0xfffff) % pitch;          // offset inside the haloed plane
+                    int iw = (cell0 % WP) - g.pw;
+                    float *q = dst;
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        *q = v[i];
+                        if (++iw == g.W) { iw = 0; q += WP - g.W + 1; } else ++q;
+                    }
+                }
             }
     };
+    // The patches of one group out of window buffer buf: one per (image, output channel) pair t = n_l * M + j, nine
+    // LDS reads and nine multiply-adds each.  The reads of pair t + 1 are issued before the multiply-adds of pair t
+    // (two register sets, alternating), so a wavefront always has a patch in flight behind the one it is adding.
+    // No branches inside the loop: a pair index beyond the group re-reads the last pair and adds it with weight
+    // zero.  slot0: lane that holds the group's first map in hw_blk / sv_blk.
+    auto gather_group = [&](const float *buf, int nb_cur, int slot0) {
+        if (lane >= cvalid || nb_cur <= 0) return;
+        const float *plane = buf + lane * pitch;
+        const int T = nb_cur * M;
+        float v[2][9];
+        auto issue = [&](int t, float (&dst)[9]) {
+            t = t < T ? t : T - 1;
+            const int p = __builtin_amdgcn_readlane(hw_blk, slot0 + t);
+            const float *win = plane + (t / M) * (kGatherCT * pitch) + (p >> 16) * g.sh * WP + (p & 0xffff) * g.sw;
+#pragma unroll
+            for (int r = 0; r < 3; ++r)
+#pragma unroll
+                for (int s3 = 0; s3 < 3; ++s3) dst[r * 3 + s3] = win[r * WP + s3];
+        };
+        auto add = [&](int t, int j, const float (&src)[9]) {
+            float sv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sv_blk), slot0 + (t < T ? t : T - 1)));
+            sv = t < T ? sv : 0.f;
+#pragma unroll
+            for (int e = 0; e < 9; ++e) acc[j][e] = fmaf(sv, src[e], acc[j][e]);
+        };
+        constexpr int U = M == 1 ? 2 : M;               // pairs per trip: the output channel t % M and the register set
+        issue(0, v[0]);                                 // t & 1 of a pair are compile-time constants
+        for (int t0 = 0; t0 < T; t0 += U) {
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                issue(t0 + u + 1, v[(u + 1) & 1]);
+                add(t0 + u, u % M, v[u & 1]);
+            }
+        }
+    };
+    // the (position, sum) block of the group that starts at image n0; returns the lane of the group's first map
+    int gi_blk = 0;                                        // the group's number within its block of maps
+    auto maps_for_group = [&](int n0) {
+        if (gi_blk == blk_groups) gi_blk = 0;
+        if (gi_blk == 0) {
+            // a new block: take over what was requested a block ago (opaque moves: the wait sits here), request the next
+            asm volatile("v_mov_b32 %0, %1" : "=v"(hw_blk) : "v"(hw_blk_next));
+            asm volatile("v_mov_b32 %0, %1" : "=v"(sv_blk) : "v"(sv_blk_next));
+            if (n0 + blk_images < n_end) prefetch_maps(n0 + blk_images);
+        }
+        return gi_blk++ * nb * M;
+    };
+    using ic0 = std::integral_constant<int, 0>;
+    using ic2 = std::integral_constant<int, 2>;
+    using icS = std::integral_constant<int, kGatherSlots>;
 
     FTRACE(0);
     long long t_stage = 0, t_loop = 0, t_mark = FTRACE_CLOCK();
-    prefetch(n_begin);
-    int parity = 0;
-    for (int n0 = n_begin; n0 < n_end; n0 += nb, parity ^= 1) {
-        const int nb_cur = n_end - n0 < nb ? n_end - n0 : nb;
-        float *buf = xs + parity * buf_floats;
-        if (n0 == n_begin) __syncthreads();               // the zero fill is complete
-        {   // registers -> LDS (interior of the haloed planes)
-#pragma unroll
-            for (int u = 0; u < kGatherSlots; ++u)
-                if (slot_dst[u] >= 0 && (slot_dst[u] >> 20) < nb_cur) {
-                    float v[4];
-                    if (BF16) {
-                        const uint2 r = *(const uint2 *)&xr[u];
-                        v[0] = __uint_as_float(r.x << 16); v[1] = __uint_as_float(r.x & 0xffff0000u);
-                        v[2] = __uint_as_float(r.y << 16); v[3] = __uint_as_float(r.y & 0xffff0000u);
-                    } else {
-                        const float4 r = *(const float4 *)&xr[u];
-                        v[0] = r.x; v[1] = r.y; v[2] = r.z; v[3] = r.w;
-                    }
-                    float *dst = buf + (slot_dst[u] & 0xfffff);
-                    if (rowmode == 0) {
-                        dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
-                    } else if (rowmode == 1) {
-                        dst[0] = v[0]; dst[1] = v[1]; dst[WP] = v[2]; dst[WP + 1] = v[3];
-                    } else {
-                        // dst is the cell of the piece's first element: walk on from its column
-                        const int cell0 = (slot_dst[u] & 0xfffff) % pitch;          // offset inside the haloed plane
-                        int iw = (cell0 % WP) - g.pw;
-                        float *q = dst;
-#pragma unroll
-                        for (int i = 0; i < 4; ++i) {
-                            *q = v[i];
-                            if (++iw == g.W) { iw = 0; q += WP - g.W + 1; } else ++q;
-                        }
-                    }
-                }
+    // A group that needs at most two staging slots per thread (one image of 8x8 planes) is far shorter than a load
+    // takes to arrive: the four slot registers then hold TWO groups, the loads of group g + 2 being issued while
+    // group g is computed.  Both groups of a trip run unconditionally (a group beyond the chunk commits and adds
+    // nothing) and every slot loads, so the wait before a commit names exactly its own loads.
+    const bool two_deep = !TOPK && kGatherSlots == 4 && nb * kGatherCT * hw4 <= 2 * kGatherBlock;
+    if (two_deep) {
+        prefetch_maps(n_begin);
+        prefetch_slots(n_begin, ic0(), ic2(), std::true_type());
+        prefetch_slots(n_begin + nb < n_end ? n_begin + nb : n_end - 1, ic2(), ic2(), std::true_type());
+        __syncthreads();                                   // the zero fill is complete
+        auto one_group = [&](int n0, auto set_c) {
+            constexpr int SET = decltype(set_c)::value;
+            const int nb_cur = n0 >= n_end ? 0 : (n_end - n0 < nb ? n_end - n0 : nb);
+            float *buf = xs + SET * buf_floats;
+            const int slot0 = nb_cur > 0 ? maps_for_group(n0) : 0;
+            commit_slots(nb_cur, buf, std::integral_constant<int, 2 * SET>(), ic2());
+            __syncthreads();
+            prefetch_slots(n0 + 2 * nb < n_end ? n0 + 2 * nb : n_end - 1, std::integral_constant<int, 2 * SET>(), ic2(), std::true_type());
+            { const long long now = FTRACE_CLOCK(); t_stage += now - t_mark; t_mark = now; }
+            gather_group(buf, nb_cur, slot0);
+            { const long long now = FTRACE_CLOCK(); t_loop += now - t_mark; t_mark = now; }
+        };
+        for (int n0 = n_begin; n0 < n_end; n0 += 2 * nb) {
+            one_group(n0, ic0());
+            one_group(n0 + nb, std::integral_constant<int, 1>());
         }
-        // Copy through an opaque move: it makes the wait for these two loads happen here, where
-        // they have long arrived, instead of at their first use below, after the next group's
-        // loads have been issued (the memory counter is in-order: waiting there would drain those).
-        int hw_cur;
-        float sv_cur;
-        asm volatile("v_mov_b32 %0, %1" : "=v"(hw_cur) : "v"(hw_next));
-        asm volatile("v_mov_b32 %0, %1" : "=v"(sv_cur) : "v"(sv_next));
-        __syncthreads();
-        if (n0 + nb < n_end) prefetch(n0 + nb);
-        { const long long now = FTRACE_CLOCK(); t_stage += now - t_mark; t_mark = now; }
-
-        if (lane < cvalid && !TOPK) {
-            // One patch per (image, output channel) pair t = n_l * M + j of the group, nine LDS reads and nine
-            // multiply-adds each.  The reads of pair t + 1 are issued before the multiply-adds of pair t (two
-            // register sets, alternating), so a wavefront always has a patch in flight behind the one it is adding.
-            const float *plane = buf + lane * pitch;
-            const int T = nb_cur * M;
-            float v[2][9];
-            // (no branches inside the loop: a pair index beyond the group re-reads the last pair and adds it
-            // with weight zero)
-            auto issue = [&](int t, float (&dst)[9]) {
-                t = t < T ? t : T - 1;
-                const int p = __builtin_amdgcn_readlane(hw_cur, t);
-                const float *win = plane + (t / M) * (kGatherCT * pitch) + (p >> 16) * g.sh * WP + (p & 0xffff) * g.sw;
-#pragma unroll
-                for (int r = 0; r < 3; ++r)
-#pragma unroll
-                    for (int s3 = 0; s3 < 3; ++s3) dst[r * 3 + s3] = win[r * WP + s3];
-            };
-            auto add = [&](int t, int j, const float (&src)[9]) {
-                float sv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sv_cur), t < T ? t : T - 1));
-                sv = t < T ? sv : 0.f;
-#pragma unroll
-                for (int e = 0; e < 9; ++e) acc[j][e] = fmaf(sv, src[e], acc[j][e]);
-            };
-            constexpr int U = M == 1 ? 2 : M;           // pairs per trip: the output channel t % M and the register set
-            issue(0, v[0]);                             // t & 1 of a pair are compile-time constants
-            for (int t0 = 0; t0 < T; t0 += U) {
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    issue(t0 + u + 1, v[(u + 1) & 1]);
-                    add(t0 + u, u % M, v[u & 1]);
-                }
+    } else {
+        if (TOPK) prefetch_topk(n_begin); else prefetch_maps(n_begin);
+        prefetch_slots(n_begin, ic0(), icS(), std::false_type());
+        int parity = 0;
+        for (int n0 = n_begin; n0 < n_end; n0 += nb, parity ^= 1) {
+            const int nb_cur = n_end - n0 < nb ? n_end - n0 : nb;
+            float *buf = xs + parity * buf_floats;
+            const int slot0 = TOPK ? 0 : maps_for_group(n0);
+            if (n0 == n_begin) __syncthreads();           // the zero fill is complete
+            commit_slots(nb_cur, buf, ic0(), icS());
+            // Copy through an opaque move: it makes the wait for these two loads happen here, where
+            // they have long arrived, instead of at their first use below, after the next group's
+            // loads have been issued (the memory counter is in-order: waiting there would drain those).
+            int hw_cur;
+            float sv_cur;
+            asm volatile("v_mov_b32 %0, %1" : "=v"(hw_cur) : "v"(hw_next));
+            asm volatile("v_mov_b32 %0, %1" : "=v"(sv_cur) : "v"(sv_next));
+            __syncthreads();
+            if (n0 + nb < n_end) {
+                if (TOPK) prefetch_topk(n0 + nb);
+                prefetch_slots(n0 + nb, ic0(), icS(), std::false_type());
             }
-        }
-        { const long long now = FTRACE_CLOCK(); t_loop += now - t_mark; t_mark = now; }
-        if (lane < cvalid && TOPK) {
-            const float *plane = buf + lane * pitch;
-            for (int n_l = 0; n_l < nb_cur; ++n_l, plane += kGatherCT * pitch) {
+            { const long long now = FTRACE_CLOCK(); t_stage += now - t_mark; t_mark = now; }
+            if (!TOPK) gather_group(buf, nb_cur, slot0);
+            { const long long now = FTRACE_CLOCK(); t_loop += now - t_mark; t_mark = now; }
+            if (lane < cvalid && TOPK) {
+                const float *plane = buf + lane * pitch;
+                for (int n_l = 0; n_l < nb_cur; ++n_l, plane += kGatherCT * pitch) {
 #pragma unroll
-                for (int j = 0; j < M; ++j) {
-                    for (int t = 0; t < gp.tk; ++t) {
-                        const int slot = (n_l * M + j) * gp.tk + t;
-                        const int p = __builtin_amdgcn_readlane(hw_cur, slot);
-                        const float sv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sv_cur), slot));
-                        const float *win = plane + (p >> 16) * g.sh * WP + (p & 0xffff) * g.sw;   // window origin
+                    for (int j = 0; j < M; ++j) {
+                        for (int t = 0; t < gp.tk; ++t) {
+                            const int slot = (n_l * M + j) * gp.tk + t;
+                            const int p = __builtin_amdgcn_readlane(hw_cur, slot);
+                            const float sv = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, sv_cur), slot));
+                            const float *win = plane + (p >> 16) * g.sh * WP + (p & 0xffff) * g.sw;   // window origin
 #pragma unroll
-                        for (int r = 0; r < 3; ++r) {
-                            const float *row = win + r * WP;
+                            for (int r = 0; r < 3; ++r) {
+                                const float *row = win + r * WP;
 #pragma unroll
-                            for (int s = 0; s < 3; ++s) acc[j][r * 3 + s] = fmaf(sv, row[s], acc[j][r * 3 + s]);
+                                for (int s = 0; s < 3; ++s) acc[j][r * 3 + s] = fmaf(sv, row[s], acc[j][r * 3 + s]);
+                            }
                         }
                     }
                 }
