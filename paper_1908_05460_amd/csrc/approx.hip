@@ -1476,7 +1476,9 @@ ApproxPlan plan_approx(const Geometry &g, bool allow_lds, bool allow_fused, bool
                  && (size_t)2 * kGatherCT * pitch * 4 <= kGatherLds;
     long chunks;
     if (pl.use_lds) {
-        pl.m = g.K >= 256 ? 2 : 1;
+        // output channels per wavefront: four where K allows (the work between two barriers doubles against two, the
+        // re-staging of X per output channel halves: VGG-19 fp32 approximation phase -6 %)
+        pl.m = g.K >= 256 ? 4 : 1;
         pl.pitch = pitch;
         pl.wp = wp;
         // images per group: at most 8 16-byte loads per thread, one lane per (image, channel) pair
@@ -1492,6 +1494,9 @@ ApproxPlan plan_approx(const Geometry &g, bool allow_lds, bool allow_fused, bool
         chunks = tiles >= want_blocks ? 1 : (want_blocks + tiles - 1) / tiles;
         const long max_chunks = (g.N + pl.nb - 1) / pl.nb;
         if (chunks > max_chunks) chunks = max_chunks;
+        // the batch-chunk partial sums are written and read once each: never more than 20 MiB of them
+        const long by_bytes = (20l << 20) / (outs * 4) < 1 ? 1 : (20l << 20) / (outs * 4);
+        if (chunks > by_bytes) chunks = by_bytes;
     } else if (allow_fused && tune_int("WGRAD_APPROX_FUSED", 1) && (g.Ho * g.Wo) % 4 == 0
                && g.Ho * g.Wo <= 64 * kFusedV * 4 && g.crs() <= 64 * kFusedJ * kFusedSlices && g.R * g.S <= 63
                && ((long)g.H + 2l * g.ph + g.R) * ((long)g.W + 2l * g.pw + g.S) * g.C < (1l << 24)) {
@@ -1538,7 +1543,7 @@ static void launch_gather_lds(const ApproxPlan &pl, dim3 grid, size_t lds, hipSt
 {
     const GatherParams gp = gather_params(pl, g, scale);
 #define GL_ARGS grid, dim3(kGatherBlock), lds, st, ab, g, gp
-    if (pl.m == 2) WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 2>), GL_ARGS);
+    if (pl.m == 4) WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 4>), GL_ARGS);
     else WGRAD_LAUNCH((approx_gather_lds3x3<BF16, 1>), GL_ARGS);
 #undef GL_ARGS
 }
@@ -1581,8 +1586,8 @@ int gather_flush(GatherQueue &q, hipStream_t st)
     q.n = 0; q.lds = 0;
     if (blocks >= (1l << 31)) return WGRAD_UNSUPPORTED;
 #define GM_ARGS dim3((unsigned)blocks), dim3(kGatherBlock), lds, st, m
-    if (bf16) { if (mm == 2) WGRAD_LAUNCH((approx_gather_lds_multi<true, 2>), GM_ARGS); else WGRAD_LAUNCH((approx_gather_lds_multi<true, 1>), GM_ARGS); }
-    else      { if (mm == 2) WGRAD_LAUNCH((approx_gather_lds_multi<false, 2>), GM_ARGS); else WGRAD_LAUNCH((approx_gather_lds_multi<false, 1>), GM_ARGS); }
+    if (bf16) { if (mm == 4) WGRAD_LAUNCH((approx_gather_lds_multi<true, 4>), GM_ARGS); else WGRAD_LAUNCH((approx_gather_lds_multi<true, 1>), GM_ARGS); }
+    else      { if (mm == 4) WGRAD_LAUNCH((approx_gather_lds_multi<false, 4>), GM_ARGS); else WGRAD_LAUNCH((approx_gather_lds_multi<false, 1>), GM_ARGS); }
 #undef GM_ARGS
     return launch_status();
 }
@@ -1685,9 +1690,9 @@ bool topk_gather_lds(const Geometry &g, const void *X, const int32_t *hw, const 
     const dim3 grid(pl.ctiles * pl.ktiles, pl.chunks, 1);
     const size_t lds = (size_t)2 * pl.nb * kGatherCT * pl.pitch * 4;
 #define GL_ARGS grid, dim3(kGatherBlock), lds, st, ab, g, gp
-    if (g.bf16) { if (pl.m == 2) WGRAD_LAUNCH((approx_gather_lds3x3<true, 2, true>), GL_ARGS);
+    if (g.bf16) { if (pl.m == 4) WGRAD_LAUNCH((approx_gather_lds3x3<true, 4, true>), GL_ARGS);
                   else           WGRAD_LAUNCH((approx_gather_lds3x3<true, 1, true>), GL_ARGS); }
-    else        { if (pl.m == 2) WGRAD_LAUNCH((approx_gather_lds3x3<false, 2, true>), GL_ARGS);
+    else        { if (pl.m == 4) WGRAD_LAUNCH((approx_gather_lds3x3<false, 4, true>), GL_ARGS);
                   else           WGRAD_LAUNCH((approx_gather_lds3x3<false, 1, true>), GL_ARGS); }
 #undef GL_ARGS
     *rc = launch_status();
