@@ -704,6 +704,7 @@ struct FusedParams {
     int tk;                      // top-k form only: kept positions per map, each weighted by sum * inv_k
     float inv_k;
     int nslice;                  // workgroups per output channel, each owning kFusedJ * 64 of its C*R*S entries
+    int slice_major;             // numbering of the nslice * K workgroups of a chunk: all K of slice 0 first (1), or the slices of a channel side by side (0)
     int rows3;                   // filter-row form (fp32, NCHW, S = 3): (channel, row) pairs per lane, 1..3; 0 = element form
     FastDiv d_r;
 };
@@ -743,10 +744,13 @@ __device__ __forceinline__ void fused_body(const ApproxBatch &ab, const Geometry
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     // The K workgroups of one (problem, batch chunk) read the same input planes: number the workgroups so
     // that they sit on one XCD and find each other's planes in its L2.
-    // nk = K * fp.nslice: the slices of one output channel are neighbours (they scan the same maps)
+    // nk = K * fp.nslice.  Slice-major numbering: the K workgroups of one slice are neighbours, so an XCD that runs a
+    // slice needs only that slice's 64 input channels of the chunk in its L2 (the maps are then fetched once per
+    // slice: measured 93 -> 64 MB on 128->128 @ 16x16, N = 128, against the slices of a channel side by side).
     const int logical = xcd_contiguous_id(linear, nk * nchunks * nprob);
     const int kk = logical % nk;
-    const int k = kk / fp.nslice, j_base = (kk - k * fp.nslice) * (kFusedJ * 64);
+    const int k = fp.slice_major ? kk % g.K : kk / fp.nslice;
+    const int j_base = (fp.slice_major ? kk / g.K : kk - k * fp.nslice) * (kFusedJ * 64);
     const bool first_slice = j_base == 0;                  // writes the optional position / sum outputs
     const int by = (logical / nk) % nchunks, bz = logical / (nk * nchunks);
     const char *__restrict__ X = (const char *)ab.X[bz];
@@ -1044,7 +1048,7 @@ __device__ __forceinline__ void fused3_body(const ApproxBatch &ab, const Geometr
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int logical = xcd_contiguous_id(linear, nk * nchunks * nprob);
     const int kk = logical % nk;
-    const int k = kk / fp.nslice, slice = kk - k * fp.nslice;
+    const int k = fp.slice_major ? kk % g.K : kk / fp.nslice, slice = fp.slice_major ? kk / g.K : kk - k * fp.nslice;
     const bool first_slice = slice == 0;
     const int by = (logical / nk) % nchunks, bz = logical / (nk * nchunks);
     const char *__restrict__ X = (const char *)ab.X[bz];
@@ -1644,7 +1648,7 @@ bool topk_fused(const Geometry &g, const Batch &b, int k, float scale,
     FusedParams fp;
     fp.chunk_n = pl.chunk_n; fp.scale = pl.chunks > 1 ? 1.0f : scale;
     fp.d_rs = FastDiv(g.R * g.S); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
-    fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = k; fp.inv_k = 1.0f / k; fp.nslice = fused_slices(g);
+    fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = k; fp.inv_k = 1.0f / k; fp.nslice = fused_slices(g); fp.slice_major = tune_int("WGRAD_FUSED_SLICE_MAJOR", 1);
     fp.rows3 = 0; fp.d_r = FastDiv(g.R);
     if (fq) {
         if (fq->n == kFusedMultiMax || (fq->n > 0 && (fq->bf16 != g.bf16 || !fq->topk))) {
@@ -1809,7 +1813,7 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         FusedParams fp;
         fp.chunk_n = pl.chunk_n; fp.scale = kscale;
         fp.d_rs = FastDiv(g.R * g.S); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
-        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = 1; fp.inv_k = 1.0f; fp.nslice = fused_slices(g);
+        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = WGRAD_DW_OIHW; fp.tk = 1; fp.inv_k = 1.0f; fp.nslice = fused_slices(g); fp.slice_major = tune_int("WGRAD_FUSED_SLICE_MAJOR", 1);
         fp.rows3 = tune_int("WGRAD_FUSED_ROWS3", 1) ? fused_rows3(g) : 0; fp.d_r = FastDiv(g.R);
         if (fq) {
             // part of a multi-group launch (groups of one element type)
@@ -1900,7 +1904,7 @@ int launch_approx_nhwc(const Geometry &g, const void *X, const void *dY, float *
         FusedParams fp;
         fp.chunk_n = pl.chunk_n; fp.scale = kscale;
         fp.d_rs = FastDiv(g.C); fp.d_s = FastDiv(g.S); fp.d_wo = FastDiv(g.Wo);
-        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = dw_layout; fp.tk = 1; fp.inv_k = 1.0f; fp.nslice = fused_slices(g);
+        fp.flat_out = idx_out; fp.sum_out = sum_out; fp.dw_layout = dw_layout; fp.tk = 1; fp.inv_k = 1.0f; fp.nslice = fused_slices(g); fp.slice_major = tune_int("WGRAD_FUSED_SLICE_MAJOR", 1);
         fp.rows3 = 0; fp.d_r = FastDiv(g.R);
         const dim3 grid(g.K * fp.nslice, pl.chunks, 1);
         if (g.bf16) WGRAD_LAUNCH((approx_fused_nhwc<true>), grid, dim3(kBlock), 0, st, ab, g, fp);
