@@ -211,12 +211,17 @@ def run_workload(args, name, machine, steps, warmup, headline):
 
     lds_roof = machine["lds_read_b32_gbs"] if machine else None
     tot = {"exact_us": 0.0, "approx_us": 0.0, "flops": 0.0, "valid_flops": 0.0, "approx_bytes": 0.0,
-           "hbm_set_bytes": 0.0, "hbm_set_us": 0.0, "roof_us": 0.0}
+           "hbm_set_bytes": 0.0, "hbm_set_us": 0.0, "roof_us": 0.0, "exact_roof_us": 0.0, "exact_hbm_layers": []}
     seen_shapes = {}
     for i, l in enumerate(stack):
         d = descs[i]
         fl, vfl, ab = l.flops(N), l.valid_flops(N), approx_algorithmic_bytes(l, N, e)
         tot["flops"] += fl; tot["valid_flops"] += vfl; tot["approx_bytes"] += ab
+        # the roof that binds the exact gradient of this layer: the matrix core for its nominal FLOPs, or HBM for its
+        # operands where those take longer (few channels: 3->64, and 64->64 with bf16 inputs)
+        t_ex_mm, t_ex_hbm = fl / (MFMA_PEAK_TFLOPS[dtype] * 1e6), exact_min_bytes(l, N, e) / (HBM_PEAK_GBS * 1e3)
+        tot["exact_roof_us"] += max(t_ex_mm, t_ex_hbm)
+        if t_ex_hbm > t_ex_mm: tot["exact_hbm_layers"].append(l.name)
         if reps <= 0:       # counter runs: no single-layer calls
             continue
         key = (l.C, l.K, l.H, l.stride)
@@ -248,6 +253,7 @@ def run_workload(args, name, machine, steps, warmup, headline):
                "exact_us": round(t_ex, 2), "approx_us": round(t_ap, 2), "select_us": round(t_sel, 2),
                "exact_tflops": round(fl / t_ex / 1e6, 2), "exact_valid_tflops": round(vfl / t_ex / 1e6, 2),
                "exact_frac_mfma": round(fl / t_ex / 1e6 / MFMA_PEAK_TFLOPS[dtype], 4),
+               "exact_bound": "hbm" if t_ex_hbm > t_ex_mm else "mfma", "exact_roof_us": round(max(t_ex_mm, t_ex_hbm), 2),
                "approx_gbs": round(ab / t_ap / 1e3, 1),
                "approx_frac_hbm": round(ab / t_ap / 1e3 / HBM_PEAK_GBS, 4),
                "approx_bound": bound, "approx_roof_us": round(t_roof, 2),
@@ -306,6 +312,9 @@ def run_workload(args, name, machine, steps, warmup, headline):
                 "achieved_best": round(tot["flops"] / phase_min["exact"] / 1e9, 3),
                 "algorithmic_flops": tot["flops"], "valid_tap_flops": tot["valid_flops"],
                 "algorithmic_min_bytes": sum(exact_min_bytes(l, N, e) for l in stack),
+                "binding_roofs": {"note": "sum over the layers of max(nominal FLOPs / matrix-core peak, minimal bytes / HBM peak) against the phase time",
+                                  "sum_roof_us": round(tot["exact_roof_us"], 1), "hbm_bound_layers": tot["exact_hbm_layers"],
+                                  "frac": round(tot["exact_roof_us"] / (phase_ms["exact"] * 1e3), 4)},
                 "layers": nl, "phase_us": round(phase_ms["exact"] * 1e3, 1), "phase_us_min": round(phase_min["exact"] * 1e3, 1),
                 "single_layer_calls": {"sum_us": round(tot["exact_us"], 1),
                                        "tflops": round(tot["flops"] / tot["exact_us"] / 1e6, 2)} if single else None}
