@@ -317,6 +317,11 @@ static int schedule_run_impl(const wgrad_conv_desc *layers, const void *const *X
                 // input channels (bound by the dY stream), strides (a window four times the tile)
                 if (gj.C < 16) w *= tune_int("WGRAD_MULTI_W_FLAT", 20) / 10.0;
                 if (gj.sh > 1 || gj.sw > 1) w *= tune_int("WGRAD_MULTI_W_STRIDE", 25) / 10.0;
+                // 4x4 planes: their tiles are half as long (the window of eight images does not fit next to a
+                // second workgroup's), so a FLOP takes longer there even with the halo-only taps left out (swept)
+                const int wc = plan_exact(gj).wc;
+                if (wc == 1) w *= tune_int("WGRAD_MULTI_W_WC1", 125) / 100.0;
+                if (wc == 2) w *= tune_int("WGRAD_MULTI_W_WC2", 100) / 100.0;
                 f += w;
             }
         return f;

@@ -56,6 +56,16 @@ bool plan_exact_stream(const Geometry &g, ExactPlan &pl)
         if (lds > lds_cap || x_slots > (long)stream_xslots(pl.wk, gpw) * kBlock || iht > 255 || (long)xbuf >= (1 << 20)) continue;
         if ((long)nti * g.K * L * 4 >= (1l << 31) || (long)nti * g.C * g.H * g.W * 4 >= (1l << 31)) continue;
         pl.stream = 1; pl.gpw = gpw; pl.xv = xv;
+        // column-uniform position order (the taps that meet only the zero halo are left out): 3x3, stride 1,
+        // padding 1, rows of four or eight positions, K tiles of 64, whole blocks of four rows
+        pl.wc = 0;
+        if (tune_int("WGRAD_STREAM_WC", 1) && !g.bf16 && pl.tap_mode && pl.nt == 9 && xv == 4
+            && (pl.wk == 4 || (pl.wk == 2 && g.Wo == 16 && tune_int("WGRAD_STREAM_WC_K32", 1)))
+            && g.R == 3 && g.S == 3 && g.sh == 1 && g.sw == 1 && g.ph == 1 && g.pw == 1
+            && ((g.Wo == 4 && gpw == 4 && rowp == 12) || (g.Wo == 8 && gpw == 8 && rowp == 12)
+                || (tune_int("WGRAD_STREAM_WC_WIDE", 1) && ((g.Wo == 16 && gpw == 8 && rowp == 20) || (g.Wo == 32 && gpw == 8 && rowp == 36))))
+            && ht % 4 == 0 && q % 16 == 0)
+            pl.wc = g.Wo / 4;
         pl.nti = nti; pl.ht = ht; pl.q = q; pl.qpad = qt; pl.qp = 0;
         pl.iht = iht; pl.iwt = iwt; pl.pp = pp; pl.xbuf = xbuf; pl.rowp = rowp;
         pl.lds_bytes = lds;
@@ -92,6 +102,8 @@ int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, 
     p.seg = pl.ht * g.Wo;
     p.xbuf = pl.xbuf;
     p.rowp = pl.rowp;
+    p.wc = pl.wc;
+    p.d_gpi = FastDiv(pl.wc ? (pl.ht / 4) * pl.wc : 1);
     p.d_wv = FastDiv(g.W / pl.xv);
     p.d_rows = FastDiv(pl.nti * pl.iht);
     p.d_iht = FastDiv(pl.iht);
@@ -110,8 +122,10 @@ int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, 
     L.grid = pl.ktiles * pl.ctiles * pl.splits * b.n;
     L.rowp_inst = stream_has_rowp(pl.rowp, pl.xv) && pl.nt == 9 && pl.tap_mode ? pl.rowp : 0;
     L.nt = pl.nt; L.wk = pl.wk; L.xv = pl.xv; L.gpw = pl.gpw; L.lds = pl.lds_bytes;
+    L.wc = L.rowp_inst ? pl.wc : 0;
+    p.wc = L.wc;
     // up to three workgroups per CU must fit next to each other for a mixed launch to pay
-    if (mq && !g.bf16 && L.lds <= 52 * 1024 && multi_variant(L.nt, L.wk, L.xv, L.gpw, L.rowp_inst) >= 0) {
+    if (mq && !g.bf16 && L.lds <= 52 * 1024 && multi_variant(L.nt, L.wk, L.xv, L.gpw, L.rowp_inst, L.wc) >= 0) {
         if (mq->n == kMultiMax) {
             const int rc = multi_flush(*mq, st);
             if (rc != WGRAD_OK) return rc;

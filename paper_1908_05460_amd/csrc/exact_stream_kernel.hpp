@@ -58,7 +58,9 @@ struct StreamParams {
     int seg;                    // ht * Wo : contiguous dY elements per (image, channel) in a tile
     int xbuf;                   // floats per LDS window buffer (multiple of 4)
     int rowp;                   // LDS pitch of a window row (>= iwt)
+    int wc;                     // column-uniform position order: 4-column blocks per output row (0: row-major order)
     FastDiv d_wv, d_rows, d_iht, d_rs, d_s, d_seg, d_wo, d_htiles;
+    FastDiv d_gpi;              // column-uniform order: groups of 16 positions per image of a tile, (ht / 4) * wc
     int tile_c0[9], tile_toff[9], tile_tap[9];
 };
 
@@ -105,12 +107,19 @@ __device__ __forceinline__ void stream_column_of(const StreamParams &p, int colt
 // the nine taps of a step are then one per-lane address plus nine immediate offsets, and the
 // loop has one VALU instruction per nine MFMAs instead of nine (the adds, not LDS or the matrix
 // core, bound the loop otherwise).  ROWP = 0: run-time pitch and tap offsets (any filter).
+// WC (3x3, stride 1, padding 1, output rows of 4 * WC positions, tiles of a multiple of four rows): the
+// positions of a tile are taken in column-uniform order -- a group of 16 is four rows x four columns, lane group
+// kk holding row kk of it -- so that the four positions an MFMA step contracts share their column.  A step on the
+// first (last) column of a row then multiplies the taps of filter column 0 (2) with the zero halo only: those
+// three MFMAs and their LDS reads are left out, statically (the step's column block is gi % WC).  That is 1/6 of
+// the matrix work on 4x4 planes, 1/12 on 8x8.  WC = 0: row-major order, every tap multiplied.
 // The body takes the workgroup's number `bid` among the `nblk` workgroups of its launch (or of its
 // share of a launch that carries several shapes) and the dynamic LDS.
-template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP>
+template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP, int WC = 0>
 __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, int bid, int nblk)
 {
     static_assert(ROWP == 0 || NT == 9, "immediate tap offsets are for 3x3 filters in tap mode");
+    static_assert(WC == 0 || (ROWP != 0 && GPW % WC == 0), "the column-uniform order needs immediate taps and whole rows of blocks per wavefront");
     const int rowp = ROWP ? ROWP : p.rowp;
     constexpr int KT = 16 * WK, WQ = 4 / WK;
     constexpr int ESZ = BF16 ? 2 : 4;
@@ -159,7 +168,13 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
         a_off[gi] = 0;
         if (q < p.q && k_row < g.K) {
             uint32_t n_l, rem;
-            p.d_seg.divmod(q, n_l, rem);
+            if (WC) {                       // group -> (image, block of four rows, block of four columns); kk = row in the block
+                uint32_t gimg;
+                p.d_gpi.divmod((uint32_t)(wq * GPW + gi), n_l, gimg);
+                rem = (4 * (gimg / WC) + kk) * g.Wo + 4 * (gimg % WC);
+            } else {
+                p.d_seg.divmod(q, n_l, rem);
+            }
             a_off[gi] = ((n_l * g.K + (wk * 16 + i16)) * L + rem) * ESZ;
             a_live |= 1u << gi;
         }
@@ -268,8 +283,15 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
         int off = 0;
         if (q < p.q) {
             uint32_t n_l, rem, h_l, w;
-            p.d_seg.divmod(q, n_l, rem);
-            p.d_wo.divmod(rem, h_l, w);
+            if (WC) {
+                uint32_t gimg;
+                p.d_gpi.divmod((uint32_t)q >> 4, n_l, gimg);
+                h_l = 4 * (gimg / WC) + ((q >> 2) & 3);
+                w = 4 * (gimg % WC) + (q & 3);
+            } else {
+                p.d_seg.divmod(q, n_l, rem);
+                p.d_wo.divmod(rem, h_l, w);
+            }
             off = (n_l * p.iht * rowp + h_l * g.sh * rowp + w * g.sw) * 4;
         }
         xoff[q] = off;
@@ -340,9 +362,14 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
                     read_b(Xw, xo, bq[(t + 1) & 1]);
                 }
                 WGRAD_SCHED_FENCE();
+                // column-uniform order: this step's four positions lie on column 4 * (gi % WC) + st of their rows
+                const bool first_col = WC && st == 0 && gi % (WC ? WC : 1) == 0;
+                const bool last_col = WC && st == 3 && gi % (WC ? WC : 1) == (WC ? WC : 1) - 1;
 #pragma unroll
-                for (int j = 0; j < NT; ++j)
+                for (int j = 0; j < NT; ++j) {
+                    if ((first_col && j % 3 == 0) || (last_col && j % 3 == 2)) continue;      // taps on the zero halo
                     acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[st], bq[t & 1][j], acc[j], 0, 0, 0);
+                }
                 WGRAD_SCHED_FENCE();
                 WGRAD_STEP_PATTERN(NT);
                 if (st == 3 && gi + 1 < GPW) {
@@ -398,18 +425,18 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
     TRACE_BLK(1);
 }
 
-template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP>
+template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP, int WC = 0>
 __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams p)
 {
     extern __shared__ float smem[];
-    stream_body<NT, WK, BF16, XV, GPW, ROWP>(p, smem, blockIdx.x, gridDim.x);
+    stream_body<NT, WK, BF16, XV, GPW, ROWP, WC>(p, smem, blockIdx.x, gridDim.x);
 }
 
 // A prepared launch of the streaming kernel, and a queue of them for a multi-shape launch.
 constexpr int kMultiMax = 6;        // groups per multi-shape launch (their parameters are kernel arguments)
 struct StreamLaunch {
     StreamParams p;
-    int nt, wk, xv, gpw, rowp_inst, grid;
+    int nt, wk, xv, gpw, rowp_inst, wc, grid;
     int plane2;                 // the 2x2-plane matrix-product form (exact_plane2_kernel.hpp): only the tensors, g and per_prob of p are set
     size_t lds;
 };
@@ -417,7 +444,7 @@ struct MultiQueue {
     int n = 0;
     StreamLaunch item[kMultiMax];
 };
-int multi_variant(int nt, int wk, int xv, int gpw, int rowp);     // -1: not among the shapes a multi launch mixes
+int multi_variant(int nt, int wk, int xv, int gpw, int rowp, int wc);     // -1: not among the shapes a multi launch mixes
 int launch_stream_now(const StreamLaunch &L, hipStream_t st);
 void launch_plane2_kernel(const StreamLaunch &L, hipStream_t st);
 int multi_flush(MultiQueue &q, hipStream_t st);
@@ -426,6 +453,13 @@ int multi_flush(MultiQueue &q, hipStream_t st);
 void stream_launch_w1(const StreamParams &p, int nt, int xv, int gpw, int rowp, int grid, size_t lds, hipStream_t st);
 void stream_launch_w2(const StreamParams &p, int nt, int xv, int gpw, int rowp, int grid, size_t lds, hipStream_t st);
 void stream_launch_w4(const StreamParams &p, int nt, int xv, int gpw, int rowp, int grid, size_t lds, hipStream_t st);
+
+// The column-uniform instantiations (WC blocks of four columns per output row).
+template <int WK, int GPW, int ROWP, int WC>
+static void stream_inst_wc(const StreamParams &p, int grid, size_t lds, hipStream_t st)
+{
+    WGRAD_LAUNCH((wgrad_exact_stream<9, WK, false, 4, GPW, ROWP, WC>), dim3(grid), dim3(kBlock), lds, st, p);
+}
 
 template <int NT, int WK, bool BF16, int XV, int ROWP>
 static void stream_inst(const StreamParams &p, int gpw, int grid, size_t lds, hipStream_t st)
@@ -451,6 +485,15 @@ template <int WK, bool BF16>
 static void stream_pick(const StreamParams &p, int nt, int xv, int gpw, int rowp, int grid, size_t lds, hipStream_t st)
 {
     if (nt == 9) {
+        if constexpr (WK == 4 && !BF16) {
+            if (p.wc == 1 && rowp == 12 && xv == 4 && gpw == 4) { stream_inst_wc<4, 4, 12, 1>(p, grid, lds, st); return; }
+            if (p.wc == 2 && rowp == 12 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 12, 2>(p, grid, lds, st); return; }
+            if (p.wc == 4 && rowp == 20 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 20, 4>(p, grid, lds, st); return; }
+            if (p.wc == 8 && rowp == 36 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 36, 8>(p, grid, lds, st); return; }
+        }
+        if constexpr (WK == 2 && !BF16) {
+            if (p.wc == 4 && rowp == 20 && xv == 4 && gpw == 8) { stream_inst_wc<2, 8, 20, 4>(p, grid, lds, st); return; }
+        }
         if (rowp == 4 && xv == 2) stream_inst<9, WK, BF16, 2, 4>(p, gpw, grid, lds, st);
         else if (rowp == 12 && xv == 4) stream_inst<9, WK, BF16, 4, 12>(p, gpw, grid, lds, st);
         else if (rowp == 20 && xv == 4) stream_inst<9, WK, BF16, 4, 20>(p, gpw, grid, lds, st);
