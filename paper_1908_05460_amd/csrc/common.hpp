@@ -89,6 +89,7 @@ struct ExactPlan {
     int xv;                          // elements per staging access (4, 2; 0 = element-wise staging)
     int stream, gpw, xbuf, rowp;           // streaming form: A operand from global memory, window double-buffered
     int wc;                          // streaming form: column-uniform position order with this many 4-column blocks per output row (0: row-major order)
+    int img4;                        // streaming form, 4x4 planes: image-uniform position order (a step contracts one position of four images)
     int mm16;                        // bf16 matrix-core form of the streaming kernel
     int direct;                      // general form: no tile of whole output rows fits the LDS
     int plane2;                      // 2x2 planes, fp32: the plain matrix product over (position, element) pairs

@@ -22,17 +22,17 @@ struct MultiParams {
 // The instantiations a multi-shape launch can mix: 3x3 layers of CIFAR-sized networks (maps of 32, 16, 8, 4,
 // 2 and the first layer's three input channels).  (NT, WK, XV, GPW, ROWP)
 #define WGRAD_MULTI_VARIANTS(X) \
-    X(0, 2, 1, 4, 8, 0, 0)  X(1, 9, 1, 4, 4, 36, 0) X(2, 9, 2, 4, 2, 36, 0) X(3, 9, 2, 4, 8, 20, 0)  \
-    X(4, 9, 4, 4, 4, 20, 0) X(5, 9, 4, 4, 8, 12, 0) X(6, 2, 4, 4, 8, 0, 0)  X(7, 9, 4, 4, 8, 36, 0)  \
-    X(8, 9, 4, 4, 8, 20, 0) X(9, 9, 4, 4, 4, 12, 0) X(10, 9, 4, 2, 4, 4, 0) X(12, 9, 4, 4, 4, 12, 1) \
-    X(13, 9, 4, 4, 8, 12, 2) X(14, 9, 4, 4, 8, 20, 4) X(15, 9, 4, 4, 8, 36, 8) \
-    X(16, 9, 2, 4, 8, 20, 4)
+    X(0, 2, 1, 4, 8, 0, 0, false)  X(1, 9, 1, 4, 4, 36, 0, false) X(2, 9, 2, 4, 2, 36, 0, false) X(3, 9, 2, 4, 8, 20, 0, false)  \
+    X(4, 9, 4, 4, 4, 20, 0, false) X(5, 9, 4, 4, 8, 12, 0, false) X(6, 2, 4, 4, 8, 0, 0, false)  X(7, 9, 4, 4, 8, 36, 0, false)  \
+    X(8, 9, 4, 4, 8, 20, 0, false) X(9, 9, 4, 4, 4, 12, 0, false) X(10, 9, 4, 2, 4, 4, 0, false) X(12, 9, 4, 4, 4, 12, 1, false) \
+    X(13, 9, 4, 4, 8, 12, 2, false) X(14, 9, 4, 4, 8, 20, 4, false) X(15, 9, 4, 4, 8, 36, 8, false) \
+    X(16, 9, 2, 4, 8, 20, 4, false) X(17, 9, 4, 4, 8, 6, 1, true)
 
 constexpr int kMultiPlane2 = 11;    // the 2x2-plane matrix-product form rides along as one more variant
 
-int multi_variant(int nt, int wk, int xv, int gpw, int rowp, int wc)
+int multi_variant(int nt, int wk, int xv, int gpw, int rowp, int wc, int img4)
 {
-#define X(ID, NT, WK, XV, GPW, ROWP, WC) if (nt == NT && wk == WK && xv == XV && gpw == GPW && rowp == ROWP && wc == WC) return ID;
+#define X(ID, NT, WK, XV, GPW, ROWP, WC, IMG4) if (nt == NT && wk == WK && xv == XV && gpw == GPW && rowp == ROWP && wc == WC && (img4 != 0) == IMG4) return ID;
     WGRAD_MULTI_VARIANTS(X)
 #undef X
     return -1;
@@ -51,7 +51,7 @@ __global__ __launch_bounds__(kBlock, 3) void wgrad_exact_multi(const MultiParams
     if (bid >= nblk) return;
     const StreamParams &p = mp->p[gi];      // still kernel-argument memory at a uniform address: scalar loads
     switch (mp->variant[gi]) {
-#define X(ID, NT, WK, XV, GPW, ROWP, WC) case ID: stream_body<NT, WK, false, XV, GPW, ROWP, WC>(p, smem, bid, nblk); break;
+#define X(ID, NT, WK, XV, GPW, ROWP, WC, IMG4) case ID: stream_body<NT, WK, false, XV, GPW, ROWP, WC, IMG4>(p, smem, bid, nblk); break;
         WGRAD_MULTI_VARIANTS(X)
 #undef X
         case kMultiPlane2: plane2_body(p, bid); break;
@@ -77,7 +77,7 @@ int multi_flush(MultiQueue &q, hipStream_t st)
         const StreamLaunch &L = q.item[i];
         mp.begin[i] = blocks;
         mp.count[i] = L.grid;
-        mp.variant[i] = L.plane2 ? kMultiPlane2 : multi_variant(L.nt, L.wk, L.xv, L.gpw, L.rowp_inst, L.wc);
+        mp.variant[i] = L.plane2 ? kMultiPlane2 : multi_variant(L.nt, L.wk, L.xv, L.gpw, L.rowp_inst, L.wc, L.img4);
         mp.p[i] = L.p;
         blocks += (L.grid + 7) / 8 * 8;
         if (L.lds > lds) lds = L.lds;

@@ -45,7 +45,17 @@ bool plan_exact_stream(const Geometry &g, ExactPlan &pl)
             const int fixed = iwt <= 4 ? 4 : (iwt <= 12 ? 12 : (iwt <= 20 ? 20 : (iwt <= 36 ? 36 : 0)));
             if (fixed && stream_has_rowp(fixed, xv)) rowp = fixed;
         }
-        const int pp = stream_pitch(nti * iht * rowp);
+        // 4x4 planes, tiles of eight whole images: image-uniform order.  The lane groups of an operand read then address
+        // different images and the same row, so the rows are packed (pitch 6: the window of eight images fits next to
+        // two other workgroups' only so) and the images' windows are placed 4 (mod 8) floats apart, which spreads the
+        // 64 lanes over all banks
+        const bool img4 = tune_int("WGRAD_STREAM_IMG4", 1) && !g.bf16 && pl.tap_mode && pl.nt == 9 && pl.wk == 4 && xv == 4
+                          && gpw == 8 && g.R == 3 && g.S == 3 && g.sh == 1 && g.sw == 1 && g.ph == 1 && g.pw == 1
+                          && g.Ho == 4 && g.Wo == 4 && nti == 8 && ht == 4;
+        if (img4) rowp = 6;
+        int ipitch = iht * rowp;
+        if (img4) while (ipitch % 8 != 4) ++ipitch;
+        const int pp = stream_pitch(nti * ipitch);
         const int xbuf = (pl.ctch + 3) / 4 * (4 * pp + 4);        // quads of channels, see stream_chan_off
         size_t lds = ((size_t)2 * xbuf + qt) * 4;
         const size_t red = (size_t)WQ * (pl.nt * 16) * (16 * pl.wk + 4) * 4;    // epilogue exchange buffer [WQ][NT*16][KT + 4]
@@ -56,13 +66,14 @@ bool plan_exact_stream(const Geometry &g, ExactPlan &pl)
         if (lds > lds_cap || x_slots > (long)stream_xslots(pl.wk, gpw) * kBlock || iht > 255 || (long)xbuf >= (1 << 20)) continue;
         if ((long)nti * g.K * L * 4 >= (1l << 31) || (long)nti * g.C * g.H * g.W * 4 >= (1l << 31)) continue;
         pl.stream = 1; pl.gpw = gpw; pl.xv = xv;
+        pl.img4 = img4;
         // column-uniform position order (the taps that meet only the zero halo are left out): 3x3, stride 1,
         // padding 1, rows of four or eight positions, K tiles of 64, whole blocks of four rows
         pl.wc = 0;
         if (tune_int("WGRAD_STREAM_WC", 1) && !g.bf16 && pl.tap_mode && pl.nt == 9 && xv == 4
             && (pl.wk == 4 || (pl.wk == 2 && g.Wo == 16 && tune_int("WGRAD_STREAM_WC_K32", 1)))
             && g.R == 3 && g.S == 3 && g.sh == 1 && g.sw == 1 && g.ph == 1 && g.pw == 1
-            && ((g.Wo == 4 && gpw == 4 && rowp == 12) || (g.Wo == 8 && gpw == 8 && rowp == 12)
+            && ((g.Wo == 4 && gpw == 4 && rowp == 12) || img4 || (g.Wo == 8 && gpw == 8 && rowp == 12)
                 || (tune_int("WGRAD_STREAM_WC_WIDE", 1) && ((g.Wo == 16 && gpw == 8 && rowp == 20) || (g.Wo == 32 && gpw == 8 && rowp == 36))))
             && ht % 4 == 0 && q % 16 == 0)
             pl.wc = g.Wo / 4;
@@ -103,6 +114,9 @@ int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, 
     p.xbuf = pl.xbuf;
     p.rowp = pl.rowp;
     p.wc = pl.wc;
+    p.img4 = pl.img4;
+    p.ipitch = pl.iht * pl.rowp;
+    if (pl.img4) while (p.ipitch % 8 != 4) ++p.ipitch;
     p.d_gpi = FastDiv(pl.wc ? (pl.ht / 4) * pl.wc : 1);
     p.d_wv = FastDiv(g.W / pl.xv);
     p.d_rows = FastDiv(pl.nti * pl.iht);
@@ -123,9 +137,10 @@ int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, 
     L.rowp_inst = stream_has_rowp(pl.rowp, pl.xv) && pl.nt == 9 && pl.tap_mode ? pl.rowp : 0;
     L.nt = pl.nt; L.wk = pl.wk; L.xv = pl.xv; L.gpw = pl.gpw; L.lds = pl.lds_bytes;
     L.wc = L.rowp_inst ? pl.wc : 0;
+    L.img4 = L.wc == 1 ? pl.img4 : 0;
     p.wc = L.wc;
     // up to three workgroups per CU must fit next to each other for a mixed launch to pay
-    if (mq && !g.bf16 && L.lds <= 52 * 1024 && multi_variant(L.nt, L.wk, L.xv, L.gpw, L.rowp_inst, L.wc) >= 0) {
+    if (mq && !g.bf16 && L.lds <= 52 * 1024 && multi_variant(L.nt, L.wk, L.xv, L.gpw, L.rowp_inst, L.wc, L.img4) >= 0) {
         if (mq->n == kMultiMax) {
             const int rc = multi_flush(*mq, st);
             if (rc != WGRAD_OK) return rc;

@@ -59,6 +59,8 @@ struct StreamParams {
     int xbuf;                   // floats per LDS window buffer (multiple of 4)
     int rowp;                   // LDS pitch of a window row (>= iwt)
     int wc;                     // column-uniform position order: 4-column blocks per output row (0: row-major order)
+    int img4;                   // image-uniform position order on 4x4 planes (tiles of four whole images)
+    int ipitch;                 // floats between the windows of consecutive images of a tile (iht * rowp, or more)
     FastDiv d_wv, d_rows, d_iht, d_rs, d_s, d_seg, d_wo, d_htiles;
     FastDiv d_gpi;              // column-uniform order: groups of 16 positions per image of a tile, (ht / 4) * wc
     int tile_c0[9], tile_toff[9], tile_tap[9];
@@ -113,12 +115,18 @@ __device__ __forceinline__ void stream_column_of(const StreamParams &p, int colt
 // first (last) column of a row then multiplies the taps of filter column 0 (2) with the zero halo only: those
 // three MFMAs and their LDS reads are left out, statically (the step's column block is gi % WC).  That is 1/6 of
 // the matrix work on 4x4 planes, 1/12 on 8x8.  WC = 0: row-major order, every tap multiplied.
+// IMG4 (4x4 planes, tiles of eight images, eight groups per wavefront): image-uniform order -- group gi is output
+// row gi % 4 of the four images 4 * (gi / 4) .. + 3, lane group kk holding image kk's row -- so the four positions
+// of a step are ONE position (gi % 4, st) of four images and every tap that falls outside X for that position, by
+// row or by column, is left out: 100 of a plane's 144 (position, tap) pairs remain, exactly the products that do
+// not multiply padding.
 // The body takes the workgroup's number `bid` among the `nblk` workgroups of its launch (or of its
 // share of a launch that carries several shapes) and the dynamic LDS.
-template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP, int WC = 0>
+template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP, int WC = 0, bool IMG4 = false>
 __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, int bid, int nblk)
 {
     static_assert(ROWP == 0 || NT == 9, "immediate tap offsets are for 3x3 filters in tap mode");
+    static_assert(!IMG4 || (WC == 1 && GPW % 4 == 0 && WK == 4), "the image-uniform order is for 4x4 planes: four images = four groups, one per output row");
     static_assert(WC == 0 || (ROWP != 0 && GPW % WC == 0), "the column-uniform order needs immediate taps and whole rows of blocks per wavefront");
     const int rowp = ROWP ? ROWP : p.rowp;
     constexpr int KT = 16 * WK, WQ = 4 / WK;
@@ -168,7 +176,10 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
         a_off[gi] = 0;
         if (q < p.q && k_row < g.K) {
             uint32_t n_l, rem;
-            if (WC) {                       // group -> (image, block of four rows, block of four columns); kk = row in the block
+            if (IMG4) {                     // group = (four images, output row), lane group = image
+                n_l = 4 * ((wq * GPW + gi) >> 2) + kk;
+                rem = 4 * ((wq * GPW + gi) & 3);
+            } else if (WC) {                // group -> (image, block of four rows, block of four columns); kk = row in the block
                 uint32_t gimg;
                 p.d_gpi.divmod((uint32_t)(wq * GPW + gi), n_l, gimg);
                 rem = (4 * (gimg / WC) + kk) * g.Wo + 4 * (gimg % WC);
@@ -198,7 +209,7 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
                 int nv = p.iwt - col0;                       // columns right of the window are not staged
                 nv = nv > XV ? XV : nv;
                 if (c_first + (int)c_l < g.C && nv > 0) {
-                    x_pack[u] = (int)(stream_chan_off(c_l, p.pp) + rem * rowp + col0) | (int)(ih_l << 20) | (nv << 28);
+                    x_pack[u] = (int)(stream_chan_off(c_l, p.pp) + n_l * p.ipitch + ih_l * rowp + col0) | (int)(ih_l << 20) | (nv << 28);
                     x_src[u] = ((n_l * g.C + c_l) * (g.H * g.W) + jv * XV) * ESZ;
                 }
             }
@@ -283,7 +294,9 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
         int off = 0;
         if (q < p.q) {
             uint32_t n_l, rem, h_l, w;
-            if (WC) {
+            if (IMG4) {
+                n_l = 4 * (q >> 6) + ((q >> 2) & 3); h_l = (q >> 4) & 3; w = q & 3;
+            } else if (WC) {
                 uint32_t gimg;
                 p.d_gpi.divmod((uint32_t)q >> 4, n_l, gimg);
                 h_l = 4 * (gimg / WC) + ((q >> 2) & 3);
@@ -292,7 +305,7 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
                 p.d_seg.divmod(q, n_l, rem);
                 p.d_wo.divmod(rem, h_l, w);
             }
-            off = (n_l * p.iht * rowp + h_l * g.sh * rowp + w * g.sw) * 4;
+            off = (n_l * p.ipitch + h_l * g.sh * rowp + w * g.sw) * 4;
         }
         xoff[q] = off;
     }
@@ -365,9 +378,12 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
                 // column-uniform order: this step's four positions lie on column 4 * (gi % WC) + st of their rows
                 const bool first_col = WC && st == 0 && gi % (WC ? WC : 1) == 0;
                 const bool last_col = WC && st == 3 && gi % (WC ? WC : 1) == (WC ? WC : 1) - 1;
+                // image-uniform order: the step is output row gi of its four images
+                const bool first_row = IMG4 && gi % 4 == 0, last_row = IMG4 && gi % 4 == 3;
 #pragma unroll
                 for (int j = 0; j < NT; ++j) {
                     if ((first_col && j % 3 == 0) || (last_col && j % 3 == 2)) continue;      // taps on the zero halo
+                    if ((first_row && j / 3 == 0) || (last_row && j / 3 == 2)) continue;
                     acc[j] = __builtin_amdgcn_mfma_f32_16x16x4f32(a_cur[st], bq[t & 1][j], acc[j], 0, 0, 0);
                 }
                 WGRAD_SCHED_FENCE();
@@ -425,18 +441,18 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
     TRACE_BLK(1);
 }
 
-template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP, int WC = 0>
+template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP, int WC = 0, bool IMG4 = false>
 __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams p)
 {
     extern __shared__ float smem[];
-    stream_body<NT, WK, BF16, XV, GPW, ROWP, WC>(p, smem, blockIdx.x, gridDim.x);
+    stream_body<NT, WK, BF16, XV, GPW, ROWP, WC, IMG4>(p, smem, blockIdx.x, gridDim.x);
 }
 
 // A prepared launch of the streaming kernel, and a queue of them for a multi-shape launch.
 constexpr int kMultiMax = 6;        // groups per multi-shape launch (their parameters are kernel arguments)
 struct StreamLaunch {
     StreamParams p;
-    int nt, wk, xv, gpw, rowp_inst, wc, grid;
+    int nt, wk, xv, gpw, rowp_inst, wc, img4, grid;
     int plane2;                 // the 2x2-plane matrix-product form (exact_plane2_kernel.hpp): only the tensors, g and per_prob of p are set
     size_t lds;
 };
@@ -444,7 +460,7 @@ struct MultiQueue {
     int n = 0;
     StreamLaunch item[kMultiMax];
 };
-int multi_variant(int nt, int wk, int xv, int gpw, int rowp, int wc);     // -1: not among the shapes a multi launch mixes
+int multi_variant(int nt, int wk, int xv, int gpw, int rowp, int wc, int img4);     // -1: not among the shapes a multi launch mixes
 int launch_stream_now(const StreamLaunch &L, hipStream_t st);
 void launch_plane2_kernel(const StreamLaunch &L, hipStream_t st);
 int multi_flush(MultiQueue &q, hipStream_t st);
@@ -455,10 +471,10 @@ void stream_launch_w2(const StreamParams &p, int nt, int xv, int gpw, int rowp, 
 void stream_launch_w4(const StreamParams &p, int nt, int xv, int gpw, int rowp, int grid, size_t lds, hipStream_t st);
 
 // The column-uniform instantiations (WC blocks of four columns per output row).
-template <int WK, int GPW, int ROWP, int WC>
+template <int WK, int GPW, int ROWP, int WC, bool IMG4 = false>
 static void stream_inst_wc(const StreamParams &p, int grid, size_t lds, hipStream_t st)
 {
-    WGRAD_LAUNCH((wgrad_exact_stream<9, WK, false, 4, GPW, ROWP, WC>), dim3(grid), dim3(kBlock), lds, st, p);
+    WGRAD_LAUNCH((wgrad_exact_stream<9, WK, false, 4, GPW, ROWP, WC, IMG4>), dim3(grid), dim3(kBlock), lds, st, p);
 }
 
 template <int NT, int WK, bool BF16, int XV, int ROWP>
@@ -486,6 +502,7 @@ static void stream_pick(const StreamParams &p, int nt, int xv, int gpw, int rowp
 {
     if (nt == 9) {
         if constexpr (WK == 4 && !BF16) {
+            if (p.wc == 1 && p.img4 && rowp == 6 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 6, 1, true>(p, grid, lds, st); return; }
             if (p.wc == 1 && rowp == 12 && xv == 4 && gpw == 4) { stream_inst_wc<4, 4, 12, 1>(p, grid, lds, st); return; }
             if (p.wc == 2 && rowp == 12 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 12, 2>(p, grid, lds, st); return; }
             if (p.wc == 4 && rowp == 20 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 20, 4>(p, grid, lds, st); return; }
@@ -510,6 +527,6 @@ static void stream_pick(const StreamParams &p, int nt, int xv, int gpw, int rowp
 }
 
 // pairs (rowp, xv) that have an immediate-offset instantiation
-inline bool stream_has_rowp(int rowp, int xv) { return (rowp == 4 && xv == 2) || ((rowp == 12 || rowp == 20 || rowp == 36) && xv == 4); }
+inline bool stream_has_rowp(int rowp, int xv) { return (rowp == 4 && xv == 2) || ((rowp == 6 || rowp == 12 || rowp == 20 || rowp == 36) && xv == 4); }
 
 }  // namespace wgrad
