@@ -309,6 +309,10 @@ def run_workload(args, name, machine, steps, warmup, headline):
                 "peak_measured": mfma_measured,
                 "frac_of_measured": round(achieved_tf / mfma_measured, 4) if mfma_measured else None,
                 "achieved_valid_taps": round(tot["valid_flops"] / phase_ms["exact"] / 1e9, 3),
+                "frac_valid_taps": round(tot["valid_flops"] / phase_ms["exact"] / 1e9 / MFMA_PEAK_TFLOPS[dtype], 4),
+                "note": "achieved counts nominal FLOPs (padding taps included, the usual convention); the fp32 kernels leave out "
+                        "matrix instructions whose taps meet only padding, so the matrix core's own rate is bounded by "
+                        "achieved_valid_taps (products that do not multiply padding) from below and achieved from above",
                 "achieved_best": round(tot["flops"] / phase_min["exact"] / 1e9, 3),
                 "algorithmic_flops": tot["flops"], "valid_tap_flops": tot["valid_flops"],
                 "algorithmic_min_bytes": sum(exact_min_bytes(l, N, e) for l in stack),
