@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libwgrad.so")
 ROOFS_LIB = os.path.join(HERE, "libwgrad_roofs.so")   # bench-only kernels that measure the machine's ceilings
 SOURCES = ["api.hip", "exact_mfma.hip", "exact_stream.hip", "exact_stream_w1.hip", "exact_stream_w2.hip",
-           "exact_stream_w4.hip", "exact_multi.hip", "exact_bf16.hip", "exact_direct.hip", "exact_plane2.hip", "approx.hip", "approx_topk.hip", "combine.hip",
+           "exact_stream_w4.hip", "exact_multi.hip", "exact_bf16.hip", "exact_bf16_planes.hip", "exact_direct.hip", "exact_plane2.hip", "approx.hip", "approx_topk.hip", "combine.hip",
            "fill.hip", "layouts.hip"]
 # packed fp32 VALU forms are switched off on purpose (they have misbehaved on the test machines)
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

@@ -1781,6 +1781,19 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
         if (rc != WGRAD_OK) return rc;
         return launch_exact(g, pl.ex, eb, (char *)ws + (size_t)b.n * pl.off_part, st, defer);
     }
+    bool aligned16 = true;
+    for (int i = 0; i < b.n; ++i) aligned16 = aligned16 && ((uintptr_t)b.X[i] % 16) == 0;
+    if (pl.mm && planes_bf16_takes(g) && aligned16 && (!bq || tune_int("WGRAD_BF16_PLANES_APPROX_SHARED", 0))) {
+        // 2x2 and 4x4 planes, single calls: the position-major kernel, its A operand built from the selections; it
+        // writes dW itself.  (In a schedule run the selections and the sparse-operand launches of all layers share
+        // two launches, which measured faster than this kernel with a selection and a launch per group.)
+        rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st, nullptr);
+        if (rc != WGRAD_OK) return rc;
+        SparseA sp{};
+        for (int i = 0; i < b.n; ++i) { sp.hw[i] = ab.hw[i]; sp.sum[i] = ab.sum[i]; }
+        sp.scale = scale;
+        return launch_exact_bf16_planes(g, b, st, &sp);
+    }
     if (pl.mm) {
         rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st, bq ? sq : nullptr);   // (a queued consumer issues queued selections first)
         if (rc != WGRAD_OK) return rc;

@@ -124,6 +124,9 @@ void bf16_queue_delete(Bf16Queue *q);
 int bf16_flush(Bf16Queue &q, hipStream_t st);
 int launch_exact_bf16(const Geometry &g, const ExactPlan &pl, const Batch &b, float *const *out, hipStream_t st,
                       const SparseA *sparse = nullptr, Bf16Queue *queue = nullptr);
+// bf16 inputs on 2x2 and 4x4 planes: the position-major matrix-core kernel (no split, writes dW itself)
+bool planes_bf16_takes(const Geometry &g);
+int launch_exact_bf16_planes(const Geometry &g, const Batch &b, hipStream_t st, const SparseA *sparse = nullptr);
 struct CombineQueue;
 int launch_exact(const Geometry &g, const ExactPlan &pl, const Batch &b, void *ws, hipStream_t st,
                  CombineQueue *defer = nullptr, MultiQueue *mq = nullptr, int mq_blocks = 0, Bf16Queue *bq = nullptr);
