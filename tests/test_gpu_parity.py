@@ -76,6 +76,38 @@ def test_approx_matches_oracle(t, dtype):
     assert normwise_err(got, want) <= TOL[dtype]
 
 
+# 3x3, stride 1, padding 1 on planes of 4, 8, 16 and 32 columns with 32 or 64 output channels: the position orders of
+# the streaming kernel that leave out the taps which meet only padding (column-uniform; image-uniform on 4x4 planes
+# in tiles of eight images), and their neighbours that fall back to the row-major order (batches the tiles do not divide)
+SKIP_ORDERS = [
+    (16, 32, 4, 4, 64), (8, 16, 4, 4, 128), (12, 16, 4, 4, 64), (6, 16, 4, 4, 64), (5, 16, 4, 4, 64),
+    (8, 16, 8, 8, 64), (6, 32, 8, 8, 128), (3, 16, 8, 8, 64),
+    (4, 16, 16, 16, 64), (3, 16, 16, 16, 32), (2, 32, 16, 16, 128),
+    (2, 16, 32, 32, 64), (3, 16, 32, 32, 64),
+]
+
+
+@pytest.mark.parametrize("t", SKIP_ORDERS)
+def test_exact_orders_that_leave_out_padding_taps(t):
+    N, C, H, W, K = t
+    d = B.desc(N, C, H, W, K, R=3, S=3, pad=1)
+    X, dY = rand_inputs(d, 5150 + N + H)
+    g = oracle_shape(d)
+    want = oracle.wgrad_exact(g, X, dY)
+    assert normwise_err(B.conv_wgrad_exact(d, to_gpu(X), to_gpu(dY)).cpu().numpy(), want) <= TOL["fp32"]
+    # the same layer beside one of another shape in a schedule run (the multi-shape launch's instantiations)
+    import torch
+    d2 = B.desc(8, 16, 8, 8, 64, R=3, S=3, pad=1)
+    X2, dY2 = rand_inputs(d2, 6160 + N + H)
+    dWs = [torch.empty((K, C, 3, 3), device="cuda"), torch.empty((64, 16, 3, 3), device="cuda")]
+    S = B.Schedule([d, d2], [to_gpu(X), to_gpu(X2)], [to_gpu(dY), to_gpu(dY2)], dWs)
+    mask = np.full(2, B.EXACT, np.uint8)
+    S.run(mask, B.alloc_workspace(S.workspace_bytes(mask)))
+    torch.cuda.synchronize()
+    assert normwise_err(dWs[0].cpu().numpy(), want) <= TOL["fp32"]
+    assert normwise_err(dWs[1].cpu().numpy(), oracle.wgrad_exact(oracle_shape(d2), X2, dY2)) <= TOL["fp32"]
+
+
 def test_strided_input_whose_planes_exceed_the_fused_offset_field():
     """70 channels of 512x512 under stride 16: maps of 1024 positions and 70 entries per output channel, the
     shape class of the fused form, but tap offsets inside one image need more than 24 bits."""
