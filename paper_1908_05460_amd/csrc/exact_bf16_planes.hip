@@ -15,8 +15,8 @@
 // pieces of a row XOR-swizzled with bits of the channel so that the 16 rows of an operand read spread over all banks.
 // A workgroup owns 32 output channels x 64 (2x2) or 32 (4x4) input channels and walks the whole batch; its four
 // wavefronts are 2 x 2 tiles of 16 output channels x 32 or 16 input channels.  No split of the reduction, no partial
-// sums.  LDS is double-buffered and so are the staging registers: while stage t is multiplied, stage t + 1 is
-// transposed into the other buffer between the matrix instructions and the loads of stage t + 2 are in flight.
+// sums.  LDS is double-buffered and so are the staging registers: while four wavefronts multiply stage t, four others
+// transpose stage t + 1 into the other buffer and have the loads of stage t + 2 in flight.
 // What bounds it: the operands are read out of LDS twice (two wavefronts share each 16-row tile), about one LDS
 // byte-cycle per matrix cycle, and every operand row is fetched once per tile column (row) of the result, K / 32 or
 // C / 32 times, out of the L2 -- 512 -> 512 @ 4x4, N = 512: 37 us against 60 for the row-window kernel, 12 at the
@@ -41,6 +41,7 @@ struct PlanesParams {
     float scale;                        // applied to what is written
     int per_prob;                       // workgroups per problem
     int N, K, C;
+    int bk, bc;                         // tiles of one XCD's block per problem (rows x columns); 0: tiles in plain order
 };
 
 constexpr int kPlanesKT = 32;                                   // output channels per workgroup
@@ -57,13 +58,32 @@ __device__ __forceinline__ void planes_body(const PlanesParams &p, char *smem, i
     constexpr int PCH = P / PV;                   // staging tasks per plane
     constexpr int LW = PV / 2;                    // 32-bit words per load
     typedef uint32_t word;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    // eight wavefronts: four multiply (2 x 2 tiles of the workgroup's result), four stage (loads, transposition,
+    // LDS writes); a SIMD holds one of each, so the staging runs under the matrix instructions of the other
+    // (a lone wavefront per SIMD overlapped nothing: its stage time was the sum of the parts)
+    const int tid = threadIdx.x & (kBlock - 1), lane = tid & 63, wave = tid >> 6;      // tid: number among the staging (or the multiplying) threads
+    const bool producer = __builtin_amdgcn_readfirstlane((int)threadIdx.x >> 8) != 0;
     const int i16 = lane & 15, kk = lane >> 4;
     const int wk = wave & 1, wc = wave >> 1;
 
-    const int prob = bid / p.per_prob, tile = bid - prob * p.per_prob;
+    // Workgroups go to the XCDs round robin.  Every operand row is fetched once per tile column (row) of the result
+    // that needs it, out of the XCD's own L2: an XCD therefore takes a block of bk x bc tiles of every problem -- as
+    // square as the tile counts allow -- instead of every eighth tile, and fetches bk / (K / 32) of dY and
+    // bc / (C / CT) of X instead of all of one of them.
     const int ctiles = p.C / CT;
-    const int k0 = (tile / ctiles) * KT, c0 = (tile % ctiles) * CT;
+    int prob, kt, ct;
+    if (p.bk) {
+        const int xcd = bid & 7, i = bid >> 3, per_xcd = p.bk * p.bc, bcols = ctiles / p.bc;
+        prob = i / per_xcd;
+        const int tl = i - prob * per_xcd;
+        kt = (xcd / bcols) * p.bk + tl / p.bc;
+        ct = (xcd % bcols) * p.bc + tl % p.bc;
+    } else {
+        prob = bid / p.per_prob;
+        const int tile = bid - prob * p.per_prob;
+        kt = tile / ctiles; ct = tile % ctiles;
+    }
+    const int k0 = kt * KT, c0 = ct * CT;
     const char *const Xp = (const char *)p.X[prob];
     const char *const dYp = (const char *)p.dY[prob];
 
@@ -154,37 +174,55 @@ __device__ __forceinline__ void planes_body(const PlanesParams &p, char *smem, i
     const uint32_t swz = 16u * (uint32_t)(kk ^ ((i16 >> 1) & 3));
     const uint32_t a_rd = (uint32_t)((wk * 16 + i16) * 64) + swz;                                  // + position * KT * 64
     const uint32_t b_rd = (uint32_t)P * KT * 64 + (uint32_t)((wc * (CT / 2) + i16) * 64) + swz;    // + position * CT * 64 + column tile * 16 * 64
-    float4_t acc[NTC][9];
-#pragma unroll
-    for (int nt = 0; nt < NTC; ++nt)
-#pragma unroll
-        for (int t = 0; t < 9; ++t) acc[nt][t] = float4_t{0.f, 0.f, 0.f, 0.f};
-
     constexpr size_t BUF = planes_lds_bytes(HW) / 2;
     constexpr int UNITS = 2 * PV;                  // transposition units per thread and stage
     static_assert(UNITS % P == 0, "the units of a stage are spread evenly over the positions");
     const int stages = p.N / 32;
     typedef std::integral_constant<int, 0> set0;
     typedef std::integral_constant<int, 1> set1;
-    // Stage s: multiply it out of buffer s % 2 while the pieces of stage s + 1 (register set (s + 1) % 2, requested
-    // a stage ago) are transposed into the other buffer, a unit or two between the matrix instructions of each
-    // position, and the pieces of stage s + 2 are requested into the set that stage s came from.  Past the end the
-    // last stage is requested and transposed again (never read): the loop body is free of branches.
-    auto run_stage = [&](auto par_c, int s) {
-        constexpr int PAR = decltype(par_c)::value;
-        typedef std::integral_constant<int, PAR> this_set;
-        typedef std::integral_constant<int, PAR ^ 1> next_set;
-        const char *cur = smem + PAR * BUF;
-        char *nxt = smem + (PAR ^ 1) * BUF;
-        const int s2 = s + 2 < stages ? s + 2 : stages - 1;
-        load_stage(this_set{}, 32 * s2);
+    // Stage s is multiplied out of buffer s % 2 while the pieces of stage s + 1 (register set (s + 1) % 2, requested a
+    // stage ago) are transposed into the other buffer and the pieces of stage s + 2 are requested into the set that
+    // stage s came from; one barrier per stage.  Past the end the last stage is requested and transposed again
+    // (never read): the loops are free of branches.  Both kinds of wavefront pass 1 + stages barriers.
+    if (producer) {
+        auto stage_next = [&](auto par_c, int s) {
+            constexpr int PAR = decltype(par_c)::value;
+            typedef std::integral_constant<int, PAR> this_set;
+            typedef std::integral_constant<int, PAR ^ 1> next_set;
+            char *nxt = smem + (PAR ^ 1) * BUF;
+            const int s2 = s + 2 < stages ? s + 2 : stages - 1;
+            load_stage(this_set{}, 32 * s2);
+#pragma unroll
+            for (int u = 0; u < UNITS; ++u) write_unit(next_set{}, u, nxt);
+            __syncthreads();      // the other buffer is complete; everyone has left this one
+        };
+        load_stage(set0{}, 0);
+#pragma unroll
+        for (int u = 0; u < UNITS; ++u) write_unit(set0{}, u, smem);
+        load_stage(set1{}, stages > 1 ? 32 : 0);
+        __syncthreads();
+        int s = 0;
+        for (; s + 1 < stages; s += 2) {
+            stage_next(set0{}, s);
+            stage_next(set1{}, s + 1);
+        }
+        if (s < stages) stage_next(set0{}, s);
+        return;
+    }
+
+    float4_t acc[NTC][9];
+#pragma unroll
+    for (int nt = 0; nt < NTC; ++nt)
+#pragma unroll
+        for (int t = 0; t < 9; ++t) acc[nt][t] = float4_t{0.f, 0.f, 0.f, 0.f};
+    auto multiply = [&](const char *cur) {
+        // every position's B operand, then the A operands one by one (each requested a position ahead), each
+        // against the taps that stay inside X
         pl_bf16x8 bop[NTC][P];
 #pragma unroll
         for (int nt = 0; nt < NTC; ++nt)
 #pragma unroll
             for (int q = 0; q < P; ++q) bop[nt][q] = *(const pl_bf16x8 *)(cur + b_rd + (size_t)(q * CT + nt * 16) * 64);
-        // the A operand of the next position is requested before this position's matrix instructions, so its
-        // LDS latency (and that of the transposition's writes, which share the counter) hides under them
         pl_bf16x8 aop = *(const pl_bf16x8 *)(cur + a_rd);
 #pragma unroll
         for (int pp = 0; pp < P; ++pp) {
@@ -199,24 +237,12 @@ __device__ __forceinline__ void planes_body(const PlanesParams &p, char *smem, i
                 for (int nt = 0; nt < NTC; ++nt)
                     acc[nt][t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(aop, bop[nt][ih * HW + iw], acc[nt][t], 0, 0, 0);
             }
-#pragma unroll
-            for (int u = pp * (UNITS / P); u < (pp + 1) * (UNITS / P); ++u) write_unit(next_set{}, u, nxt);
             aop = aop_next;
         }
-        __syncthreads();      // the other buffer is complete; everyone has left this one
+        __syncthreads();
     };
-
-    load_stage(set0{}, 0);
-#pragma unroll
-    for (int u = 0; u < UNITS; ++u) write_unit(set0{}, u, smem);
-    load_stage(set1{}, stages > 1 ? 32 : 0);
     __syncthreads();
-    int s = 0;
-    for (; s + 1 < stages; s += 2) {
-        run_stage(set0{}, s);
-        run_stage(set1{}, s + 1);
-    }
-    if (s < stages) run_stage(set0{}, s);
+    for (int s = 0; s < stages; ++s) multiply(smem + (s & 1) * BUF);
 
     // ---- the nine taps of every (k, c) of the tile: a lane holds rows 4 * kk + v, column i16 of each 16 x 16 tile ----
     float *const out = p.out[prob];
@@ -232,7 +258,7 @@ __device__ __forceinline__ void planes_body(const PlanesParams &p, char *smem, i
 }
 
 template <int HW, bool SPARSE>
-__global__ __launch_bounds__(kBlock, HW == 2 ? 2 : 1) void wgrad_exact_bf16_planes(const PlanesParams p)
+__global__ __launch_bounds__(2 * kBlock, 2) void wgrad_exact_bf16_planes(const PlanesParams p)
 {
     extern __shared__ char planes_smem[];
     planes_body<HW, SPARSE>(p, planes_smem, (int)blockIdx.x);
@@ -254,7 +280,7 @@ static int planes_launch(const PlanesParams &p, int grid, hipStream_t st)
     const size_t lds = planes_lds_bytes(HW);
     if (lds > 64 * 1024 && hipFuncSetAttribute((const void *)wgrad_exact_bf16_planes<HW, SPARSE>,
                                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds) != hipSuccess) return WGRAD_LAUNCH_FAILED;
-    WGRAD_LAUNCH((wgrad_exact_bf16_planes<HW, SPARSE>), dim3((unsigned)grid), dim3(kBlock), lds, st, p);
+    WGRAD_LAUNCH((wgrad_exact_bf16_planes<HW, SPARSE>), dim3((unsigned)grid), dim3(2 * kBlock), lds, st, p);
     return launch_status();
 }
 
@@ -271,7 +297,21 @@ int launch_exact_bf16_planes(const Geometry &g, const Batch &b, hipStream_t st, 
     }
     p.scale = sparse ? sparse->scale : 1.0f;
     p.N = g.N; p.K = g.K; p.C = g.C;
-    p.per_prob = (g.K / kPlanesKT) * (g.C / planes_ct(g.H));
+    const int ktn = g.K / kPlanesKT, ctn = g.C / planes_ct(g.H);
+    p.per_prob = ktn * ctn;
+    // the block of tiles that one XCD takes of every problem: bk x bc = a eighth of the tiles, eight blocks tiling the result
+    p.bk = p.bc = 0;
+    if (p.per_prob % 8 == 0 && tune_int("WGRAD_BF16_PLANES_XCD", 1)) {
+        const int per_xcd = p.per_prob / 8;
+        double best = 1e30;
+        for (int bc = 1; bc <= ctn; ++bc) {
+            if (ctn % bc || per_xcd % bc) continue;
+            const int bk = per_xcd / bc;
+            if (bk > ktn || ktn % bk || (ktn / bk) * (ctn / bc) != 8) continue;
+            const double cost = (double)bk / ktn + (double)bc / ctn;
+            if (cost < best) { best = cost; p.bk = bk; p.bc = bc; }
+        }
+    }
     const int grid = p.per_prob * b.n;
     if (g.H == 2) return sparse ? planes_launch<2, true>(p, grid, st) : planes_launch<2, false>(p, grid, st);
     return sparse ? planes_launch<4, true>(p, grid, st) : planes_launch<4, false>(p, grid, st);
