@@ -16,8 +16,12 @@ struct MultiParams {
                                     // group then starts on XCD 0); begin[n] = grid size
     int count[kMultiMax];           // workgroups of the group that do work (the rest of its share exit)
     int variant[kMultiMax];
-    StreamParams p[kMultiMax];
+    int first[kMultiMax];           // the group's first problem in the tensor tables
+    StreamShape s[kMultiMax];
+    const void *X[kMultiTensors], *dY[kMultiTensors];
+    float *out[kMultiTensors];
 };
+static_assert(sizeof(MultiParams) <= 4096, "kernel arguments");
 
 // The instantiations a multi-shape launch can mix: 3x3 layers of CIFAR-sized networks (maps of 32, 16, 8, 4,
 // 2 and the first layer's three input channels).  (NT, WK, XV, GPW, ROWP)
@@ -49,12 +53,15 @@ __global__ __launch_bounds__(kBlock, 3) void wgrad_exact_multi(const MultiParams
     for (int i = 1; i < n; ++i) gi += (int)blockIdx.x >= mp->begin[i];
     const int bid = (int)blockIdx.x - mp->begin[gi], nblk = mp->count[gi];
     if (bid >= nblk) return;
-    const StreamParams &p = mp->p[gi];      // still kernel-argument memory at a uniform address: scalar loads
+    const StreamShape &p = mp->s[gi];       // still kernel-argument memory at a uniform address: scalar loads
+    const int first = mp->first[gi];
+    const void *const *Xt = mp->X + first, *const *dYt = mp->dY + first;
+    float *const *outt = mp->out + first;
     switch (mp->variant[gi]) {
-#define X(ID, NT, WK, XV, GPW, ROWP, WC, IMG4) case ID: stream_body<NT, WK, false, XV, GPW, ROWP, WC, IMG4>(p, smem, bid, nblk); break;
+#define X(ID, NT, WK, XV, GPW, ROWP, WC, IMG4) case ID: stream_body<NT, WK, false, XV, GPW, ROWP, WC, IMG4>(p, Xt, dYt, outt, smem, bid, nblk); break;
         WGRAD_MULTI_VARIANTS(X)
 #undef X
-        case kMultiPlane2: plane2_body(p, bid); break;
+        case kMultiPlane2: plane2_body(p, Xt, dYt, outt, bid); break;
         default: break;
     }
 }
@@ -66,24 +73,26 @@ int multi_flush(MultiQueue &q, hipStream_t st)
     if (q.n == 1) {
         const StreamLaunch &L = q.item[0];
         rc = launch_stream_now(L, st);
-        q.n = 0;
+        q.n = 0; q.tensors = 0;
         return rc;
     }
     MultiParams mp{};
     mp.n = q.n;
     size_t lds = 0;
-    int blocks = 0;
+    int blocks = 0, tensors = 0;
     for (int i = 0; i < q.n; ++i) {
         const StreamLaunch &L = q.item[i];
         mp.begin[i] = blocks;
         mp.count[i] = L.grid;
         mp.variant[i] = L.plane2 ? kMultiPlane2 : multi_variant(L.nt, L.wk, L.xv, L.gpw, L.rowp_inst, L.wc, L.img4);
-        mp.p[i] = L.p;
+        mp.s[i] = L.p.s;
+        mp.first[i] = tensors;
+        for (int j = 0; j < L.nprob; ++j, ++tensors) { mp.X[tensors] = L.p.X[j]; mp.dY[tensors] = L.p.dY[j]; mp.out[tensors] = L.p.out[j]; }
         blocks += (L.grid + 7) / 8 * 8;
         if (L.lds > lds) lds = L.lds;
     }
     mp.begin[q.n] = blocks;
-    q.n = 0;
+    q.n = 0; q.tensors = 0;
     WGRAD_LAUNCH(wgrad_exact_multi, dim3((unsigned)blocks), dim3(kBlock), lds, st, mp);
     return launch_status();
 }

@@ -5,7 +5,7 @@ namespace wgrad {
 
 __global__ __launch_bounds__(kBlock, 2) void wgrad_exact_plane2(const StreamParams p)
 {
-    plane2_body(p, (int)blockIdx.x);
+    plane2_body(p.s, p.X, p.dY, p.out, (int)blockIdx.x);
 }
 
 // Whether the shape is this kernel's (alignment of the tensors is checked at launch).
@@ -19,22 +19,24 @@ bool plane2_takes(const Geometry &g)
 int launch_exact_plane2(const Geometry &g, const Batch &b, hipStream_t st, MultiQueue *mq)
 {
     StreamLaunch L{};
-    StreamParams &p = L.p;
+    StreamShape &p = L.p.s;
     for (int i = 0; i < kMaxBatch; ++i) {
         const int j = i < b.n ? i : 0;
-        p.X[i] = b.X[j]; p.dY[i] = b.dY[j]; p.out[i] = b.dW[j];
+        L.p.X[i] = b.X[j]; L.p.dY[i] = b.dY[j]; L.p.out[i] = b.dW[j];
     }
+    L.nprob = b.n;
     p.g = g;
     const int tiles = (g.K / 16) * (g.C / 16);
     p.per_prob = (tiles + kBlock / 64 - 1) / (kBlock / 64);
     L.plane2 = 1;
     L.grid = p.per_prob * b.n;
     if (mq) {
-        if (mq->n == kMultiMax) {
+        if (mq->n >= tune_int("WGRAD_MULTI_GROUPS", kMultiMax) || mq->tensors + b.n > kMultiTensors) {
             const int rc = multi_flush(*mq, st);
             if (rc != WGRAD_OK) return rc;
         }
         mq->item[mq->n++] = L;
+        mq->tensors += b.n;
         return WGRAD_OK;
     }
     return launch_stream_now(L, st);

@@ -26,7 +26,7 @@ constexpr int kPlane2Prefetch = 4;   // reduction steps (four images each) whose
 
 // p: the tensors, the geometry and per_prob (workgroups per problem) of the launch parameters are used;
 // bid: the workgroup's number among the per_prob * problems of its launch (or of its group in a multi-shape launch).
-__device__ __forceinline__ void plane2_body(const StreamParams &p, int bid)
+__device__ __forceinline__ void plane2_body(const StreamShape &p, const void *const *Xt, const void *const *dYt, float *const *outt, int bid)
 {
     const int lane = threadIdx.x & 63;
     const int prob = bid / p.per_prob;
@@ -35,8 +35,8 @@ __device__ __forceinline__ void plane2_body(const StreamParams &p, int bid)
     if (tile >= tiles) return;                                   // wavefront-uniform; the body has no barrier
     const int k0 = (tile / ctiles) * 16, c0 = (tile % ctiles) * 16;
     const int i16 = lane & 15, kk = lane >> 4;
-    const char *__restrict__ dYb = (const char *)p.dY[prob];
-    const char *__restrict__ Xb = (const char *)p.X[prob];
+    const char *__restrict__ dYb = (const char *)dYt[prob];
+    const char *__restrict__ Xb = (const char *)Xt[prob];
     const int N = p.g.N;
 
     // byte offsets of this lane's pieces in reduction step s: image n = 4s + kk (clamped; its values are then zeroed)
@@ -76,7 +76,7 @@ __device__ __forceinline__ void plane2_body(const StreamParams &p, int bid)
     }
 
     // fold: position p = 2h + w, element e = 2ih + iw contribute to tap (ih - h + 1, iw - w + 1)
-    float *__restrict__ out = p.out[prob];
+    float *__restrict__ out = outt[prob];
     const int c = c0 + i16;
 #pragma unroll
     for (int t = 0; t < 4; ++t) {

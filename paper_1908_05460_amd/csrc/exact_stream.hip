@@ -100,11 +100,12 @@ int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, 
                         MultiQueue *mq)
 {
     StreamLaunch L{};
-    StreamParams &p = L.p;
+    StreamShape &p = L.p.s;
     for (int i = 0; i < kMaxBatch; ++i) {          // unused slots repeat problem 0
         const int j = i < b.n ? i : 0;
-        p.X[i] = b.X[j]; p.dY[i] = b.dY[j]; p.out[i] = out[j];
+        L.p.X[i] = b.X[j]; L.p.dY[i] = b.dY[j]; L.p.out[i] = out[j];
     }
+    L.nprob = b.n;
     p.per_prob = pl.ktiles * pl.ctiles * pl.splits;
     p.g = g;
     p.tap_mode = pl.tap_mode; p.ktiles = pl.ktiles; p.ctiles = pl.ctiles; p.splits = pl.splits;
@@ -141,11 +142,12 @@ int launch_exact_stream(const Geometry &g, const ExactPlan &pl, const Batch &b, 
     p.wc = L.wc;
     // up to three workgroups per CU must fit next to each other for a mixed launch to pay
     if (mq && !g.bf16 && L.lds <= 52 * 1024 && multi_variant(L.nt, L.wk, L.xv, L.gpw, L.rowp_inst, L.wc, L.img4) >= 0) {
-        if (mq->n == kMultiMax) {
+        if (mq->n >= tune_int("WGRAD_MULTI_GROUPS", kMultiMax) || mq->tensors + b.n > kMultiTensors) {
             const int rc = multi_flush(*mq, st);
             if (rc != WGRAD_OK) return rc;
         }
         mq->item[mq->n++] = L;
+        mq->tensors += b.n;
         return WGRAD_OK;
     }
     return launch_stream_now(L, st);

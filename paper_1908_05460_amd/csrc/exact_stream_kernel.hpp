@@ -48,9 +48,9 @@ namespace wgrad {
 #define WGRAD_STEP_PATTERN(NT) do { } while (0)
 #endif
 
-struct StreamParams {
-    const void *X[kMaxBatch], *dY[kMaxBatch];
-    float *out[kMaxBatch];      // per problem: dW when splits == 1, else partials [splits][K][C*R*S]
+// Everything a workgroup needs to know about its group but the tensors: in a launch that carries several groups the
+// tensors of all of them sit in one table, so that nine groups fit the 4 KB of kernel arguments.
+struct StreamShape {
     int per_prob;               // workgroups per problem
     Geometry g;
     int tap_mode, ktiles, ctiles, splits;
@@ -64,6 +64,11 @@ struct StreamParams {
     FastDiv d_wv, d_rows, d_iht, d_rs, d_s, d_seg, d_wo, d_htiles;
     FastDiv d_gpi;              // column-uniform order: groups of 16 positions per image of a tile, (ht / 4) * wc
     int tile_c0[9], tile_toff[9], tile_tap[9];
+};
+struct StreamParams {
+    const void *X[kMaxBatch], *dY[kMaxBatch];
+    float *out[kMaxBatch];      // per problem: dW when splits == 1, else partials [splits][K][C*R*S]
+    StreamShape s;
 };
 
 // Window staging slots (16- or 8-byte row pieces) per thread and tile.
@@ -81,7 +86,7 @@ __host__ __device__ constexpr int stream_xslots(int wk, int gpw)
 __device__ __forceinline__ int stream_chan_off(int c_l, int pp) { return (c_l & 3) * pp + (c_l >> 2) * (4 * pp + 4); }
 
 template <int NT>
-__device__ __forceinline__ void stream_column_of(const StreamParams &p, int coltile, int t, int i16, int c_first,
+__device__ __forceinline__ void stream_column_of(const StreamShape &p, int coltile, int t, int i16, int c_first,
                                                  int &lds_off, int &local_col)
 {
     const Geometry &g = p.g;
@@ -123,7 +128,8 @@ __device__ __forceinline__ void stream_column_of(const StreamParams &p, int colt
 // The body takes the workgroup's number `bid` among the `nblk` workgroups of its launch (or of its
 // share of a launch that carries several shapes) and the dynamic LDS.
 template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP, int WC = 0, bool IMG4 = false>
-__device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, int bid, int nblk)
+__device__ __forceinline__ void stream_body(const StreamShape &p, const void *const *Xt, const void *const *dYt, float *const *outt,
+                                            float *smem, int bid, int nblk)
 {
     static_assert(ROWP == 0 || NT == 9, "immediate tap offsets are for 3x3 filters in tap mode");
     static_assert(!IMG4 || (WC == 1 && GPW % 4 == 0 && WK == 4), "the image-uniform order is for 4x4 planes: four images = four groups, one per output row");
@@ -148,8 +154,8 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
     const int logical_all = xcd_contiguous_id(bid, nblk);
     const int prob = logical_all / p.per_prob;
     const int logical = logical_all - prob * p.per_prob;
-    const char *const Xp = (const char *)p.X[prob];
-    const char *const dYp = (const char *)p.dY[prob];
+    const char *const Xp = (const char *)Xt[prob];
+    const char *const dYp = (const char *)dYt[prob];
     const int coltile = logical % p.ctiles;
     const int ktile = (logical / p.ctiles) % p.ktiles;
     const int split = logical / (p.ctiles * p.ktiles);
@@ -421,7 +427,7 @@ __device__ __forceinline__ void stream_body(const StreamParams &p, float *smem, 
         __syncthreads();
         TRACE(14);
         const int colbase = p.tap_mode ? c_first * RS : coltile * NCB;
-        float *out = p.out[prob] + (long)split * g.K * CRS;
+        float *out = outt[prob] + (long)split * g.K * CRS;
         for (int o = tid; o < (KT / 4) * NCB; o += kBlock) {
             const int rq = o / NCB, lc = o % NCB;
             float4_t sum = *(const float4_t *)(red + (lc * KTP + 4 * rq));
@@ -445,19 +451,22 @@ template <int NT, int WK, bool BF16, int XV, int GPW, int ROWP, int WC = 0, bool
 __global__ __launch_bounds__(kBlock) void wgrad_exact_stream(const StreamParams p)
 {
     extern __shared__ float smem[];
-    stream_body<NT, WK, BF16, XV, GPW, ROWP, WC, IMG4>(p, smem, blockIdx.x, gridDim.x);
+    stream_body<NT, WK, BF16, XV, GPW, ROWP, WC, IMG4>(p.s, p.X, p.dY, p.out, smem, blockIdx.x, gridDim.x);
 }
 
 // A prepared launch of the streaming kernel, and a queue of them for a multi-shape launch.
-constexpr int kMultiMax = 6;        // groups per multi-shape launch (their parameters are kernel arguments)
+constexpr int kMultiMax = 9;        // groups per multi-shape launch (their parameters are kernel arguments)
+constexpr int kMultiTensors = 24;   // layers per multi-shape launch (their tensors are one table in the kernel arguments)
 struct StreamLaunch {
     StreamParams p;
     int nt, wk, xv, gpw, rowp_inst, wc, img4, grid;
     int plane2;                 // the 2x2-plane matrix-product form (exact_plane2_kernel.hpp): only the tensors, g and per_prob of p are set
+    int nprob;                  // problems (layers) of the group
     size_t lds;
 };
 struct MultiQueue {
     int n = 0;
+    int tensors = 0;            // problems of the queued groups
     StreamLaunch item[kMultiMax];
 };
 int multi_variant(int nt, int wk, int xv, int gpw, int rowp, int wc, int img4);     // -1: not among the shapes a multi launch mixes
@@ -502,14 +511,14 @@ static void stream_pick(const StreamParams &p, int nt, int xv, int gpw, int rowp
 {
     if (nt == 9) {
         if constexpr (WK == 4 && !BF16) {
-            if (p.wc == 1 && p.img4 && rowp == 6 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 6, 1, true>(p, grid, lds, st); return; }
-            if (p.wc == 1 && rowp == 12 && xv == 4 && gpw == 4) { stream_inst_wc<4, 4, 12, 1>(p, grid, lds, st); return; }
-            if (p.wc == 2 && rowp == 12 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 12, 2>(p, grid, lds, st); return; }
-            if (p.wc == 4 && rowp == 20 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 20, 4>(p, grid, lds, st); return; }
-            if (p.wc == 8 && rowp == 36 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 36, 8>(p, grid, lds, st); return; }
+            if (p.s.wc == 1 && p.s.img4 && rowp == 6 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 6, 1, true>(p, grid, lds, st); return; }
+            if (p.s.wc == 1 && rowp == 12 && xv == 4 && gpw == 4) { stream_inst_wc<4, 4, 12, 1>(p, grid, lds, st); return; }
+            if (p.s.wc == 2 && rowp == 12 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 12, 2>(p, grid, lds, st); return; }
+            if (p.s.wc == 4 && rowp == 20 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 20, 4>(p, grid, lds, st); return; }
+            if (p.s.wc == 8 && rowp == 36 && xv == 4 && gpw == 8) { stream_inst_wc<4, 8, 36, 8>(p, grid, lds, st); return; }
         }
         if constexpr (WK == 2 && !BF16) {
-            if (p.wc == 4 && rowp == 20 && xv == 4 && gpw == 8) { stream_inst_wc<2, 8, 20, 4>(p, grid, lds, st); return; }
+            if (p.s.wc == 4 && rowp == 20 && xv == 4 && gpw == 8) { stream_inst_wc<2, 8, 20, 4>(p, grid, lds, st); return; }
         }
         if (rowp == 4 && xv == 2) stream_inst<9, WK, BF16, 2, 4>(p, gpw, grid, lds, st);
         else if (rowp == 12 && xv == 4) stream_inst<9, WK, BF16, 4, 12>(p, gpw, grid, lds, st);

@@ -6,7 +6,7 @@ namespace wgrad {
 
 void stream_launch_w1(const StreamParams &p, int nt, int xv, int gpw, int rowp, int grid, size_t lds, hipStream_t st)
 {
-    if (p.g.bf16) stream_pick<1, true>(p, nt, xv, gpw, rowp, grid, lds, st);
+    if (p.s.g.bf16) stream_pick<1, true>(p, nt, xv, gpw, rowp, grid, lds, st);
     else stream_pick<1, false>(p, nt, xv, gpw, rowp, grid, lds, st);
 }
 
