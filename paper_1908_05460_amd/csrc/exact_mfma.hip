@@ -627,7 +627,7 @@ int launch_exact(const Geometry &g, const ExactPlan &plan, const Batch &b, void 
                  MultiQueue *mq, int mq_blocks, Bf16Queue *bq)
 {
     if (plan.plane2 && batch_aligned(g, b, 4, 4)) return launch_exact_plane2(g, b, st, mq);   // no split, no partial sums
-    if (plan.mm16 && planes_bf16_takes(g) && batch_aligned(g, b, 8, 8)) return launch_exact_bf16_planes(g, b, st);   // likewise
+    if (planes_bf16_takes(g) && batch_aligned(g, b, 8, 8)) return launch_exact_bf16_planes(g, b, st);   // likewise (bf16, 2x2 and 4x4 planes)
     if ((plan.stream || plan.mm16) && batch_aligned(g, b, plan.xv, plan.mm16 ? 8 : 4)) {
         // one launch for the whole batch; problem i owns the i-th slice of the workspace.  The
         // workgroup target is for the whole launch: a batch splits each reduction less finely.
