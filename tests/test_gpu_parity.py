@@ -356,6 +356,29 @@ def test_schedule_run_equals_the_individual_calls():
         off += ref.numel()
 
 
+def test_exact_schedule_with_more_groups_and_layers_than_one_multi_shape_launch_carries():
+    """Thirty exact fp32 layers of ten shapes that the multi-shape launch takes: more than nine groups and more
+    than 24 layers, so the launch is issued in parts; every layer against its individual call."""
+    import torch
+    shapes = [(16, 32, 16), (16, 16, 32), (32, 16, 32), (64, 8, 64), (3, 32, 64), (64, 32, 64), (64, 16, 128),
+              (64, 4, 64), (32, 2, 32), (16, 2, 16)]                       # (C, H = W, K)
+    N, per_shape = 8, 3
+    descs, Xs, dYs, dWs = [], [], [], []
+    for rep in range(per_shape):
+        for i, (C, HW, K) in enumerate(shapes):
+            d = B.desc(N, C, HW, HW, K, R=3, S=3, pad=1)
+            X, dY = rand_inputs(d, 7000 + 10 * rep + i)
+            descs.append(d); Xs.append(to_gpu(X)); dYs.append(to_gpu(dY))
+            dWs.append(torch.full((K, C, 3, 3), float("nan"), device="cuda"))
+    s = B.Schedule(descs, Xs, dYs, dWs)
+    mask = np.full(len(descs), B.EXACT, np.uint8)
+    s.run(mask, B.alloc_workspace(s.workspace_bytes(mask)))
+    torch.cuda.synchronize()
+    for d, X, dY, dW in zip(descs, Xs, dYs, dWs):
+        ref = B.conv_wgrad_exact(d, X, dY)
+        assert normwise_err(dW.cpu().numpy(), ref.cpu().numpy().astype(np.float64)) <= 1e-5
+
+
 def test_schedule_run_with_more_layers_than_one_table_or_group_holds():
     """70 layers of five shapes and two dtypes, all four methods: groups of identical layers overflow
     (more than 8 per shape and method) and so do the tables of the reduction and of the fills (more
