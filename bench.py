@@ -302,7 +302,7 @@ def run_workload(args, name, machine, steps, warmup, headline):
     mfma_measured = None
     if machine:
         mfma_measured = machine["mfma_f32_16x16x4_tflops"] if dtype == "fp32" else machine["mfma_bf16_16x16x32_tflops"]
-    roofline = {"kernel": "exact phase = wgrad_exact_multi | wgrad_exact_stream | wgrad_exact_bf16_multi (layer groups folded into launches) + combine_table",
+    roofline = {"kernel": "exact phase = wgrad_exact_multi (fp32: all layer groups in one launch) | wgrad_exact_stream | wgrad_exact_bf16_multi + wgrad_exact_bf16_planes (bf16), + combine_table",
                 "bound": "mfma", "achieved": round(achieved_tf, 3), "peak": MFMA_PEAK_TFLOPS[dtype], "unit": "TFLOP/s",
                 "frac": round(achieved_tf / MFMA_PEAK_TFLOPS[dtype], 4),
                 "traffic": traffic["exact_phase_bytes"] if traffic else None, "traffic_source": traffic_src if traffic else None,
@@ -324,7 +324,7 @@ def run_workload(args, name, machine, steps, warmup, headline):
                                        "tflops": round(tot["flops"] / tot["exact_us"] / 1e6, 2)} if single else None}
     achieved_gbs = tot["approx_bytes"] / phase_ms["approx"] / 1e6
     read_measured = machine["hbm_read_gbs"] if machine else None
-    roofline_approx = {"kernel": "approx phase = approx_fused_multi | approx_select + (approx_gather_lds_multi | approx_gather_direct | wgrad_exact_bf16_multi<SPARSE>) | sparsify_small + wgrad_exact_stream, + combine_table",
+    roofline_approx = {"kernel": "approx phase = approx_fused_multi | approx_select_multi + (approx_gather_lds_multi | approx_gather_direct | wgrad_exact_bf16_multi<SPARSE>) | sparsify_small + wgrad_exact_plane2, + combine_table",
                        "bound": "hbm", "achieved": round(achieved_gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                        "frac": round(achieved_gbs / HBM_PEAK_GBS, 4),
                        "traffic": traffic["approx_phase_bytes"] if traffic else None, "traffic_source": traffic_src if traffic else None,
