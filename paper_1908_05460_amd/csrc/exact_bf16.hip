@@ -25,7 +25,9 @@ bool plan_exact_bf16(const Geometry &g, ExactPlan &pl)
     if (!g.bf16 || g.R != 3 || g.S != 3 || g.sh != 1 || g.sw != 1 || g.ph != 1 || g.pw != 1) return false;
     const int L = g.Ho * g.Wo;
     const bool p4 = g.H == 2 && g.W == 2;               // 2x2 planes have a staging path of their own
-    if (g.C % 16 || g.K % kBf16KT || (!p4 && (g.W % 4 || L % 8))) return false;
+    // (any number of input channels: a last tile of fewer than 16 multiplies zeros for the rest -- still a third of the
+    //  fp32 matrix core's time on the three channels of a first layer)
+    if ((g.C % 16 && !tune_int("WGRAD_BF16_ANY_C", 1)) || g.K % kBf16KT || (!p4 && (g.W % 4 || L % 8))) return false;
     const int iwt = g.Wo + 2;
     const int rowp = p4 ? 4 : (iwt <= 8 ? 8 : (iwt <= 12 ? 12 : (iwt <= 20 ? 20 : (iwt <= 36 ? 36 : 0))));
     if (!rowp) return false;
@@ -51,7 +53,7 @@ bool plan_exact_bf16(const Geometry &g, ExactPlan &pl)
         if ((long)nti * g.K * L * 2 >= (1l << 31) || (long)nti * g.C * g.H * g.W * 2 >= (1l << 31)) continue;
         pl.mm16 = 1; pl.stream = 0; pl.gpw = gpw; pl.xv = xv;
         pl.nt = 9; pl.wk = 1; pl.tap_mode = 1;
-        pl.ktiles = g.K / kBf16KT; pl.ctiles = g.C / 16; pl.ctch = 16;
+        pl.ktiles = g.K / kBf16KT; pl.ctiles = (g.C + 15) / 16; pl.ctch = 16;
         pl.nti = nti; pl.ht = ht; pl.q = q; pl.qpad = qt; pl.qp = 0;
         pl.iht = iht; pl.iwt = iwt; pl.pp = ppw; pl.xbuf = buf_words; pl.rowp = rowp;
         pl.lds_bytes = lds;

@@ -161,7 +161,7 @@ __device__ __forceinline__ void bf16_body(const Bf16Params &p, float *smem, int 
             x_pack[u] = -1; x_src[u] = 0;
             if (P4) {
                 // piece = the plane of (image e / 16, channel e % 16); its window is 4 rows of 4: 8 words
-                if (e < x_total) {
+                if (e < x_total && c_first + (e & 15) < g.C) {       // (channels beyond C: the window stays zero)
                     const int n_l = e >> 4, c_l = e & 15;
                     x_pack[u] = bf16_chan_off(c_l, p.ppw) + n_l * 8 + 2;
                     x_src[u] = ((n_l * g.C + c_l) * 4) * 2;
@@ -171,9 +171,11 @@ __device__ __forceinline__ void bf16_body(const Bf16Params &p, float *smem, int 
                 p.d_wv.divmod(e, row, jv);
                 p.d_rows.divmod(row, c_l, rem);
                 p.d_iht.divmod(rem, n_l, ih_l);
-                x_pack[u] = (int)(bf16_chan_off(c_l, p.ppw) + ((rem * ROWP + jv * XV) >> 1)) | (int)(ih_l << 20)
-                            | (jv == 0 ? 1 << 28 : 0) | (jv + 1 == p.d_wv.d ? 1 << 29 : 0);
-                x_src[u] = ((n_l * g.C + c_l) * (g.H * g.W) + jv * XV) * 2;
+                if (c_first + (int)c_l < g.C) {                      // (channels beyond C: the window stays zero)
+                    x_pack[u] = (int)(bf16_chan_off(c_l, p.ppw) + ((rem * ROWP + jv * XV) >> 1)) | (int)(ih_l << 20)
+                                | (jv == 0 ? 1 << 28 : 0) | (jv + 1 == p.d_wv.d ? 1 << 29 : 0);
+                    x_src[u] = ((n_l * g.C + c_l) * (g.H * g.W) + jv * XV) * 2;
+                }
             }
         }
     }
