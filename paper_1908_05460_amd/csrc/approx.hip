@@ -1783,10 +1783,11 @@ int launch_approx(const Geometry &g, const ApproxPlan &plan, const Batch &b, flo
     }
     bool aligned16 = true;
     for (int i = 0; i < b.n; ++i) aligned16 = aligned16 && ((uintptr_t)b.X[i] % 16) == 0;
-    if (pl.mm && planes_bf16_takes(g) && aligned16 && (!bq || tune_int("WGRAD_BF16_PLANES_APPROX_SHARED", 0))) {
-        // 2x2 and 4x4 planes, single calls: the position-major kernel, its A operand built from the selections; it
-        // writes dW itself.  (In a schedule run the selections and the sparse-operand launches of all layers share
-        // two launches, which measured faster than this kernel with a selection and a launch per group.)
+    if (pl.mm && planes_bf16_takes(g) && aligned16 && (!bq || g.H <= tune_int("WGRAD_BF16_PLANES_APPROX_SHARED_HW", 2))) {
+        // 2x2 planes, and 4x4 planes in single calls: the position-major kernel, its A operand built from the
+        // selections; it writes dW itself.  (In a schedule run the selections and the sparse-operand launches of the
+        // layers on 4x4 planes share launches with the other layers', which measured faster than this kernel with a
+        // selection and a launch per group.)
         rc = launch_select_impl(g, ab, b.n, idx_out, sum_out, st, nullptr);
         if (rc != WGRAD_OK) return rc;
         SparseA sp{};
