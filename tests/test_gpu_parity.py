@@ -108,6 +108,22 @@ def test_exact_orders_that_leave_out_padding_taps(t):
     assert normwise_err(dWs[1].cpu().numpy(), oracle.wgrad_exact(oracle_shape(d2), X2, dY2)) <= TOL["fp32"]
 
 
+# bf16 matrix-core kernel with a last tile of fewer than sixteen input channels (the missing ones stay zero in LDS)
+RAGGED_C = [(4, 3, 32, 32, 64), (6, 20, 16, 16, 64), (8, 35, 8, 8, 128), (16, 17, 4, 4, 64), (16, 40, 2, 2, 64), (3, 1, 16, 16, 64)]
+
+
+@pytest.mark.parametrize("t", RAGGED_C)
+def test_bf16_matrix_core_kernel_with_a_ragged_channel_tile(t):
+    N, C, H, W, K = t
+    d = B.desc(N, C, H, W, K, R=3, S=3, pad=1, dtype=B.BF16)
+    X, dY = rand_inputs(d, 8800 + C, "bf16")
+    g = oracle_shape(d)
+    got = B.conv_wgrad_exact(d, to_gpu(X), to_gpu(dY)).cpu().numpy()
+    assert normwise_err(got, oracle.wgrad_exact(g, X, dY)) <= TOL["bf16"]
+    got = B.conv_wgrad_approx(d, to_gpu(X), to_gpu(dY)).cpu().numpy()
+    assert normwise_err(got, oracle.wgrad_approx(g, X, dY)[0]) <= TOL["bf16"]
+
+
 def test_strided_input_whose_planes_exceed_the_fused_offset_field():
     """70 channels of 512x512 under stride 16: maps of 1024 positions and 70 entries per output channel, the
     shape class of the fused form, but tap offsets inside one image need more than 24 bits."""
